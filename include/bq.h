@@ -1,0 +1,135 @@
+/*
+ * bq.h — C ABI of the MI355X (gfx950) butterfly-transform + low-bit quantisation library.
+ *
+ * The library implements the data-parallel hot path of ButterflyQuant (arXiv 2509.09679):
+ * applying the learnable orthogonal butterfly transform B(theta) to batches of activation rows,
+ * its transpose, the fused transform + symmetric INT4/INT2 quantisation, and the backward pass
+ * (dx and dtheta summed over rows) used for calibration.
+ *
+ * The transform (paper, section "Structure and Parameterization"): for n = 2^k,
+ *     B(theta) = B_k ... B_2 B_1,
+ * where layer i consists of n/2 Givens rotations G(t) = [[cos t, -sin t], [sin t, cos t]] acting on
+ * the index pairs (a, a + 2^(i-1)).  Layer 1 (stride 1) is applied to the input first, as in the
+ * data-flow diagram of the appendix "The Butterfly Pattern Visualization"; the j-th angle of layer i
+ * belongs to the j-th pair in increasing order of a, which reproduces the 8x8 layer matrices printed
+ * in the appendix "Concrete Example: Butterfly Matrix Structure for n=8".
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless stated otherwise.  The
+ *     library never allocates, frees or synchronises; every call only enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - The descriptor structs (bq_rows, bq_quant) are HOST pointers, read during the call.
+ *   - theta / dtheta: float32, layout [heads][k][n/2] (layer-major, pair index j as above).
+ *   - A row consists of `heads` independent blocks of n contiguous elements; block h is transformed
+ *     with theta[h] (a block-diagonal transform; heads = 1 is the plain case).
+ *   - Errors are reported by return code only; on any code other than BQ_OK nothing was launched.
+ *     bq_last_error() returns a thread-local text for the last failing call of the calling thread.
+ *   - rows == 0 is valid: BQ_OK, nothing is launched.
+ */
+#ifndef BQ_H
+#define BQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BQ_OK = 0,
+    BQ_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    BQ_ERR_SHAPE = 2,       /* n not a power of two in [2, 16384], heads < 1, rows < 0, ld too small,
+                               group does not divide n, ...                                 */
+    BQ_ERR_DTYPE = 3,       /* unknown element / scale type                                 */
+    BQ_ERR_ALIGN = 4,       /* pointer or leading dimension not aligned as documented       */
+    BQ_ERR_WORKSPACE = 5,   /* plan or workspace buffer smaller than the size query returns */
+    BQ_ERR_UNSUPPORTED = 6, /* valid in principle but not implemented (e.g. bits = 3)       */
+    BQ_ERR_HIP = 7          /* a HIP runtime call failed (text in bq_last_error)            */
+} bq_status;
+
+typedef enum { BQ_F32 = 0, BQ_F16 = 1, BQ_BF16 = 2 } bq_dtype;
+
+/* One batch of rows.  Element pointers must be aligned to 16 bytes and ld_* must be multiples of
+ * 16 bytes worth of elements (4 for f32, 8 for f16/bf16) unless heads * n is smaller than that,
+ * in which case natural element alignment suffices. */
+typedef struct {
+    int64_t rows;  /* T >= 0                                                                  */
+    int32_t n;     /* transform size, power of two, 2 <= n <= 16384                           */
+    int32_t heads; /* H >= 1 transforms side by side; logical row width = H * n               */
+    int64_t ld_x;  /* row stride, in elements, of the input operand(s)  (>= H * n)            */
+    int64_t ld_y;  /* row stride, in elements, of the output operand    (>= H * n)            */
+    int32_t dtype; /* bq_dtype of the row operands (inputs and outputs share it)              */
+    int32_t reserved;
+} bq_rows;
+
+/* Quantiser parameters (paper, equation for Quant/Dequant in section "Loss Function"). */
+typedef struct {
+    int32_t bits;        /* 4 or 2                                                            */
+    int32_t group;       /* channels per scale: power of two, 8 <= group <= n, divides n;
+                            group == n gives one scale per row and head                       */
+    int32_t scale_dtype; /* BQ_F32 or BQ_F16                                                  */
+    int32_t reserved;
+} bq_quant;
+
+/* ---- plan: everything derived from theta alone --------------------------------------------- */
+
+/* Size in bytes of the device buffer bq_plan_build fills for (n, heads); 0 if the shape is invalid. */
+size_t bq_plan_bytes(int32_t n, int32_t heads);
+
+/* Derive from theta what the hot calls need (the paper's "pre-computed cos/sin twiddle factors stored
+ * in a lookup table", section "Inference Efficiency" and appendix "Inference FLOP Analysis"; kept in
+ * float32) into `plan`, a caller-owned device buffer of at least bq_plan_bytes(n, heads) bytes,
+ * aligned to 256 bytes.  Asynchronous on `stream`; call it again whenever theta changes.  The plan's
+ * layout is private to the library.  cos/sin are evaluated in double from the float32 angle and
+ * rounded once. */
+bq_status bq_plan_build(const float *theta, int32_t n, int32_t heads, void *plan, size_t plan_bytes,
+                        void *stream);
+
+/* ---- hot path ------------------------------------------------------------------------------ */
+
+/* y = B(theta) x for every row (paper: x' = Bx, equations of "Structure and Parameterization").
+ * x: [rows][ld_x], y: [rows][ld_y], both of rows->dtype; arithmetic in float32, one rounding to the
+ * output type.  y == x (with ld_y == ld_x) is allowed. */
+bq_status bq_butterfly_fwd(const void *x, void *y, const void *plan, const bq_rows *rows, void *stream);
+
+/* x = B(theta)^T y: the layers in reverse order, each transposed ("orthogonality by construction";
+ * computational invariance y = (W B^T)(B x)).  Input y: [rows][ld_x]; output x: [rows][ld_y]. */
+bq_status bq_butterfly_inv(const void *y, void *x, const void *plan, const bq_rows *rows, void *stream);
+
+/* Fused Quant(B(theta) x) (activation side of the reconstruction loss; Quant as in the paper:
+ * q = clip(round(v / s), -2^(b-1), 2^(b-1)-1), s = max|v| / (2^(b-1)-1) per group of `group`
+ * consecutive channels of a rotated row).  The rotated values stay in float32 registers; they are
+ * not rounded to rows->dtype first.  The quantiser is the following sequence of correctly rounded
+ * float32 operations: amax = max|v|; s = amax / qmax; if scale_dtype is BQ_F16, s = half(s) with
+ * round-to-nearest-even, saturating at 65504; inv = (s == 0) ? 0 : 1 / s; q = clip(rint(v * inv)).
+ *   codes : [rows][H*n*bits/8] bytes, dense.  Two's-complement fields, lowest channel in the lowest
+ *           bits (INT4: byte j/2 = (q_j & 15) | (q_{j+1} & 15) << 4; INT2: four channels per byte).
+ *   scales: [rows][H*n/group] of scale_dtype, dense; the stored value is s. */
+bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes, void *scales,
+                                 const bq_quant *quant, const bq_rows *rows, void *stream);
+
+/* Bytes of device scratch bq_butterfly_bwd needs for this batch shape (0 if the shape is invalid). */
+size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows);
+
+/* Backward pass (paper, "Gradient Flow Through Butterfly Layers": dG/dt = [[-sin,-cos],[cos,-sin]]).
+ * Given upstream dy = dL/d(Bx):  dx = B^T dy  ([rows][ld_y], rows->dtype) and
+ * dtheta[h][i][j] = sum over rows of  g_i[b] * x_i[a] - g_i[a] * x_i[b]   (float32, OVERWRITTEN),
+ * where x_i / g_i are the activations / gradients at the output of layer i and (a, b) is the pair of
+ * angle (i, j).  x and dy: [rows][ld_x].  Layer activations are recomputed, not stored.  Partial
+ * sums are kept per workgroup and combined in a fixed order in a second pass: the result does not
+ * depend on scheduling.  workspace: device scratch of at least the queried size, 256-byte aligned;
+ * its contents on entry are ignored.  dx may be NULL to skip it; dtheta may be NULL to skip it. */
+bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
+                           void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream);
+
+/* ---- helpers ------------------------------------------------------------------------------- */
+
+const char *bq_status_string(bq_status s);
+const char *bq_last_error(void); /* thread-local; "" if the last call succeeded */
+int bq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BQ_H */

@@ -1,0 +1,206 @@
+// C ABI of libbq: argument validation and dispatch.  No kernels here.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "bq_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+bq_status fail(bq_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+bq_status ok()
+{
+    g_err[0] = '\0';
+    return BQ_OK;
+}
+
+int itemsize(int dtype) { return dtype == BQ_F32 ? 4 : 2; }
+
+bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+// Validates a bq_rows descriptor and converts it.
+bq_status check_rows(const bq_rows *r, bq::Shape *s, const char *who)
+{
+    if (!r) return fail(BQ_ERR_NULL, "%s: rows descriptor is NULL", who);
+    if (r->dtype != BQ_F32 && r->dtype != BQ_F16 && r->dtype != BQ_BF16)
+        return fail(BQ_ERR_DTYPE, "%s: unknown dtype %d", who, (int)r->dtype);
+    int k = bq::ilog2_exact(r->n);
+    if (k < 0 || r->n > 16384) return fail(BQ_ERR_SHAPE, "%s: n=%d is not a power of two in [2, 16384]", who, r->n);
+    if (r->heads < 1) return fail(BQ_ERR_SHAPE, "%s: heads=%d < 1", who, r->heads);
+    if (r->rows < 0) return fail(BQ_ERR_SHAPE, "%s: rows=%lld < 0", who, (long long)r->rows);
+    int64_t w = (int64_t)r->n * r->heads;
+    if (w > (int64_t)1 << 24) return fail(BQ_ERR_SHAPE, "%s: row width %lld too large", who, (long long)w);
+    if (r->ld_x < w || r->ld_y < w)
+        return fail(BQ_ERR_SHAPE, "%s: leading dimensions (%lld, %lld) smaller than the row width %lld", who,
+                    (long long)r->ld_x, (long long)r->ld_y, (long long)w);
+    if (r->rows > 0 && r->rows > ((int64_t)1 << 40) / w) return fail(BQ_ERR_SHAPE, "%s: batch too large", who);
+    s->rows = r->rows;
+    s->n = r->n;
+    s->heads = r->heads;
+    s->k = k;
+    s->ld_x = r->ld_x;
+    s->ld_y = r->ld_y;
+    s->dtype = r->dtype;
+    return BQ_OK;
+}
+
+bq_status check_plan(const void *plan, const char *who)
+{
+    if (!plan) return fail(BQ_ERR_NULL, "%s: plan is NULL", who);
+    if (misaligned(plan, 256)) return fail(BQ_ERR_ALIGN, "%s: plan must be aligned to 256 bytes", who);
+    return BQ_OK;
+}
+
+bq_status hip_fail(hipError_t e, const char *who)
+{
+    return fail(BQ_ERR_HIP, "%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
+}
+
+bq_status transform(bq::Mode mode, const void *in, void *out, const void *plan, const bq_rows *rows,
+                    void *stream, const char *who)
+{
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (!in || !out) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
+    if ((st = check_plan(plan, who)) != BQ_OK) return st;
+    if (misaligned(in, itemsize(s.dtype)) || misaligned(out, itemsize(s.dtype)))
+        return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
+    if (s.rows == 0) return ok();
+    bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
+    hipError_t e = bq::launch_transform(mode, in, out, pv, s, nullptr, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bq_plan_bytes(int32_t n, int32_t heads)
+{
+    int k = bq::ilog2_exact(n);
+    if (k < 0 || n > 16384 || heads < 1 || (int64_t)n * heads > ((int64_t)1 << 24)) return 0;
+    return bq::plan_layout(n, heads, k).total;
+}
+
+bq_status bq_plan_build(const float *theta, int32_t n, int32_t heads, void *plan, size_t plan_bytes, void *stream)
+{
+    const char *who = "bq_plan_build";
+    size_t need = bq_plan_bytes(n, heads);
+    if (need == 0) return fail(BQ_ERR_SHAPE, "%s: invalid shape n=%d heads=%d", who, n, heads);
+    if (!theta) return fail(BQ_ERR_NULL, "%s: theta is NULL", who);
+    bq_status st = check_plan(plan, who);
+    if (st != BQ_OK) return st;
+    if (misaligned(theta, 4)) return fail(BQ_ERR_ALIGN, "%s: theta not aligned to 4 bytes", who);
+    if (plan_bytes < need)
+        return fail(BQ_ERR_WORKSPACE, "%s: plan buffer has %zu bytes, %zu needed", who, plan_bytes, need);
+    hipError_t e = bq::launch_plan_build(theta, n, heads, bq::ilog2_exact(n), plan, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+bq_status bq_butterfly_fwd(const void *x, void *y, const void *plan, const bq_rows *rows, void *stream)
+{
+    return transform(bq::kFwd, x, y, plan, rows, stream, "bq_butterfly_fwd");
+}
+
+bq_status bq_butterfly_inv(const void *y, void *x, const void *plan, const bq_rows *rows, void *stream)
+{
+    return transform(bq::kInv, y, x, plan, rows, stream, "bq_butterfly_inv");
+}
+
+bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes, void *scales,
+                                 const bq_quant *quant, const bq_rows *rows, void *stream)
+{
+    const char *who = "bq_butterfly_fwd_quant";
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (!quant) return fail(BQ_ERR_NULL, "%s: quant descriptor is NULL", who);
+    if (!x || !codes || !scales) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
+    if ((st = check_plan(plan, who)) != BQ_OK) return st;
+    if (quant->scale_dtype != BQ_F32 && quant->scale_dtype != BQ_F16)
+        return fail(BQ_ERR_DTYPE, "%s: scale_dtype must be BQ_F32 or BQ_F16", who);
+    if (quant->bits != 4 && quant->bits != 2)
+        return fail(BQ_ERR_UNSUPPORTED, "%s: bits=%d (only 4 and 2 are implemented)", who, quant->bits);
+    int g = quant->group;
+    if (g < 8 || g > s.n || (g & (g - 1)) != 0)
+        return fail(BQ_ERR_SHAPE, "%s: group=%d must be a power of two in [8, n]", who, g);
+    if (misaligned(x, itemsize(s.dtype)) || misaligned(scales, quant->scale_dtype == BQ_F32 ? 4 : 2))
+        return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
+    if (s.rows == 0) return ok();
+    bq::QuantArgs q;
+    q.bits = quant->bits;
+    q.group = g;
+    q.scale_f16 = quant->scale_dtype == BQ_F16;
+    q.codes = codes;
+    q.scales = scales;
+    bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
+    hipError_t e = bq::launch_transform(bq::kFwdQuant, x, nullptr, pv, s, &q, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows)
+{
+    bq::Shape s;
+    if (check_rows(rows, &s, "bq_butterfly_bwd_workspace_bytes") != BQ_OK) return 0;
+    g_err[0] = '\0';
+    return bq::bwd_workspace_bytes(s);
+}
+
+bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
+                           void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream)
+{
+    const char *who = "bq_butterfly_bwd";
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (!x || !dy) return fail(BQ_ERR_NULL, "%s: x or dy is NULL", who);
+    if (!dx && !dtheta) return fail(BQ_ERR_NULL, "%s: both outputs are NULL", who);
+    if ((st = check_plan(plan, who)) != BQ_OK) return st;
+    if (misaligned(x, itemsize(s.dtype)) || misaligned(dy, itemsize(s.dtype)) ||
+        (dx && misaligned(dx, itemsize(s.dtype))) || (dtheta && misaligned(dtheta, 4)))
+        return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
+    size_t need = bq::bwd_workspace_bytes(s);
+    if (!workspace) return fail(BQ_ERR_NULL, "%s: workspace is NULL", who);
+    if (misaligned(workspace, 256)) return fail(BQ_ERR_ALIGN, "%s: workspace must be aligned to 256 bytes", who);
+    if (workspace_bytes < need)
+        return fail(BQ_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", who, workspace_bytes, need);
+    bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
+    hipError_t e = bq::launch_bwd(x, dy, pv, dx, dtheta, workspace, s, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+const char *bq_status_string(bq_status s)
+{
+    switch (s) {
+        case BQ_OK: return "BQ_OK";
+        case BQ_ERR_NULL: return "BQ_ERR_NULL";
+        case BQ_ERR_SHAPE: return "BQ_ERR_SHAPE";
+        case BQ_ERR_DTYPE: return "BQ_ERR_DTYPE";
+        case BQ_ERR_ALIGN: return "BQ_ERR_ALIGN";
+        case BQ_ERR_WORKSPACE: return "BQ_ERR_WORKSPACE";
+        case BQ_ERR_UNSUPPORTED: return "BQ_ERR_UNSUPPORTED";
+        case BQ_ERR_HIP: return "BQ_ERR_HIP";
+    }
+    return "BQ_ERR_?";
+}
+
+const char *bq_last_error(void) { return g_err; }
+
+int bq_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Device helpers: element conversion and the float32 quantiser steps.
+#pragma once
+
+#include "bq_internal.h"
+
+namespace bq {
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(__half v) { return __half2float(v); }
+__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+template <typename T>
+__device__ __forceinline__ T from_float(float v);
+template <>
+__device__ __forceinline__ float from_float<float>(float v)
+{
+    return v;
+}
+template <>
+__device__ __forceinline__ __half from_float<__half>(float v)
+{
+    return __float2half_rn(v);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float v)
+{
+    bf16_t r;
+    r.bits = f32_to_bf16_bits(v);
+    return r;
+}
+
+// Scale of one quantisation group from its abs-max; every step is one correctly rounded float32
+// operation (the contract stated in bq.h).  Returns the stored scale; *inv receives 1/s (0 if s == 0).
+__device__ __forceinline__ float group_scale(float amax, float qmax, bool scale_f16, float *inv)
+{
+    float s = amax / qmax;
+    if (scale_f16) {
+        s = fminf(s, 65504.0f);
+        s = __half2float(__float2half_rn(s));
+    }
+    *inv = (s == 0.0f) ? 0.0f : 1.0f / s;
+    return s;
+}
+
+__device__ __forceinline__ int quant_code(float v, float inv, float qmin, float qmax)
+{
+    float q = rintf(v * inv);
+    q = fminf(fmaxf(q, qmin), qmax);
+    return (int)q;
+}
+
+}  // namespace bq

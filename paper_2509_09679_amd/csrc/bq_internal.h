@@ -1,0 +1,129 @@
+// Internal declarations shared by the translation units of libbq (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bq.h"
+
+namespace bq {
+
+// ---------------------------------------------------------------------------------------------
+// Plan: everything derived from theta.  Device memory, laid out as
+//   [PlanHeader (256 B)]
+//   [cs      : float2 (cos, sin)  [heads][k][n/2]]            plain twiddles, pair order
+//   [fg_fwd  : float  [heads][k][n]]   scale-deferred ("fast Givens") forward coefficients
+//   [fd_fwd  : float  [heads][n]]      forward output scales
+//   [fg_inv  : float  [heads][k][n]]   the same for the transposed cascade
+//   [fd_inv  : float  [heads][n]]
+//   [dwork   : double [heads][n]]      scratch of the plan build
+//
+// Scale-deferred form.  A rotation  ya = c xa - s xb, yb = s xa + c xb  with t = s / c is
+//   ya = c (xa - t xb),  yb = c (xb + t xa).
+// Carrying every element as x = D * u with a per-element scale D that depends on theta only,
+// one layer becomes  u[e] += coef[e] * u[partner(e)]  (one FMA per element) with
+//   coef[a] = -t * D[b] / D[a],  coef[b] = +t * D[a] / D[b],  D'[e] = c * D[e],
+// and the output is y[e] = D_k[e] * u_k[e].  coef and D_k are evaluated in double at plan build and
+// rounded once to float.  If any |log2 |D|| or |log2 |coef|| leaves a safe range (a cosine very
+// close to zero), the header's fast_ok flag is cleared and kernels use (cos, sin) instead.
+// ---------------------------------------------------------------------------------------------
+
+constexpr uint32_t kPlanMagic = 0x42515031u;  // "BQP1"
+
+struct PlanHeader {
+    uint32_t magic;
+    int32_t n, heads, k;
+    int32_t fast_bad_fwd;  // != 0: forward scale-deferred tables unusable
+    int32_t fast_bad_inv;  // != 0: inverse scale-deferred tables unusable
+    int32_t pad[58];
+};
+static_assert(sizeof(PlanHeader) == 256, "header is 256 bytes");
+
+struct PlanLayout {
+    size_t cs, fg_fwd, fd_fwd, fg_inv, fd_inv, dwork, total;
+};
+
+inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+inline PlanLayout plan_layout(int n, int heads, int k)
+{
+    PlanLayout L;
+    size_t H = (size_t)heads, N = (size_t)n, K = (size_t)k;
+    size_t off = sizeof(PlanHeader);
+    L.cs = off;      off = align256(off + H * K * (N / 2) * sizeof(float2));
+    L.fg_fwd = off;  off = align256(off + H * K * N * sizeof(float));
+    L.fd_fwd = off;  off = align256(off + H * N * sizeof(float));
+    L.fg_inv = off;  off = align256(off + H * K * N * sizeof(float));
+    L.fd_inv = off;  off = align256(off + H * N * sizeof(float));
+    L.dwork = off;   off = align256(off + H * N * sizeof(double));
+    L.total = off;
+    return L;
+}
+
+inline int ilog2_exact(int n)
+{
+    if (n < 2) return -1;
+    int k = 0;
+    while ((1 << k) < n) ++k;
+    return ((1 << k) == n) ? k : -1;
+}
+
+struct PlanView {  // device pointers into a plan
+    const PlanHeader *hdr;
+    const float2 *cs;
+    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv;
+};
+
+inline PlanView plan_view(const void *plan, int n, int heads, int k)
+{
+    PlanLayout L = plan_layout(n, heads, k);
+    const char *p = (const char *)plan;
+    PlanView v;
+    v.hdr = (const PlanHeader *)p;
+    v.cs = (const float2 *)(p + L.cs);
+    v.fg_fwd = (const float *)(p + L.fg_fwd);
+    v.fd_fwd = (const float *)(p + L.fd_fwd);
+    v.fg_inv = (const float *)(p + L.fg_inv);
+    v.fd_inv = (const float *)(p + L.fd_inv);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Shapes as the launchers see them (already validated)
+// ---------------------------------------------------------------------------------------------
+struct Shape {
+    int64_t rows;
+    int n, heads, k;
+    int64_t ld_x, ld_y;
+    int dtype;
+};
+
+struct QuantArgs {
+    int bits, group, scale_f16;
+    uint8_t *codes;
+    void *scales;
+};
+
+enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2 };
+
+// generic (any n) kernels: bq_generic.hip
+hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
+                          const QuantArgs *q, hipStream_t stream);
+size_t bwd_workspace_bytes_generic(const Shape &s);
+hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
+                              void *ws, const Shape &s, hipStream_t stream);
+
+// dispatch between specialised and generic kernels: bq_dispatch.hip
+hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
+                            const QuantArgs *q, hipStream_t stream);
+size_t bwd_workspace_bytes(const Shape &s);
+hipError_t launch_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
+                      const Shape &s, hipStream_t stream);
+
+// plan build: bq_plan.hip
+hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *plan, hipStream_t stream);
+
+}  // namespace bq

@@ -1,0 +1,95 @@
+// Plan build: cos/sin twiddles and the scale-deferred coefficient tables, all derived from theta.
+// (Paper: "pre-computed cos/sin twiddle factors stored in a lookup table", section "Inference
+// Efficiency"; kept in float32 here, evaluated in double and rounded once.)
+#include "bq_internal.h"
+
+namespace bq {
+
+__global__ void plan_cs_kernel(const float *__restrict__ theta, float2 *__restrict__ cs, size_t count,
+                               PlanHeader *hdr, int n, int heads, int k)
+{
+    size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q == 0) {
+        hdr->magic = kPlanMagic;
+        hdr->n = n;
+        hdr->heads = heads;
+        hdr->k = k;
+        hdr->fast_bad_fwd = 0;
+        hdr->fast_bad_inv = 0;
+    }
+    if (q < count) {
+        double t = (double)theta[q];
+        cs[q] = make_float2((float)cos(t), (float)sin(t));
+    }
+}
+
+// One workgroup per head.  D (double, one per element) lives in dwork; layers are processed in
+// cascade order with workgroup barriers between them.
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanMaxPerThread = 16;  // n <= 16384
+
+__global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(const float *__restrict__ theta, int n, int k,
+                                                                  int inverse, float *__restrict__ fg,
+                                                                  float *__restrict__ fd, double *__restrict__ dwork,
+                                                                  int *bad_flag)
+{
+    const int head = blockIdx.x;
+    const int tid = threadIdx.x;
+    double *D = dwork + (size_t)head * n;
+    const float *th = theta + (size_t)head * k * (n / 2);
+    float *fgh = fg + (size_t)head * k * n;
+    for (int e = tid; e < n; e += kPlanThreads) D[e] = 1.0;
+    __syncthreads();
+    int bad = 0;
+    const double lo_d = 0x1p-60, hi_d = 0x1p60, lo_c = 0x1p-100, hi_c = 0x1p100;
+    for (int step = 0; step < k; ++step) {
+        const int i = inverse ? (k - step) : (step + 1);
+        const int h = 1 << (i - 1);
+        double newD[kPlanMaxPerThread];
+        int j = 0;
+        for (int e = tid; e < n; e += kPlanThreads, ++j) {
+            const int a = e & ~h;
+            const int p = ((a >> i) << (i - 1)) | (a & (h - 1));
+            const double t = (double)th[(size_t)(i - 1) * (n / 2) + p];
+            const double c = cos(t), s = sin(t);
+            double tt = s / c;
+            if (inverse) tt = -tt;
+            const double Dself = D[e], Dpart = D[e ^ h];
+            // lower element: u_a -= t (D_b / D_a) u_b ; upper element: u_b += t (D_a / D_b) u_a
+            double coef = tt * Dpart / Dself;
+            if (!(e & h)) coef = -coef;
+            const double nd = c * Dself;
+            newD[j] = nd;
+            fgh[(size_t)(i - 1) * n + e] = (float)coef;
+            const double ac = fabs(coef), ad = fabs(nd);
+            if (!(ad > lo_d && ad < hi_d)) bad = 1;
+            if (!(ac == 0.0 || (ac > lo_c && ac < hi_c))) bad = 1;
+        }
+        __syncthreads();
+        j = 0;
+        for (int e = tid; e < n; e += kPlanThreads, ++j) D[e] = newD[j];
+        __syncthreads();
+    }
+    for (int e = tid; e < n; e += kPlanThreads) fd[(size_t)head * n + e] = (float)D[e];
+    if (bad) atomicOr(bad_flag, 1);
+}
+
+hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *plan, hipStream_t stream)
+{
+    PlanLayout L = plan_layout(n, heads, k);
+    char *p = (char *)plan;
+    PlanHeader *hdr = (PlanHeader *)p;
+    size_t count = (size_t)heads * k * (n / 2);
+    unsigned blocks = (unsigned)((count + 255) / 256);
+    hipLaunchKernelGGL(plan_cs_kernel, dim3(blocks), dim3(256), 0, stream, theta, (float2 *)(p + L.cs), count,
+                       hdr, n, heads, k);
+    hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 0,
+                       (float *)(p + L.fg_fwd), (float *)(p + L.fd_fwd), (double *)(p + L.dwork),
+                       &hdr->fast_bad_fwd);
+    hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 1,
+                       (float *)(p + L.fg_inv), (float *)(p + L.fd_inv), (double *)(p + L.dwork),
+                       &hdr->fast_bad_inv);
+    return hipGetLastError();
+}
+
+}  // namespace bq

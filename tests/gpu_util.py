@@ -1,0 +1,126 @@
+"""Helpers for the GPU parity tests: run the library through its Python binding on numpy storage
+arrays, and compare with oracle results under the tolerances stated in the design doc."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from paper_2509_09679_amd import binding as B
+from paper_2509_09679_amd import synth
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+
+
+def _dev(a, dtype, device="cuda:0"):
+    return synth.storage_to_torch(a, dtype, device)
+
+
+def run_transform(x_store, theta, n, heads, dtype, inverse=False, pad=0, inplace=False):
+    import torch
+
+    rows, w = x_store.shape
+    th = torch.from_numpy(np.ascontiguousarray(theta)).to("cuda:0")
+    plan = B.alloc_plan(th, n, heads)
+    xfull = torch.zeros((rows, w + pad), dtype=synth.torch_dtype(dtype), device="cuda:0")
+    xfull[:, :w] = _dev(x_store, dtype)
+    x = xfull[:, :w]
+    if inplace:
+        y = x
+    else:
+        yfull = torch.full((rows, w + pad), 7.0, dtype=x.dtype, device="cuda:0")
+        y = yfull[:, :w]
+    r = B.make_rows(x, n, heads, y)
+    (B.bq_butterfly_inv if inverse else B.bq_butterfly_fwd)(x, y, plan, r)
+    torch.cuda.synchronize()
+    if pad and not inplace:
+        assert (yfull[:, w:] == 7.0).all(), "kernel wrote into the row padding"
+    return synth.torch_to_storage(y, dtype)
+
+
+def run_fwd_quant(x_store, theta, n, heads, dtype, bits, group, scale_dtype):
+    import torch
+
+    rows, w = x_store.shape
+    th = torch.from_numpy(np.ascontiguousarray(theta)).to("cuda:0")
+    plan = B.alloc_plan(th, n, heads)
+    x = _dev(x_store, dtype)
+    codes, scales = B.alloc_quant_outputs(rows, n, heads, bits, group, scale_dtype, "cuda:0")
+    codes.fill_(0xAA)
+    B.bq_butterfly_fwd_quant(x, plan, codes, scales, B.make_quant(bits, group, scale_dtype), B.make_rows(x, n, heads))
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.float().cpu().numpy()
+
+
+def run_bwd(x_store, dy_store, theta, n, heads, dtype, want_dx=True, want_dtheta=True):
+    import torch
+
+    th = torch.from_numpy(np.ascontiguousarray(theta)).to("cuda:0")
+    plan = B.alloc_plan(th, n, heads)
+    x = _dev(x_store, dtype)
+    dy = _dev(dy_store, dtype)
+    dx = torch.empty_like(x) if want_dx else None
+    dth = torch.full(theta.shape, 123.0, dtype=torch.float32, device="cuda:0") if want_dtheta else None
+    r = B.make_rows(x, n, heads)
+    ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(r)), dtype=torch.uint8, device="cuda:0")
+    ws.fill_(0xFF)  # contents on entry must be ignored
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, r)
+    torch.cuda.synchronize()
+    return (synth.torch_to_storage(dx, dtype) if want_dx else None,
+            dth.cpu().numpy() if want_dtheta else None)
+
+
+def check_rotated(y_store, y_ref, dtype, what="", tol=None):
+    """|d_j| <= tol * max(|ref_j|, rms(ref row)) for every element and |d|_2 <= tol |ref|_2 per row."""
+    tol = TOL[dtype] if tol is None else tol
+    y = synth.to_f64(y_store, dtype)
+    assert np.isfinite(y).all(), f"{what}: non-finite output"
+    d = np.abs(y - y_ref)
+    rms = np.sqrt((y_ref ** 2).mean(axis=1, keepdims=True))
+    bound = tol * np.maximum(np.abs(y_ref), rms)
+    worst = (d / np.maximum(bound, 1e-300)).max()
+    assert worst <= 1.0, f"{what}: element error {worst:.3f} x the bound (tol {tol})"
+    rn = np.linalg.norm(d, axis=1)
+    ref_n = np.linalg.norm(y_ref, axis=1)
+    assert (rn <= tol * ref_n + 1e-300).all(), f"{what}: row-norm error {np.max(rn / np.maximum(ref_n, 1e-300)):.3e}"
+    return float(worst)
+
+
+def check_fused_codes(codes_packed, scales, y_ref, bits, group, scale_dtype, in_dtype, what=""):
+    """Fused path: rotated values come from the GPU's own float32 cascade, so codes may differ from
+    the oracle's where a value sits within the rotation tolerance of a rounding boundary.  Every
+    code must be a valid rounding of y_ref / s_gpu up to that tolerance, the scale must equal the
+    oracle's up to the same tolerance (plus one unit of the scale type), and almost all codes must
+    agree exactly with the oracle's."""
+    qmax = 2 ** (bits - 1) - 1
+    rows, w = y_ref.shape
+    q = oracle.unpack_codes(codes_packed, bits).astype(np.float64)
+    ref_codes, ref_scales = oracle.quantize(y_ref.astype(np.float32), group, bits, scale_dtype)
+    tol_rot = 1e-5 if in_dtype == "f32" else 2e-5  # float32 cascade error, relative to max(|y|, rms)
+    rms = np.sqrt((y_ref ** 2).mean(axis=1, keepdims=True))
+    yg = y_ref.reshape(rows, -1, group)
+    amax = np.abs(yg).max(axis=2)
+    s_gpu = scales.astype(np.float64)
+    s_ref = ref_scales.astype(np.float64)
+    ulp = 2.0 ** -10 if scale_dtype == "f16" else 2.0 ** -22
+    slack = tol_rot * np.maximum(amax, rms) / qmax
+    assert (np.abs(s_gpu - s_ref) <= s_ref * ulp + slack + 1e-30).all(), f"{what}: scales differ"
+    assert np.abs(q).max() <= qmax + (1 if scale_dtype == "f16" else 0)
+    sg = np.repeat(s_gpu, group, axis=1)
+    ok_zero = (sg == 0)
+    t = np.where(ok_zero, 0.0, y_ref / np.where(ok_zero, 1.0, sg))
+    delta = tol_rot * np.maximum(np.abs(y_ref), rms) / np.where(ok_zero, 1.0, sg) + 1e-6 * np.abs(t) + 1e-9
+    tq = np.clip(t, -(qmax + 1), qmax)
+    bad = np.abs(tq - q) > 0.5 + delta
+    assert not bad.any(), f"{what}: {bad.sum()} codes are not a valid rounding"
+    same_scale = np.repeat(s_gpu == s_ref, group, axis=1)
+    agree = (q == ref_codes)[same_scale].mean() if same_scale.any() else 1.0
+    assert agree > 0.999, f"{what}: only {agree:.5f} of codes equal the oracle's"
+    return float(agree)
+
+
+def check_dtheta(dth_gpu, dth_ref, absacc, tol=1e-5, what=""):
+    d = np.abs(dth_gpu.astype(np.float64) - dth_ref)
+    worst = (d / np.maximum(tol * absacc, 1e-300)).max()
+    assert worst <= 1.0, f"{what}: dtheta element error {worst:.3f} x the bound"
+    assert np.linalg.norm(d) <= tol * np.linalg.norm(absacc), f"{what}: dtheta norm error"
+    return float(worst)

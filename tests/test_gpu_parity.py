@@ -1,0 +1,171 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Rotated values within 1e-5 (float32 I/O) / 2e-3 (half-precision I/O), quantiser codes and
+scales bit-exact when the quantiser is fed the oracle's rotated values."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_09679_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+gu = pytest.importorskip("gpu_util")
+
+
+def _ref_fwd(x_store, theta, n, heads, dtype):
+    return oracle.forward(synth.to_f64(x_store, dtype), theta, n, heads)
+
+
+# ---- transform: shape sweep (several tiles, ragged tails, every n) ----------------------------
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384])
+def test_fwd_inv_all_sizes_f32(n):
+    rows = 37 if n <= 1024 else 5
+    x, th, _ = synth.small_case(n, rows, "f32", seed=n)
+    y = gu.run_transform(x, th, n, 1, "f32")
+    gu.check_rotated(y, _ref_fwd(x, th, n, 1, "f32"), "f32", f"fwd n={n}")
+    xi = gu.run_transform(x, th, n, 1, "f32", inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(x, "f32"), th, n), "f32", f"inv n={n}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("n,heads,rows", [(128, 1, 100), (128, 32, 67), (64, 3, 33), (4096, 1, 19),
+                                           (8192, 1, 7), (512, 2, 45)])
+def test_fwd_inv_half_types(dtype, n, heads, rows):
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=7)
+    y = gu.run_transform(x, th, n, heads, dtype)
+    gu.check_rotated(y, _ref_fwd(x, th, n, heads, dtype), dtype, f"fwd {dtype} n={n} H={heads}")
+    xi = gu.run_transform(x, th, n, heads, dtype, inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"inv {dtype} n={n}")
+
+
+@pytest.mark.parametrize("n,heads,dtype", [(128, 1, "f32"), (4096, 1, "f16"), (128, 32, "bf16")])
+def test_padded_rows_and_inplace(n, heads, dtype):
+    x, th, _ = synth.small_case(n, 21, dtype, heads=heads, seed=3)
+    ref = _ref_fwd(x, th, n, heads, dtype)
+    y = gu.run_transform(x, th, n, heads, dtype, pad=24)
+    gu.check_rotated(y, ref, dtype, "padded")
+    y2 = gu.run_transform(x, th, n, heads, dtype, inplace=True)
+    assert np.array_equal(y2, gu.run_transform(x, th, n, heads, dtype))
+
+
+def test_single_row_and_zero_rows():
+    import torch
+    from paper_2509_09679_amd import binding as B
+
+    x, th, _ = synth.small_case(4096, 1, "f16", seed=1)
+    gu.check_rotated(gu.run_transform(x, th, 4096, 1, "f16"), _ref_fwd(x, th, 4096, 1, "f16"), "f16", "T=1")
+    thd = torch.from_numpy(th).cuda()
+    plan = B.alloc_plan(thd, 4096, 1)
+    e = torch.empty((0, 4096), dtype=torch.float16, device="cuda:0")
+    r = B.make_rows(e, 4096, 1)
+    B.bq_butterfly_fwd(e, e, plan, r)  # no launch, no error
+    torch.cuda.synchronize()
+
+
+def test_theta_zero_is_identity_and_roundtrip():
+    n = 4096
+    x, th, _ = synth.small_case(n, 9, "f32", seed=5)
+    y = gu.run_transform(x, np.zeros_like(th), n, 1, "f32")
+    assert np.array_equal(y, x)
+    y = gu.run_transform(x, th, n, 1, "f32")
+    xb = gu.run_transform(y, th, n, 1, "f32", inverse=True)
+    gu.check_rotated(xb, synth.to_f64(x, "f32"), "f32", "inverse o forward", tol=2e-5)
+
+
+def test_hadamard_angles():
+    n = 1024
+    k = 10
+    th = np.full((1, k, n // 2), math.pi / 4, np.float32)
+    x, _, _ = synth.small_case(n, 4, "f32", seed=2)
+    gu.check_rotated(gu.run_transform(x, th, n, 1, "f32"), _ref_fwd(x, th, n, 1, "f32"), "f32", "theta=pi/4")
+
+
+def test_cosines_near_zero_take_the_safe_path():
+    # theta = pi/2 everywhere: cos = -4.4e-8 in float32; scale-deferred tables would overflow
+    for n, dtype in [(4096, "f16"), (128, "f32"), (8192, "bf16")]:
+        k = n.bit_length() - 1
+        th = np.full((1, k, n // 2), np.float32(math.pi / 2), np.float32)
+        th[0, ::2, ::3] = np.float32(-math.pi / 2)
+        x, _, _ = synth.small_case(n, 6, dtype, seed=4)
+        gu.check_rotated(gu.run_transform(x, th, n, 1, dtype), _ref_fwd(x, th, n, 1, dtype), dtype, f"pi/2 n={n}")
+        gu.check_rotated(gu.run_transform(x, th, n, 1, dtype, inverse=True),
+                         oracle.inverse(synth.to_f64(x, dtype), th, n), dtype, f"pi/2 inv n={n}")
+
+
+# ---- quantiser: bit-exact when fed the oracle's rotated values ---------------------------------
+
+@pytest.mark.parametrize("n,heads,bits,group,scale_dtype",
+                         [(128, 1, 4, 128, "f32"), (4096, 1, 4, 128, "f16"), (4096, 1, 2, 128, "f16"),
+                          (128, 32, 4, 128, "f32"), (4096, 1, 4, 4096, "f32"), (256, 2, 2, 8, "f16"),
+                          (4096, 1, 2, 32, "f32"), (1024, 1, 4, 64, "f16")])
+def test_quantiser_bit_exact_on_oracle_rotated_values(n, heads, bits, group, scale_dtype):
+    rows = 29
+    x, th, _ = synth.small_case(n, rows, "f16", heads=heads, seed=11)
+    y32 = _ref_fwd(x, th, n, heads, "f16").astype(np.float32)
+    y32[3, :group] = 0.0                      # an all-zero group
+    y32[4, :group] *= np.float32(1e-7)        # a scale in the binary16 subnormal range
+    y32[5, group:2 * group] *= np.float32(3e4)  # a scale that saturates binary16
+    # theta = 0 and float32 input: the cascade passes the values through exactly
+    codes, scales = gu.run_fwd_quant(y32, np.zeros_like(th), n, heads, "f32", bits, group, scale_dtype)
+    ref_codes, ref_scales = oracle.quantize(y32, group, bits, scale_dtype)
+    assert np.array_equal(scales.view(np.uint32), ref_scales.view(np.uint32))
+    assert np.array_equal(codes, oracle.pack_codes(ref_codes, bits))
+
+
+# ---- fused forward + quantisation on the five workloads ----------------------------------------
+
+@pytest.mark.parametrize("cfg,rows", [(1, None), (2, 1), (2, 8), (2, 64), (3, 300), (4, 200)])
+def test_workload_fused_forward_quant(cfg, rows):
+    w = synth.make_workload(cfg, rows=rows)
+    y_ref = _ref_fwd(w.x, w.theta, w.n, w.heads, w.dtype)
+    codes, scales = gu.run_fwd_quant(w.x, w.theta, w.n, w.heads, w.dtype, w.bits, w.group, w.scale_dtype)
+    gu.check_fused_codes(codes, scales, y_ref, w.bits, w.group, w.scale_dtype, w.dtype, w.name)
+    if cfg == 3:  # the metric kernel is also run with INT4
+        codes, scales = gu.run_fwd_quant(w.x, w.theta, w.n, w.heads, w.dtype, 4, w.group, w.scale_dtype)
+        gu.check_fused_codes(codes, scales, y_ref, 4, w.group, w.scale_dtype, w.dtype, w.name + " int4")
+
+
+@pytest.mark.parametrize("cfg,rows", [(1, None), (3, 300)])
+def test_workload_forward_then_inverse(cfg, rows):
+    w = synth.make_workload(cfg, rows=rows)
+    y = gu.run_transform(w.x, w.theta, w.n, w.heads, w.dtype)
+    gu.check_rotated(y, _ref_fwd(w.x, w.theta, w.n, w.heads, w.dtype), w.dtype, w.name)
+    xi = gu.run_transform(y, w.theta, w.n, w.heads, w.dtype, inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(y, w.dtype), w.theta, w.n, w.heads), w.dtype, w.name + " inv")
+
+
+# ---- backward ----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,heads,rows,dtype", [(8, 1, 5, "f32"), (128, 1, 70, "f32"), (128, 4, 33, "bf16"),
+                                                 (1024, 1, 40, "f16"), (4096, 1, 12, "bf16"),
+                                                 (8192, 1, 9, "bf16"), (16384, 1, 3, "f32")])
+def test_backward_shapes(n, heads, rows, dtype):
+    x, th, dy = synth.small_case(n, rows, dtype, heads=heads, seed=13, with_dy=True, outliers=0)
+    dx, dth = gu.run_bwd(x, dy, th, n, heads, dtype)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n, heads)
+    gu.check_rotated(dx, rdx, dtype, f"dx n={n}")
+    gu.check_dtheta(dth, rdth, ab, what=f"n={n} H={heads} {dtype}")
+
+
+def test_backward_workload5_sample_and_determinism():
+    w = synth.make_workload(5, rows=600)
+    dx, dth = gu.run_bwd(w.x, w.dy, w.theta, w.n, w.heads, w.dtype)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(w.x, w.dtype), synth.to_f64(w.dy, w.dtype), w.theta, w.n)
+    gu.check_rotated(dx, rdx, w.dtype, "c5 dx")
+    gu.check_dtheta(dth, rdth, ab, what="c5")
+    dx2, dth2 = gu.run_bwd(w.x, w.dy, w.theta, w.n, w.heads, w.dtype)
+    assert np.array_equal(dth, dth2) and np.array_equal(dx, dx2)  # no atomics: run-to-run bit equality
+
+
+def test_backward_optional_outputs_and_zero_rows():
+    x, th, dy = synth.small_case(256, 10, "f32", seed=2, with_dy=True)
+    dx, _ = gu.run_bwd(x, dy, th, 256, 1, "f32", want_dtheta=False)
+    gu.check_rotated(dx, oracle.inverse(synth.to_f64(dy, "f32"), th, 256), "f32", "dx only")
+    _, dth = gu.run_bwd(x, dy, th, 256, 1, "f32", want_dx=False)
+    _, rdth, ab = oracle.backward(synth.to_f64(x, "f32"), synth.to_f64(dy, "f32"), th, 256)
+    gu.check_dtheta(dth, rdth, ab)
+    _, dth0 = gu.run_bwd(x[:0], dy[:0], th, 256, 1, "f32", want_dx=False)
+    assert not dth0.any()  # dtheta is overwritten, also by an empty batch
