@@ -98,12 +98,12 @@ def _ptr(t) -> Optional[int]:
 
 def make_rows(x, n: int, heads: int, out=None) -> bq_rows:
     """Descriptor for 2-D row tensors (last dimension contiguous)."""
-    assert x.dim() == 2 and x.stride(1) == 1
+    assert x.dim() == 2 and (x.shape[0] == 0 or x.stride(1) == 1)
     r = bq_rows()
     r.rows, r.n, r.heads = x.shape[0], n, heads
-    r.ld_x = x.stride(0) if x.shape[0] > 1 else max(x.stride(0), n * heads)
+    r.ld_x = x.stride(0) if x.shape[0] > 1 else n * heads
     o = x if out is None else out
-    r.ld_y = o.stride(0) if o.shape[0] > 1 else max(o.stride(0), n * heads)
+    r.ld_y = o.stride(0) if o.shape[0] > 1 else n * heads
     r.dtype = _dtype_code(x)
     return r
 

@@ -72,6 +72,7 @@ bq_status transform(bq::Mode mode, const void *in, void *out, const void *plan, 
     bq::Shape s;
     bq_status st = check_rows(rows, &s, who);
     if (st != BQ_OK) return st;
+    if (s.rows == 0) return ok();  // an empty batch may come with NULL data pointers
     if (!in || !out) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
     if ((st = check_plan(plan, who)) != BQ_OK) return st;
     if (misaligned(in, itemsize(s.dtype)) || misaligned(out, itemsize(s.dtype)))
@@ -128,7 +129,7 @@ bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes
     bq_status st = check_rows(rows, &s, who);
     if (st != BQ_OK) return st;
     if (!quant) return fail(BQ_ERR_NULL, "%s: quant descriptor is NULL", who);
-    if (!x || !codes || !scales) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
+    if (s.rows > 0 && (!x || !codes || !scales)) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
     if ((st = check_plan(plan, who)) != BQ_OK) return st;
     if (quant->scale_dtype != BQ_F32 && quant->scale_dtype != BQ_F16)
         return fail(BQ_ERR_DTYPE, "%s: scale_dtype must be BQ_F32 or BQ_F16", who);
@@ -167,7 +168,7 @@ bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void
     bq::Shape s;
     bq_status st = check_rows(rows, &s, who);
     if (st != BQ_OK) return st;
-    if (!x || !dy) return fail(BQ_ERR_NULL, "%s: x or dy is NULL", who);
+    if (s.rows > 0 && (!x || !dy)) return fail(BQ_ERR_NULL, "%s: x or dy is NULL", who);
     if (!dx && !dtheta) return fail(BQ_ERR_NULL, "%s: both outputs are NULL", who);
     if ((st = check_plan(plan, who)) != BQ_OK) return st;
     if (misaligned(x, itemsize(s.dtype)) || misaligned(dy, itemsize(s.dtype)) ||

@@ -8,7 +8,16 @@ import oracle
 from paper_2509_09679_amd import binding as B
 from paper_2509_09679_amd import synth
 
+# Row-norm tolerance: 1e-5 for float32 I/O, 2e-3 for half-precision I/O.  Element tolerance: the same,
+# except bfloat16 outputs, whose unit roundoff 2^-8 = 3.9e-3 is already above 2e-3: there an element
+# may deviate by one output rounding plus the float32 cascade error.
 TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+ELEM_TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2.0 ** -8 + 1e-4}
+
+
+def round_to_storage(y64, dtype):
+    """Oracle values rounded once to the storage dtype, returned as float64."""
+    return synth.to_f64(synth.cast_storage(y64, dtype), dtype)
 
 
 def _dev(a, dtype, device="cuda:0"):
@@ -71,15 +80,26 @@ def run_bwd(x_store, dy_store, theta, n, heads, dtype, want_dx=True, want_dtheta
 
 def check_rotated(y_store, y_ref, dtype, what="", tol=None):
     """|d_j| <= tol * max(|ref_j|, rms(ref row)) for every element and |d|_2 <= tol |ref|_2 per row."""
+    etol = ELEM_TOL[dtype] if tol is None else tol
     tol = TOL[dtype] if tol is None else tol
     y = synth.to_f64(y_store, dtype)
     assert np.isfinite(y).all(), f"{what}: non-finite output"
     d = np.abs(y - y_ref)
     rms = np.sqrt((y_ref ** 2).mean(axis=1, keepdims=True))
-    bound = tol * np.maximum(np.abs(y_ref), rms)
+    bound = etol * np.maximum(np.abs(y_ref), rms)
+    d_norm = d
+    if dtype != "f32":
+        # half-precision outputs must almost always be THE correct rounding of the oracle value
+        ref_r = round_to_storage(y_ref, dtype)
+        exact = (y == ref_r).mean()
+        assert exact > 0.99, f"{what}: only {exact:.4f} of outputs are the correctly rounded oracle value"
+        if dtype == "bf16":
+            # rounding to bfloat16 alone moves a row by up to ~2.4e-3 of its norm: the row-norm bound
+            # is applied to the distance from the correctly rounded oracle row instead
+            d_norm = np.abs(y - ref_r)
     worst = (d / np.maximum(bound, 1e-300)).max()
     assert worst <= 1.0, f"{what}: element error {worst:.3f} x the bound (tol {tol})"
-    rn = np.linalg.norm(d, axis=1)
+    rn = np.linalg.norm(d_norm, axis=1)
     ref_n = np.linalg.norm(y_ref, axis=1)
     assert (rn <= tol * ref_n + 1e-300).all(), f"{what}: row-norm error {np.max(rn / np.maximum(ref_n, 1e-300)):.3e}"
     return float(worst)

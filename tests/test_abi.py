@@ -102,7 +102,7 @@ def test_quant_validation():
     q = B.make_quant(4, 128, "f16")
     q.scale_dtype = B.BQ_BF16
     assert call(q) == 3
-    assert call(B.make_quant(4, 128, "f16"), codes=None) == 1
+    assert call(B.make_quant(4, 128, "f16"), r=_rows(rows=3), codes=None) == 1
     assert call(B.make_quant(4, 128, "f32"), scales=FAKE + 2) == 4
 
 
