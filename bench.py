@@ -1,0 +1,290 @@
+#!/usr/bin/env python3
+"""Benchmark of the butterfly + quantisation hot path on one MI355X.
+
+A step is one pass of the whole path over the calibration/prefill batch (n = 4096, 262144 rows of
+fp16 activations, resident in HBM): plan build from theta, fused forward + INT2 quantisation
+(group 128, fp16 scales), standalone forward, standalone inverse, and the backward pass (dx, dtheta).
+`value` is rows per second through that whole step.  The `roofline` object describes the fused
+forward + quantisation kernel, the kernel the headline metric is about; `kernels` lists the same
+figures for every kernel of the step, `decode` the latency of the small-batch calls.
+
+Prints one JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+VALU_PEAK_TFLOPS = 157.3       # published fp32 vector peak (counts packed fp32 FMAs)
+
+
+def alg_bytes_per_row(op: str, n: int, heads: int, itemsize: int, bits: int = 0, group: int = 0,
+                      scale_bytes: int = 0) -> int:
+    """Bytes the method itself must move per row (twiddles excluded: read once per workgroup)."""
+    w = n * heads
+    if op in ("fwd", "inv"):
+        return 2 * w * itemsize
+    if op == "fwd_quant":
+        return w * itemsize + w * bits // 8 + (w // group) * scale_bytes
+    if op == "bwd":
+        return 3 * w * itemsize
+    raise ValueError(op)
+
+
+def alg_flops_per_row(op: str, n: int, heads: int) -> int:
+    """3 n log2 n per transform application (paper, table of per-application arithmetic); the
+    backward pass runs three cascades plus 4 flops per pair for dtheta."""
+    k = n.bit_length() - 1
+    one = 3 * n * k * heads
+    if op == "bwd":
+        return 3 * one + 4 * (n // 2) * k * heads
+    return one
+
+
+def time_kernel(fn, iters: int, warmup: int = 2):
+    """Average duration in ms of `fn` (launches on torch's current stream) measured with events on
+    that stream."""
+    import torch
+
+    for _ in range(warmup):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[-1]
+
+
+def cpu_baseline(sample_rows: int):
+    """The oracle, as it is, on the host cores: the same step (forward + INT2 quantisation, forward,
+    inverse, backward) on a bounded sample of the workload."""
+    import numpy as np
+
+    import oracle
+    from paper_2509_09679_amd import synth
+
+    chunk = 4096
+    t_total = 0.0
+    done = 0
+    salt = 0
+    while done < sample_rows:
+        rows = min(chunk, sample_rows - done)
+        w = synth.make_workload(3, rows=rows, salt=salt)
+        dy = np.random.default_rng(salt).standard_normal((rows, w.n))
+        x64 = synth.to_f64(w.x, w.dtype)
+        t0 = time.perf_counter()
+        y = oracle.forward(x64, w.theta, w.n)
+        codes, scales = oracle.quantize(y.astype(np.float32), w.group, w.bits, w.scale_dtype)
+        oracle.pack_codes(codes, w.bits)
+        oracle.forward(x64, w.theta, w.n)
+        oracle.inverse(y, w.theta, w.n)
+        oracle.backward(x64, dy, w.theta, w.n, want_abs=False)
+        t_total += time.perf_counter() - t0
+        done += rows
+        salt += 1
+    return {"value": done / t_total, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{done} rows of the n=4096 fp16 workload, same step (fwd+INT2 quant, fwd, inv, bwd), "
+                      f"{t_total:.1f} s of CPU work"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--rows", type=int, default=262144, help="rows of the batch (default: the full workload)")
+    ap.add_argument("--cpu-rows", type=int, default=32768, help="rows of the oracle's timed sample (0 = skip)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the decode / per-head / n=8192 backward figures")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (rows are independent, so more "
+              "GPUs would each take a slice of the rows; see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2509_09679_amd import binding as B
+    from paper_2509_09679_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.lib()  # fails loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    cfg = 3
+    T = args.rows
+    x, theta_h, dy = synth.device_rows(cfg, T, dev, want_dy=True)
+    wl = synth.make_workload(cfg, rows=1)
+    n, heads, bits, group = wl.n, wl.heads, wl.bits, wl.group
+    theta = torch.from_numpy(theta_h).to(dev)
+    plan = torch.empty(B.bq_plan_bytes(n, heads), dtype=torch.uint8, device=dev)
+    y = torch.empty_like(x)
+    xi = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    dtheta = torch.empty_like(theta)
+    codes, scales = B.alloc_quant_outputs(T, n, heads, bits, group, wl.scale_dtype, dev)
+    rows = B.make_rows(x, n, heads)
+    quant = B.make_quant(bits, group, wl.scale_dtype)
+    ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows)), dtype=torch.uint8, device=dev)
+
+    kernels = {
+        "plan_build": lambda: B.bq_plan_build(theta, n, heads, plan),
+        "fwd_quant": lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, quant, rows),
+        "fwd": lambda: B.bq_butterfly_fwd(x, y, plan, rows),
+        "inv": lambda: B.bq_butterfly_inv(y, xi, plan, rows),
+        "bwd": lambda: B.bq_butterfly_bwd(x, dy, plan, dx, dtheta, ws, rows),
+    }
+    order = ["plan_build", "fwd_quant", "fwd", "inv", "bwd"]
+
+    def step(events=None):
+        for name in order:
+            if events is not None:
+                a = torch.cuda.Event(enable_timing=True)
+                b = torch.cuda.Event(enable_timing=True)
+                a.record()
+                kernels[name]()
+                b.record()
+                events.setdefault(name, []).append((a, b))
+            else:
+                kernels[name]()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    itemsize = 2
+    kinfo = {}
+    for name in order:
+        ts = [a.elapsed_time(b) for a, b in events[name]]
+        avg = sum(ts) / len(ts)
+        rec = {"avg_ms": round(avg, 4)}
+        if name != "plan_build":
+            bpr = alg_bytes_per_row(name, n, heads, itemsize, bits, group, 2)
+            fpr = alg_flops_per_row(name, n, heads)
+            gbs = bpr * T / (avg * 1e-3) / 1e9
+            tf = fpr * T / (avg * 1e-3) / 1e12
+            rec.update({"rows_per_s": T / (avg * 1e-3), "alg_bytes_per_row": bpr, "GBps": round(gbs, 1),
+                        "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "alg_TFLOPps": round(tf, 2),
+                        "valu_frac": round(tf / VALU_PEAK_TFLOPS, 4)})
+        kinfo[name] = rec
+
+    fq = kinfo["fwd_quant"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("fwd_quant_n4096_f16_int2_g128")
+        except Exception:
+            traffic = None
+    roofline = {"kernel": "fused forward + INT2 quantisation, n=4096 fp16, group 128", "bound": "hbm",
+                "achieved": fq["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fq["hbm_frac"],
+                "traffic": traffic, "launch_ms": fq["avg_ms"], "alg_bytes_per_launch": fq["alg_bytes_per_row"] * T}
+
+    extra = {}
+    if not args.no_extra:
+        extra = extra_figures(B, synth, torch, dev)
+
+    out = {
+        "metric": "rows/sec + achieved HBM GB/s (% peak), butterfly fwd+quant n=4096 fp16",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"calibration/prefill shape: n=4096, T={T} rows, fp16 Student-t(3) activations with "
+                               "1% outlier channels x100; step = plan build + fused fwd+INT2 quant (g128, fp16 "
+                               "scales) + fwd + inv + bwd",
+                   "n": n, "rows": T, "io_dtype": "f16", "bits": bits, "group": group},
+        "fwd_quant_rows_per_s": fq["rows_per_s"],
+        "fwd_quant_GBps": fq["GBps"],
+        "fwd_quant_hbm_frac": fq["hbm_frac"],
+        "roofline": roofline,
+        "kernels": kinfo,
+    }
+    out.update(extra)
+    if args.cpu_rows > 0:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_rows)
+    print(json.dumps(out))
+    return 0
+
+
+def extra_figures(B, synth, torch, dev):
+    """Figures for the other workload shapes (not part of the timed step)."""
+    res = {}
+    # decode latency: n=4096 fp16, T in {1, 8, 64}, fused forward + INT4, group 128
+    wl = synth.make_workload(2, rows=64)
+    theta = torch.from_numpy(wl.theta).to(dev)
+    plan = B.alloc_plan(theta, wl.n, 1)
+    xs = synth.storage_to_torch(wl.x, wl.dtype, dev)
+    dec = {}
+    for T in (1, 8, 64):
+        x = xs[:T].contiguous()
+        codes, scales = B.alloc_quant_outputs(T, wl.n, 1, 4, 128, "f16", dev)
+        rows = B.make_rows(x, wl.n, 1)
+        q = B.make_quant(4, 128, "f16")
+        avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows), 200, 20)
+        dec[f"T{T}"] = {"avg_us": round(avg * 1e3, 2), "median_us": round(med * 1e3, 2), "max_us": round(mx * 1e3, 2)}
+    res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream", **dec}
+    # per-head: 32 heads x n=128, T=8192, bf16, rotating over 6 buffers (> 256 MB in total)
+    x4, th4, _ = synth.device_rows(4, 8192, dev)
+    theta4 = torch.from_numpy(th4).to(dev)
+    plan4 = B.alloc_plan(theta4, 128, 32)
+    bufs = [x4] + [x4.clone() for _ in range(5)]
+    codes4, scales4 = B.alloc_quant_outputs(8192, 128, 32, 4, 128, "f32", dev)
+    rows4 = B.make_rows(x4, 128, 32)
+    q4 = B.make_quant(4, 128, "f32")
+    state = {"i": 0}
+
+    def run4():
+        state["i"] = (state["i"] + 1) % len(bufs)
+        B.bq_butterfly_fwd_quant(bufs[state["i"]], plan4, codes4, scales4, q4, rows4)
+
+    avg, med, mx = time_kernel(run4, 30, 6)
+    bpr = alg_bytes_per_row("fwd_quant", 128, 32, 2, 4, 128, 4)
+    res["per_head"] = {"workload": "32 heads x n=128, T=8192, bf16, fused fwd + per-head INT4",
+                       "avg_ms": round(avg, 4), "rows_per_s": 8192 / (avg * 1e-3),
+                       "GBps": round(bpr * 8192 / (avg * 1e-3) / 1e9, 1),
+                       "hbm_frac": round(bpr * 8192 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del bufs, x4
+    # backward at n=8192, T=65536, bf16
+    T5 = 65536
+    x5, th5, dy5 = synth.device_rows(5, T5, dev, want_dy=True)
+    theta5 = torch.from_numpy(th5).to(dev)
+    plan5 = B.alloc_plan(theta5, 8192, 1)
+    dx5 = torch.empty_like(x5)
+    dth5 = torch.empty_like(theta5)
+    rows5 = B.make_rows(x5, 8192, 1)
+    ws5 = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows5)), dtype=torch.uint8, device=dev)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x5, dy5, plan5, dx5, dth5, ws5, rows5), 5, 1)
+    bpr = alg_bytes_per_row("bwd", 8192, 1, 2)
+    fpr = alg_flops_per_row("bwd", 8192, 1)
+    res["bwd_n8192"] = {"workload": "n=8192, T=65536, bf16: dx and dtheta", "avg_ms": round(avg, 4),
+                        "rows_per_s": T5 / (avg * 1e-3), "GBps": round(bpr * T5 / (avg * 1e-3) / 1e9, 1),
+                        "hbm_frac": round(bpr * T5 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                        "alg_TFLOPps": round(fpr * T5 / (avg * 1e-3) / 1e12, 2),
+                        "valu_frac": round(fpr * T5 / (avg * 1e-3) / 1e12 / VALU_PEAK_TFLOPS, 4)}
+    return res
+
+
+if __name__ == "__main__":
+    sys.exit(main())

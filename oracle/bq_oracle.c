@@ -142,7 +142,7 @@ int bq_oracle_inv(const double *y, double *x, const float *theta, long rows, int
  * Butterfly Layers").  With x_0 = x, x_i = B_i x_{i-1}, g_k = dy, g_{i-1} = B_i^T g_i:
  *     dL/dtheta_{i,j} = g_i[a,b] . (dG/dtheta)(theta_{i,j}) . x_{i-1}[a,b],
  *     dG/dtheta = [[-sin, -cos], [cos, -sin]],
- * summed over rows;  dx = g_0.  All layer inputs x_{i-1} are kept (no recomputation).
+ * summed over rows;  dx = g_0.  All layer inputs x_{i-1} of a row are kept (no recomputation).
  * dtheta (double, layout of theta) is overwritten.  absacc, if not NULL, receives for every angle
  * the sum over rows of the absolute values of the four products entering its gradient; tests use it
  * as the scale of the rounding-error bound. */
@@ -157,40 +157,65 @@ int bq_oracle_bwd(const double *x, const double *dy, const float *theta, double 
     size_t m = (size_t)heads * (size_t)k * (size_t)(n / 2);
     memset(dtheta, 0, m * sizeof(double));
     if (absacc) memset(absacc, 0, m * sizeof(double));
-    double *xs = (double *)malloc((size_t)(k + 1) * (size_t)n * sizeof(double));
-    double *g = (double *)malloc((size_t)n * sizeof(double));
-    /* rows are summed in order in double: deterministic */
-    for (long r = 0; r < rows; ++r) {
-        for (int hd = 0; hd < heads; ++hd) {
-            memcpy(xs, x + r * w + (long)hd * n, (size_t)n * sizeof(double));
-            for (int i = 1; i <= k; ++i) {
-                size_t off = ((size_t)hd * k + (size_t)(i - 1)) * (size_t)(n / 2);
-                double *cur = xs + (size_t)i * n;
-                memcpy(cur, xs + (size_t)(i - 1) * n, (size_t)n * sizeof(double));
-                layer_apply(cur, c + off, s + off, n, i);
-            }
-            memcpy(g, dy + r * w + (long)hd * n, (size_t)n * sizeof(double));
-            for (int i = k; i >= 1; --i) {
-                size_t off = ((size_t)hd * k + (size_t)(i - 1)) * (size_t)(n / 2);
-                const double *xin = xs + (size_t)(i - 1) * n;
-                long h = 1L << (i - 1);
-                for (long j = 0; j < n / 2; ++j) {
-                    long a = pair_lo(j, i), b = a + h;
-                    double cc = c[off + j], ss = s[off + j];
-                    double da = -ss * xin[a] - cc * xin[b]; /* row 1 of dG/dtheta times x_{i-1} */
-                    double db = cc * xin[a] - ss * xin[b];  /* row 2 */
-                    dtheta[off + j] += g[a] * da + g[b] * db;
-                    if (absacc)
-                        absacc[off + j] += fabs(g[a] * ss * xin[a]) + fabs(g[a] * cc * xin[b]) +
-                                           fabs(g[b] * cc * xin[a]) + fabs(g[b] * ss * xin[b]);
+    /* Rows are split into contiguous chunks, one per thread; every thread sums its rows in order into
+     * its own accumulator, and the accumulators are added in thread order afterwards: the result is
+     * reproducible for a given thread count. */
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = omp_get_max_threads();
+#endif
+    if (nthreads > rows) nthreads = rows > 0 ? (int)rows : 1;
+    double *acc_all = (double *)calloc((size_t)nthreads * m * (absacc ? 2 : 1), sizeof(double));
+#pragma omp parallel num_threads(nthreads)
+    {
+        int tid = 0;
+#ifdef _OPENMP
+        tid = omp_get_thread_num();
+#endif
+        double *acc = acc_all + (size_t)tid * m * (absacc ? 2 : 1);
+        double *aab = absacc ? acc + m : NULL;
+        double *xs = (double *)malloc((size_t)(k + 1) * (size_t)n * sizeof(double));
+        double *g = (double *)malloc((size_t)n * sizeof(double));
+        long r0 = rows * tid / nthreads, r1 = rows * (tid + 1) / nthreads;
+        for (long r = r0; r < r1; ++r) {
+            for (int hd = 0; hd < heads; ++hd) {
+                memcpy(xs, x + r * w + (long)hd * n, (size_t)n * sizeof(double));
+                for (int i = 1; i <= k; ++i) {
+                    size_t off = ((size_t)hd * k + (size_t)(i - 1)) * (size_t)(n / 2);
+                    double *cur = xs + (size_t)i * n;
+                    memcpy(cur, xs + (size_t)(i - 1) * n, (size_t)n * sizeof(double));
+                    layer_apply(cur, c + off, s + off, n, i);
                 }
-                layer_apply_T(g, c + off, s + off, n, i);
+                memcpy(g, dy + r * w + (long)hd * n, (size_t)n * sizeof(double));
+                for (int i = k; i >= 1; --i) {
+                    size_t off = ((size_t)hd * k + (size_t)(i - 1)) * (size_t)(n / 2);
+                    const double *xin = xs + (size_t)(i - 1) * n;
+                    long h = 1L << (i - 1);
+                    for (long j = 0; j < n / 2; ++j) {
+                        long a = pair_lo(j, i), b = a + h;
+                        double cc = c[off + j], ss = s[off + j];
+                        double da = -ss * xin[a] - cc * xin[b]; /* row 1 of dG/dtheta times x_{i-1} */
+                        double db = cc * xin[a] - ss * xin[b];  /* row 2 */
+                        acc[off + j] += g[a] * da + g[b] * db;
+                        if (aab)
+                            aab[off + j] += fabs(g[a] * ss * xin[a]) + fabs(g[a] * cc * xin[b]) +
+                                            fabs(g[b] * cc * xin[a]) + fabs(g[b] * ss * xin[b]);
+                    }
+                    layer_apply_T(g, c + off, s + off, n, i);
+                }
+                memcpy(dx + r * w + (long)hd * n, g, (size_t)n * sizeof(double));
             }
-            memcpy(dx + r * w + (long)hd * n, g, (size_t)n * sizeof(double));
         }
+        free(xs);
+        free(g);
     }
-    free(xs);
-    free(g);
+    for (int t = 0; t < nthreads; ++t) {
+        const double *acc = acc_all + (size_t)t * m * (absacc ? 2 : 1);
+        for (size_t q = 0; q < m; ++q) dtheta[q] += acc[q];
+        if (absacc)
+            for (size_t q = 0; q < m; ++q) absacc[q] += acc[m + q];
+    }
+    free(acc_all);
     free(c);
     free(s);
     return 0;

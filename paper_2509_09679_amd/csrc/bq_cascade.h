@@ -1,0 +1,177 @@
+// Register/DPP building blocks of the specialised cascade kernels (gfx950, wave64).
+//
+// Every thread carries 8 elements of a transform in registers, in the scale-deferred form described
+// in bq_internal.h: one layer is  u[e] += coef[e] * u[partner(e)], one FMA per element.
+//   * partner in the same thread  -> plain FMAs on register pairs
+//   * partner in another lane of the same 16-lane row -> one v_fmac_f32 with a DPP operand; the
+//     lane exchange costs no extra instruction.  gfx9 DPP offers the lane XOR masks 1, 2
+//     (quad_perm), 7 (row_half_mirror), 8 (row_ror:8) and 15 (row_mirror); the masks {1, 2, 7, 8}
+//     are linearly independent over GF(2), so four butterfly layers fit in a 16-lane row if lane l
+//     holds the chunk  e(l) = l ^ (l & 4 ? 3 : 0)  (then e(l ^ 7) = e(l) ^ 4).
+//
+// The DPP instructions are written as inline assembly because the compiler does not fold a DPP move
+// into an FMA whose accumulator is the permuted register itself.  A VALU write followed by a DPP
+// read of the same VGPR needs two wait states; the compiler does not see inside the assembly, so
+// every block starts with s_nop 1, and inside a block the eight instructions touch eight different
+// registers.
+#pragma once
+
+#include "bq_device.h"
+
+namespace bq {
+
+// chunk held by lane l (only the low four lane bits are permuted)
+__device__ __forceinline__ int lane_chunk(int lane) { return lane ^ ((lane & 4) ? 3 : 0); }
+
+#define BQ_DPP_FMAC8(MOD)                                                                              \
+    asm volatile("s_nop 1\n\t"                                                                        \
+                 "v_fmac_f32_dpp %0, %0, %8 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_fmac_f32_dpp %1, %1, %9 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_fmac_f32_dpp %2, %2, %10 " MOD " row_mask:0xf bank_mask:0xf\n\t"                  \
+                 "v_fmac_f32_dpp %3, %3, %11 " MOD " row_mask:0xf bank_mask:0xf\n\t"                  \
+                 "v_fmac_f32_dpp %4, %4, %12 " MOD " row_mask:0xf bank_mask:0xf\n\t"                  \
+                 "v_fmac_f32_dpp %5, %5, %13 " MOD " row_mask:0xf bank_mask:0xf\n\t"                  \
+                 "v_fmac_f32_dpp %6, %6, %14 " MOD " row_mask:0xf bank_mask:0xf\n\t"                  \
+                 "v_fmac_f32_dpp %7, %7, %15 " MOD " row_mask:0xf bank_mask:0xf"                      \
+                 : "+v"(u[0]), "+v"(u[1]), "+v"(u[2]), "+v"(u[3]), "+v"(u[4]), "+v"(u[5]), "+v"(u[6]),  \
+                   "+v"(u[7])                                                                          \
+                 : "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(c[4]), "v"(c[5]), "v"(c[6]), "v"(c[7]))
+
+// u[r] += c[r] * u[r] of lane (lane ^ mask), for the four supported masks
+__device__ __forceinline__ void dpp_layer_xor1(float (&u)[8], const float (&c)[8]) { BQ_DPP_FMAC8("quad_perm:[1,0,3,2]"); }
+__device__ __forceinline__ void dpp_layer_xor2(float (&u)[8], const float (&c)[8]) { BQ_DPP_FMAC8("quad_perm:[2,3,0,1]"); }
+__device__ __forceinline__ void dpp_layer_xor7(float (&u)[8], const float (&c)[8]) { BQ_DPP_FMAC8("row_half_mirror"); }
+__device__ __forceinline__ void dpp_layer_xor8(float (&u)[8], const float (&c)[8]) { BQ_DPP_FMAC8("row_ror:8"); }
+
+// m = max(m, m of lane ^ mask) over the 16-lane row: after the four steps every lane holds the row max
+__device__ __forceinline__ float row16_max(float m)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"
+                 : "+v"(m));
+    return m;
+}
+
+// max over lane groups of 2, 4 or 8 lanes (subsets of the steps above)
+__device__ __forceinline__ float lanes_max(float m, int lanes)
+{
+    if (lanes >= 2)
+        asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "+v"(m));
+    if (lanes >= 4)
+        asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "+v"(m));
+    if (lanes >= 8)
+        asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf" : "+v"(m));
+    if (lanes >= 16)
+        asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf" : "+v"(m));
+    return m;
+}
+
+// One layer on register pairs: partner of register r is r ^ (1 << J)
+template <int J>
+__device__ __forceinline__ void reg_layer(float (&u)[8], const float (&c)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (!(r & (1 << J))) {
+            const int a = r, b = r | (1 << J);
+            const float ua = u[a], ub = u[b];
+            u[a] = __builtin_fmaf(c[a], ub, ua);
+            u[b] = __builtin_fmaf(c[b], ua, ub);
+        }
+    }
+}
+
+// ---- row I/O: 8 consecutive elements per thread ------------------------------------------------
+struct Raw8 {
+    uint4 lo, hi;  // f16/bf16 use lo only
+};
+
+template <typename T>
+__device__ __forceinline__ Raw8 load8(const T *p)
+{
+    Raw8 r;
+    r.lo = *(const uint4 *)p;
+    if (sizeof(T) == 4) r.hi = *((const uint4 *)p + 1);
+    return r;
+}
+
+__device__ __forceinline__ void unpack8(const Raw8 &r, float (&u)[8], const float *)
+{
+    u[0] = __uint_as_float(r.lo.x); u[1] = __uint_as_float(r.lo.y); u[2] = __uint_as_float(r.lo.z);
+    u[3] = __uint_as_float(r.lo.w); u[4] = __uint_as_float(r.hi.x); u[5] = __uint_as_float(r.hi.y);
+    u[6] = __uint_as_float(r.hi.z); u[7] = __uint_as_float(r.hi.w);
+}
+__device__ __forceinline__ void unpack8(const Raw8 &r, float (&u)[8], const __half *)
+{
+    const uint32_t w[4] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const __half2 h = *(const __half2 *)&w[i];
+        u[2 * i] = __low2float(h);
+        u[2 * i + 1] = __high2float(h);
+    }
+}
+__device__ __forceinline__ void unpack8(const Raw8 &r, float (&u)[8], const bf16_t *)
+{
+    const uint32_t w[4] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        u[2 * i] = __uint_as_float(w[i] << 16);
+        u[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+}
+
+__device__ __forceinline__ void store8(float *p, const float (&y)[8])
+{
+    *(float4 *)p = make_float4(y[0], y[1], y[2], y[3]);
+    *((float4 *)p + 1) = make_float4(y[4], y[5], y[6], y[7]);
+}
+__device__ __forceinline__ void store8(__half *p, const float (&y)[8])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const __half2 h = __halves2half2(__float2half_rn(y[2 * i]), __float2half_rn(y[2 * i + 1]));
+        w[i] = *(const uint32_t *)&h;
+    }
+    *(uint4 *)p = make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ void store8(bf16_t *p, const float (&y)[8])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        w[i] = (uint32_t)f32_to_bf16_bits(y[2 * i]) | ((uint32_t)f32_to_bf16_bits(y[2 * i + 1]) << 16);
+    *(uint4 *)p = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ---- quantiser epilogue for 8 consecutive channels per thread ----------------------------------
+// `lanes` consecutive lanes of a 16-lane row (1, 2, 4, 8 or 16) share one group, i.e. group = 8 * lanes.
+// Returns the packed codes of the thread's 8 channels (16 bits for INT2, 32 for INT4) and the stored
+// scale.  Same float32 operation sequence as documented in bq.h.
+template <int BITS>
+__device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out)
+{
+    float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fmaxf(fabsf(y[2]), fabsf(y[3])));
+    m = fmaxf(m, fmaxf(fmaxf(fabsf(y[4]), fabsf(y[5])), fmaxf(fabsf(y[6]), fabsf(y[7]))));
+    m = lanes_max(m, lanes);
+    constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
+    constexpr float qmin = -(float)(1 << (BITS - 1));
+    float inv;
+    *scale_out = group_scale(m, qmax, scale_f16, &inv);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int q = quant_code(y[r], inv, qmin, qmax);
+        packed |= ((uint32_t)q & ((1u << BITS) - 1u)) << (r * BITS);
+    }
+    return packed;
+}
+
+}  // namespace bq

@@ -6,6 +6,7 @@ namespace bq {
 hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                             const QuantArgs *q, hipStream_t stream)
 {
+    if (k12_supported(mode, in, out, s, q)) return launch_k12(mode, in, out, pv, s, q, stream);
     return launch_generic(mode, in, out, pv, s, q, stream);
 }
 

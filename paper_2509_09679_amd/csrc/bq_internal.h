@@ -116,6 +116,11 @@ size_t bwd_workspace_bytes_generic(const Shape &s);
 hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
                               void *ws, const Shape &s, hipStream_t stream);
 
+// n = 4096 specialised kernels: bq_k12.hip
+bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q);
+hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
+                      const QuantArgs *q, hipStream_t stream);
+
 // dispatch between specialised and generic kernels: bq_dispatch.hip
 hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                             const QuantArgs *q, hipStream_t stream);
