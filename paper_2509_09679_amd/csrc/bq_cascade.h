@@ -152,25 +152,72 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&y)[8])
 }
 
 // ---- quantiser epilogue for 8 consecutive channels per thread ----------------------------------
+// Reciprocal of a positive normal float whose significand has at most 11 bits (a binary16 value),
+// correctly rounded: hardware estimate (1 ulp) plus one Newton step in FMA arithmetic.  Used only
+// for binary16-valued scales (2^-24 .. 65504); the parity tests sweep every such value.
+__device__ __forceinline__ float rcp_f16_valued(float s)
+{
+    const float r = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, r, 1.0f);
+    return __builtin_fmaf(e, r, r);
+}
+
 // `lanes` consecutive lanes of a 16-lane row (1, 2, 4, 8 or 16) share one group, i.e. group = 8 * lanes.
 // Returns the packed codes of the thread's 8 channels (16 bits for INT2, 32 for INT4) and the stored
-// scale.  Same float32 operation sequence as documented in bq.h.
+// scale.  Same float32 operation sequence as documented in bq.h:
+//   amax -> s = amax / qmax -> (binary16 rounding) -> inv = 1 / s -> q = clip(rint(y * inv)).
+// The clip is applied to y * inv before rounding (the bounds are integers, so clipping and rounding
+// commute); rint is done by adding 1.5 * 2^23: the adder rounds the sum to an integer, ties to even,
+// and the low mantissa bits of the sum hold q in two's complement.  The 8 codes are gathered with one
+// shift-add each:  acc = sum (bits(f_j) << j*BITS)  =  sum q_j 2^(j*BITS) + const.  Adding the bias
+// 2^(BITS-1) to every field makes all fields non-negative (no borrows between fields); the final
+// XOR takes the bias out again, field by field.
 template <int BITS>
 __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out)
 {
-    float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fmaxf(fabsf(y[2]), fabsf(y[3])));
-    m = fmaxf(m, fmaxf(fmaxf(fabsf(y[4]), fabsf(y[5])), fmaxf(fabsf(y[6]), fabsf(y[7]))));
+    float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fabsf(y[2]));
+    m = fmaxf(fmaxf(m, fabsf(y[3])), fabsf(y[4]));
+    m = fmaxf(fmaxf(m, fabsf(y[5])), fabsf(y[6]));
+    m = fmaxf(m, fabsf(y[7]));
     m = lanes_max(m, lanes);
     constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
     constexpr float qmin = -(float)(1 << (BITS - 1));
-    float inv;
-    *scale_out = group_scale(m, qmax, scale_f16, &inv);
-    uint32_t packed = 0;
+    float s, inv;
+    if (scale_f16) {
+        // qmax = 1 for INT2: the division is the identity.  For INT4, m / 7 correctly rounded with
+        // three FMA-class operations (multiply by RN(1/7), exact remainder, correction); exact for
+        // every normal quotient, and quotients below the binary16 range round to a zero scale anyway.
+        if (BITS == 2) {
+            s = m;
+        } else {
+            constexpr float kRcp = 1.0f / qmax;
+            const float q0 = m * kRcp;
+            const float rem = __builtin_fmaf(-qmax, q0, m);
+            s = __builtin_fmaf(rem, kRcp, q0);
+        }
+        s = __half2float(__float2half_rn(fminf(s, 65504.0f)));
+        inv = rcp_f16_valued(s);
+    } else {
+        s = (BITS == 2) ? m : m / qmax;
+        inv = 1.0f / s;
+    }
+    inv = (s == 0.0f) ? 0.0f : inv;
+    *scale_out = s;
+    constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
+    uint32_t acc = 0;
+#pragma unroll
+    for (int r = 7; r >= 0; --r) {
+        const float t = __builtin_amdgcn_fmed3f(y[r] * inv, qmin, qmax);
+        acc = (acc << BITS) + __float_as_uint(t + kMagic);
+    }
+    uint32_t magic_sum = 0, bias = 0;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        const int q = quant_code(y[r], inv, qmin, qmax);
-        packed |= ((uint32_t)q & ((1u << BITS) - 1u)) << (r * BITS);
+        magic_sum += 0x4B400000u << (r * BITS);
+        bias |= (1u << (BITS - 1)) << (r * BITS);
     }
+    uint32_t packed = (acc - magic_sum + bias) ^ bias;
+    if (BITS == 2) packed &= 0xFFFFu;
     return packed;
 }
 

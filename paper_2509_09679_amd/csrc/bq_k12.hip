@@ -8,25 +8,36 @@
 //   layout N ("natural"): thread (wave w, lane l) holds idx = 8*chunk + r, chunk = 64 w + e(l),
 //                         r = 0..7.  Layers 1-3 pair registers, layers 4-7 pair lanes of a 16-lane
 //                         row through DPP (bq_cascade.h).
-//   layout P            : thread holds idx = baseP + 512 r'; idx bits 9,10,11 are the register index,
-//                         idx bits 7,8 are lane bits 0,1 (DPP quad_perm), the other seven idx bits are
-//                         spread over lane bits 2..5 and the wave index.  Layers 8,9 use DPP,
-//                         layers 10-12 pair registers.
-//   forward : load N, layers 1..7, LDS N->P, layers 8..12, LDS P->N, scale, quantise/store
-//   inverse : load N, LDS N->P, layers 12..8, LDS P->N, layers 7..1, scale, store
+//   layout P            : thread holds idx = baseP + b0 + 1024 r1 + 2048 r2 (register r' = b0 + 2 r1 +
+//                         4 r2): idx bit 0 and idx bits 10, 11 are register bits, idx bits 7, 8, 9 are
+//                         the chunk bits of lane bits 0..2 (DPP masks 1, 2, 7), idx bit 2 is lane
+//                         bit 3, the remaining idx bits are lane bits 4, 5 and the wave index.
+//                         Layers 8, 9, 10 use DPP, layers 11, 12 pair registers.
+//   forward : A: load N, layers 1..7, write LDS1 | B: read P, layers 8..12, write LDS2 |
+//             C: read N, output scale, quantise or store
+//   inverse : A: load N, write LDS1 | B: read P, layers 12..8, write LDS2 | C: read N, layers 7..1,
+//             output scale, store
 //
-// LDS float address of idx is idx + (idx >> 5) (one pad word per 32): with 32 banks both the N-side
-// accesses (lane stride 8 words) and the P-side accesses (lanes spread over idx bits 0,1,4 and 7,8)
-// of a half-wave hit 32 different banks.
+// The three phases of consecutive rows are software-pipelined: iteration `it` of a workgroup runs
+// C(row it-2), B(row it-1), A(row it) and then ONE barrier; LDS1 and LDS2 are double-buffered by row
+// parity, so every read of a buffer is separated from the next write to it by a barrier.
+//
+// LDS accesses are 64-bit (two adjacent floats per lane), which is what reaches the full LDS rate.
+// LDS float address of idx is idx + 2 (idx >> 5) + 2 (idx >> 9).  For a group of 16 lanes the N-side
+// accesses vary idx bits 3..6 and the P-side accesses idx bits 2, 7, 8, 9; in both cases the four
+// bits move the address by 2, 4, 8 and 16 words modulo 32, so the 16 lanes hit 16 different bank
+// pairs (the padding terms supply what the plain index lacks).
 //
 // If the plan flags the scale-deferred tables as unusable (a cosine too close to zero), the cascade
 // of a row runs through LDS with plain (cos, sin) rotations instead; everything else is unchanged.
+#include <cstdlib>
 #include "bq_cascade.h"
 
 namespace bq {
 
 constexpr int kN = 4096, kK = 12, kThreads = 512;
-constexpr int kLdsRow = kN + kN / 32;  // padded row
+constexpr int kLdsRow = 4368;  // floats: 4095 + 2*127 + 2*7 + 1, rounded up to a multiple of 4
+constexpr size_t kLdsBytes = 4 * kLdsRow * sizeof(float);  // three row buffers + the output-scale table
 
 struct K12Args {
     const void *in;
@@ -41,16 +52,51 @@ struct K12Args {
     uint8_t *codes;
     void *scales;
     int group, scale_f16;
+#ifdef BQ_TRACE
+    unsigned long long *trace;
+#endif
 };
 
-__device__ __forceinline__ int lds_addr(int idx) { return idx + (idx >> 5); }
+__device__ __forceinline__ int lds_addr(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
+constexpr int kPStepR1 = 1024 + 2 * 32 + 2 * 2;  // address step of register bit r1 (idx + 1024)
+constexpr int kPStepR2 = 2 * kPStepR1;           // register bit r2 (idx + 2048)
 
-// thread's base index in layout P (register r' adds 512 r')
+// thread's base index in layout P
 __device__ __forceinline__ int base_p(int wave, int lane)
 {
-    return ((lane & 1) << 7) | (((lane >> 1) & 1) << 8) | (((lane >> 2) & 1) << 0) | (((lane >> 3) & 1) << 1) |
-           (((lane >> 4) & 1) << 4) | (((lane >> 5) & 1) << 2) | ((wave & 1) << 3) | (((wave >> 1) & 1) << 5) |
-           (((wave >> 2) & 1) << 6);
+    const int c3 = lane_chunk(lane & 15) & 7;
+    return (c3 << 7) | (((lane >> 3) & 1) << 2) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 3) | (wave << 4);
+}
+__device__ __forceinline__ int p_reg_idx(int r) { return (r & 1) + 1024 * ((r >> 1) & 1) + 2048 * (r >> 2); }
+
+__device__ __forceinline__ void lds_write_n(float *buf, int an, const float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(float2 *)&buf[an + 2 * j] = make_float2(u[2 * j], u[2 * j + 1]);
+}
+__device__ __forceinline__ void lds_read_n(const float *buf, int an, float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 v = *(const float2 *)&buf[an + 2 * j];
+        u[2 * j] = v.x;
+        u[2 * j + 1] = v.y;
+    }
+}
+__device__ __forceinline__ void lds_write_p(float *buf, int ap, const float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        *(float2 *)&buf[ap + (j & 1) * kPStepR1 + (j >> 1) * kPStepR2] = make_float2(u[2 * j], u[2 * j + 1]);
+}
+__device__ __forceinline__ void lds_read_p(const float *buf, int ap, float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 v = *(const float2 *)&buf[ap + (j & 1) * kPStepR1 + (j >> 1) * kPStepR2];
+        u[2 * j] = v.x;
+        u[2 * j + 1] = v.y;
+    }
 }
 
 // slow cascade through LDS with (cos, sin); in: u[] in layout N, out: y[] in layout N (true values)
@@ -84,36 +130,40 @@ __device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const fl
 }
 
 // Epilogue shared by the fast and the slow loop: y[] holds the rotated values in layout N.
-template <typename T, int kMode, int kBits>
-__device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], T *out, int64_t row, int head,
-                                           int chunk)
+// kLanes > 0 fixes the group size (8 * kLanes) and kScale fixes the scale type (0 = float32,
+// 1 = binary16) at compile time; kLanes == 0 reads both from the arguments.
+// Addresses are a uniform row base plus a 32-bit per-thread offset.
+template <typename T, int kMode, int kBits, int kLanes, int kScale>
+__device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk)
 {
     if (kMode != kFwdQuant) {
-        store8(out + row * A.ld_out, y);
+        T *out_row = (T *)A.out + row * A.ld_out;
+        store8(out_row + (uint32_t)(head * kN + chunk * 8), y);
     } else {
-        const int lanes = A.group >> 3;  // 1..16 lanes per group
+        const int lanes = kLanes > 0 ? kLanes : (A.group >> 3);  // 1..16 lanes per group
+        const bool f16 = kLanes > 0 ? (kScale != 0) : (A.scale_f16 != 0);
         float s;
-        const uint32_t packed = quant8<kBits>(y, lanes, A.scale_f16 != 0, &s);
+        const uint32_t packed = quant8<kBits>(y, lanes, f16, &s);
         const int64_t unit = row * A.heads + head;
+        uint8_t *codes_row = A.codes + unit * (kN * kBits / 8);
         if (kBits == 2)
-            *(uint16_t *)(A.codes + unit * (kN / 4) + chunk * 2) = (uint16_t)packed;
+            *(uint16_t *)(codes_row + (uint32_t)(chunk * 2)) = (uint16_t)packed;
         else
-            *(uint32_t *)(A.codes + unit * (kN / 2) + chunk * 4) = packed;
-        if ((chunk & (lanes - 1)) == 0) {
-            const int64_t sidx = unit * (kN / A.group) + (chunk * 8) / A.group;
-            if (A.scale_f16)
-                ((__half *)A.scales)[sidx] = __float2half_rn(s);
-            else
-                ((float *)A.scales)[sidx] = s;
-        }
+            *(uint32_t *)(codes_row + (uint32_t)(chunk * 4)) = packed;
+        // every lane of a group stores the group's scale (same value, same address): no divergence
+        const uint32_t g = (uint32_t)chunk / (uint32_t)lanes;
+        const int groups = (kN / 8) / lanes;
+        if (f16)
+            ((__half *)A.scales + unit * groups)[g] = __float2half_rn(s);
+        else
+            ((float *)A.scales + unit * groups)[g] = s;
     }
 }
 
-template <typename T, int kMode, int kBits>
+template <typename T, int kMode, int kBits, int kLanes, int kScale>
 __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 {
-    __shared__ float lds1[kLdsRow];
-    __shared__ float lds2[kLdsRow];
+    extern __shared__ float lds[];  // row buffers L[0..2], then the output scales d in layout-N order
     constexpr bool kInverse = (kMode == kInv);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int chunk = wave * 64 + lane_chunk(lane);
@@ -121,28 +171,26 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
     const int head = blockIdx.x % A.heads;
     const int64_t row_first = blockIdx.x / A.heads;
     const int64_t row_step = gridDim.x / A.heads;
-    const T *in = (const T *)A.in + (size_t)head * kN + idx_n;
-    T *out = (T *)A.out + (size_t)head * kN + idx_n;
-    int64_t row = row_first;
-    if (row >= A.rows) return;
+    const uint32_t off_n = (uint32_t)(head * kN + idx_n);  // element offset of the thread inside a row
+    const T *in = (const T *)A.in;
+    if (row_first >= A.rows) return;
 
     if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
         const float2 *cs = A.cs + (size_t)head * kK * (kN / 2);
-        for (; row < A.rows; row += row_step) {
+        for (int64_t row = row_first; row < A.rows; row += row_step) {
             float u[8];
-            unpack8(load8(in + row * A.ld_in), u, (const T *)nullptr);
-            slow_cascade<kInverse>(u, lds1, cs, idx_n);
-            finish_row<T, kMode, kBits>(A, u, out, row, head, chunk);
+            unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
+            slow_cascade<kInverse>(u, lds, cs, idx_n);
+            finish_row<T, kMode, kBits, kLanes, kScale>(A, u, row, head, chunk);
         }
         return;
     }
 
     // coefficients: cn[j][r] for layer j+1 (layout N), cp[j][r'] for layer 8+j (layout P), d[r] (layout N)
     const int idx_p = base_p(wave, lane);
-    float cn[7][8], cp[5][8], d[8];
+    float cn[7][8], cp[5][8];
     {
         const float *fg = A.fg + (size_t)head * kK * kN;
-        const float *fd = A.fd + (size_t)head * kN;
 #pragma unroll
         for (int j = 0; j < 7; ++j)
 #pragma unroll
@@ -150,66 +198,94 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 #pragma unroll
         for (int j = 0; j < 5; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * kN + idx_p + 512 * r];
+            for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * kN + idx_p + p_reg_idx(r)];
+    }
+    const int an = lds_addr(idx_n);
+    const int ap = lds_addr(idx_p);
+    {   // output scales: kept in LDS (same padded addresses as a row), re-read by phase C of every row
+        const float *fd = A.fd + (size_t)head * kN;
+        float d[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) d[r] = fd[idx_n + r];
+        lds_write_n(lds + 3 * kLdsRow, an, d);
     }
-    const int an = lds_addr(idx_n);  // + r
-    const int ap = lds_addr(idx_p);  // + 528 r'
+    __syncthreads();
 
-    Raw8 raw = load8(in + row * A.ld_in);
-    for (; row < A.rows; row += row_step) {
-        float u[8];
-        unpack8(raw, u, (const T *)nullptr);
-        const int64_t next = row + row_step;
-        if (next < A.rows) raw = load8(in + next * A.ld_in);  // prefetch the next row of this workgroup
-
-        if (!kInverse) {
-            reg_layer<0>(u, cn[0]);
-            reg_layer<1>(u, cn[1]);
-            reg_layer<2>(u, cn[2]);
-            dpp_layer_xor1(u, cn[3]);
-            dpp_layer_xor2(u, cn[4]);
-            dpp_layer_xor7(u, cn[5]);
-            dpp_layer_xor8(u, cn[6]);
+    const int64_t n_my = (A.rows - row_first + row_step - 1) / row_step;  // rows of this workgroup
+    Raw8 raw = load8(in + row_first * A.ld_in + off_n);
+    int ba = 0, bb = 2, bc = 1;  // buffers of A(it), B(it-1), C(it-2)
+    for (int64_t it = 0; it < n_my + 2; ++it) {
+#ifdef BQ_TRACE
+#define TR(k) if (lane == 0 && blockIdx.x < 2 && it < 40) A.trace[((blockIdx.x * 8 + wave) * 40 + it) * 8 + (k)] = __builtin_readcyclecounter();
+#else
+#define TR(k)
+#endif
+        TR(0)
+        // row j lives in buffer j % 3: A(it) fills it, B(it-1) transforms it in place (every thread
+        // rewrites exactly the words it read), C(it-2) reads it.
+        float *la = lds + ba * kLdsRow;
+        float *lb = lds + bb * kLdsRow;
+        float *lc = lds + bc * kLdsRow;
+        if (it < n_my) {  // A(it)
+            float u[8];
+            unpack8(raw, u, (const T *)nullptr);
+            if (!kInverse) {
+                reg_layer<0>(u, cn[0]);
+                reg_layer<1>(u, cn[1]);
+                reg_layer<2>(u, cn[2]);
+                dpp_layer_xor1(u, cn[3]);
+                dpp_layer_xor2(u, cn[4]);
+                dpp_layer_xor7(u, cn[5]);
+                dpp_layer_xor8(u, cn[6]);
+            }
+            lds_write_n(la, an, u);
         }
-        // N -> P
+        TR(1)
+        if (it + 1 < n_my) raw = load8(in + (row_first + (it + 1) * row_step) * A.ld_in + off_n);  // prefetch
+        TR(2)
+        if (it >= 2) {  // C(it-2)
+            float u[8];
+            lds_read_n(lc, an, u);
+            if (kInverse) {
+                dpp_layer_xor8(u, cn[6]);
+                dpp_layer_xor7(u, cn[5]);
+                dpp_layer_xor2(u, cn[4]);
+                dpp_layer_xor1(u, cn[3]);
+                reg_layer<2>(u, cn[2]);
+                reg_layer<1>(u, cn[1]);
+                reg_layer<0>(u, cn[0]);
+            }
+            {
+                float d[8];
+                lds_read_n(lds + 3 * kLdsRow, an, d);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) lds1[an + r] = u[r];
+                for (int r = 0; r < 8; ++r) u[r] *= d[r];
+            }
+            finish_row<T, kMode, kBits, kLanes, kScale>(A, u, row_first + (it - 2) * row_step, head, chunk);
+        }
+        TR(3)
+        if (it >= 1 && it <= n_my) {  // B(it-1)
+            float u[8];
+            lds_read_p(lb, ap, u);
+            if (!kInverse) {
+                dpp_layer_xor1(u, cp[0]);
+                dpp_layer_xor2(u, cp[1]);
+                dpp_layer_xor7(u, cp[2]);
+                reg_layer<1>(u, cp[3]);
+                reg_layer<2>(u, cp[4]);
+            } else {
+                reg_layer<2>(u, cp[4]);
+                reg_layer<1>(u, cp[3]);
+                dpp_layer_xor7(u, cp[2]);
+                dpp_layer_xor2(u, cp[1]);
+                dpp_layer_xor1(u, cp[0]);
+            }
+            lds_write_p(lb, ap, u);
+        }
+        TR(4)
         __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 8; ++r) u[r] = lds1[ap + 528 * r];
-        if (!kInverse) {
-            dpp_layer_xor1(u, cp[0]);
-            dpp_layer_xor2(u, cp[1]);
-            reg_layer<0>(u, cp[2]);
-            reg_layer<1>(u, cp[3]);
-            reg_layer<2>(u, cp[4]);
-        } else {
-            reg_layer<2>(u, cp[4]);
-            reg_layer<1>(u, cp[3]);
-            reg_layer<0>(u, cp[2]);
-            dpp_layer_xor2(u, cp[1]);
-            dpp_layer_xor1(u, cp[0]);
-        }
-        // P -> N
-#pragma unroll
-        for (int r = 0; r < 8; ++r) lds2[ap + 528 * r] = u[r];
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 8; ++r) u[r] = lds2[an + r];
-        if (kInverse) {
-            dpp_layer_xor8(u, cn[6]);
-            dpp_layer_xor7(u, cn[5]);
-            dpp_layer_xor2(u, cn[4]);
-            dpp_layer_xor1(u, cn[3]);
-            reg_layer<2>(u, cn[2]);
-            reg_layer<1>(u, cn[1]);
-            reg_layer<0>(u, cn[0]);
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) u[r] *= d[r];
-        finish_row<T, kMode, kBits>(A, u, out, row, head, chunk);
+        TR(5)
+        { const int t = bc; bc = bb; bb = ba; ba = t; }
     }
 }
 
@@ -218,12 +294,16 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
 {
     void (*kern)(K12Args) = nullptr;
     if (mode == kFwd)
-        kern = k12_kernel<T, kFwd, 4>;
+        kern = k12_kernel<T, kFwd, 4, 0, 0>;
     else if (mode == kInv)
-        kern = k12_kernel<T, kInv, 4>;
+        kern = k12_kernel<T, kInv, 4, 0, 0>;
+    else if (A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
+        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1> : k12_kernel<T, kFwdQuant, 4, 16, 1>;
     else
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2> : k12_kernel<T, kFwdQuant, 4>;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), 0, stream, A);
+        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0> : k12_kernel<T, kFwdQuant, 4, 0, 0>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, A);
     return hipGetLastError();
 }
 
@@ -256,6 +336,9 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.ld_in = s.ld_x;
     A.ld_out = s.ld_y;
     A.heads = s.heads;
+#ifdef BQ_TRACE
+    A.trace = (unsigned long long *)strtoull(getenv("BQ_TRACE_PTR"), nullptr, 0);
+#endif
     int bits = 4;
     if (q) {
         A.codes = q->codes;
@@ -267,6 +350,7 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // persistent workgroups: two per compute unit, a multiple of the head count
     int64_t per_head = s.rows < (512 / s.heads > 0 ? 512 / s.heads : 1) ? s.rows : (512 / s.heads > 0 ? 512 / s.heads : 1);
     unsigned grid = (unsigned)(per_head * s.heads);
+    if (const char *g = getenv("BQ_K12_GRID")) { unsigned v = (unsigned)atoi(g); if (v > 0 && v <= s.rows && s.heads == 1) grid = v; }
     switch (s.dtype) {
         case BQ_F32: return launch_k12_t<float>(mode, A, bits, grid, stream);
         case BQ_F16: return launch_k12_t<__half>(mode, A, bits, grid, stream);
