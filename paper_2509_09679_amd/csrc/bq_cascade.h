@@ -87,6 +87,22 @@ __device__ __forceinline__ void reg_layer(float (&u)[8], const float (&c)[8])
     }
 }
 
+// First layer of a cascade: every element still has scale 1, so the two coefficients of a pair are
+// t and -t; only the upper element's coefficient c[b] is read (the negation is an operand modifier).
+template <int J>
+__device__ __forceinline__ void reg_layer_first(float (&u)[8], const float (&c)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (!(r & (1 << J))) {
+            const int a = r, b = r | (1 << J);
+            const float ua = u[a], ub = u[b];
+            u[a] = __builtin_fmaf(-c[b], ub, ua);
+            u[b] = __builtin_fmaf(c[b], ua, ub);
+        }
+    }
+}
+
 // ---- row I/O: 8 consecutive elements per thread ------------------------------------------------
 struct Raw8 {
     uint4 lo, hi;  // f16/bf16 use lo only
