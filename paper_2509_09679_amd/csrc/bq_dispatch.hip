@@ -7,6 +7,7 @@ hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView
                             const QuantArgs *q, hipStream_t stream)
 {
     if (k12_supported(mode, in, out, s, q)) return launch_k12(mode, in, out, pv, s, q, stream);
+    if (small_supported(mode, in, out, s, q)) return launch_small(mode, in, out, pv, s, q, stream);
     return launch_generic(mode, in, out, pv, s, q, stream);
 }
 

@@ -121,6 +121,11 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream);
 
+// n = 8..128 specialised kernels: bq_small.hip
+bool small_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q);
+hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
+                        const QuantArgs *q, hipStream_t stream);
+
 // dispatch between specialised and generic kernels: bq_dispatch.hip
 hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                             const QuantArgs *q, hipStream_t stream);

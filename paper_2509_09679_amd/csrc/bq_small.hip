@@ -1,0 +1,278 @@
+// Specialised kernels for small transforms, n = 8 .. 128 (k = 3 .. 7), any number of heads whose row
+// width tiles 2048 elements: forward, inverse and fused forward + quantisation.
+//
+// A transform of n elements occupies n/8 consecutive lanes (at most one 16-lane row), 8 consecutive
+// elements per lane, and never touches LDS: layers 1-3 pair registers, layers 4..k pair lanes through
+// DPP (bq_cascade.h).  All k*8 scale-deferred coefficients and the 8 output scales of a thread stay
+// in registers; a workgroup of 256 threads covers 2048 consecutive elements — a slice of a wide row
+// (e.g. 32 heads x 128) or several narrow rows (e.g. 16 rows of 128) — and loops over the batch with
+// the same coefficients.  Two independent row groups are processed per iteration and the next two are
+// prefetched meanwhile, so that four 16-byte loads per lane are in flight.
+//
+// If the plan flags the scale-deferred tables as unusable, rows go through plain (cos, sin) rotations
+// with the twiddles re-read from the plan (slow, rare).
+#include "bq_cascade.h"
+
+namespace bq {
+
+constexpr int kSmallThreads = 256;
+constexpr int kSmallSpan = kSmallThreads * 8;  // elements covered by a workgroup
+
+struct SmallArgs {
+    const void *in;
+    void *out;
+    const float *fg, *fd;
+    const float2 *cs;
+    const int *fast_bad;
+    int64_t rows, ld_in, ld_out;
+    int heads, width;    // width = heads * n
+    int rows_per_block;  // kSmallSpan / width if width < kSmallSpan, else 1
+    int slices;          // width / kSmallSpan if width >= kSmallSpan, else 1
+    int64_t n_groups;    // row groups = ceil(rows / rows_per_block)
+    uint8_t *codes;
+    void *scales;
+    int group, scale_f16;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Plain (cos, sin) cascade for flagged plans: a run-time loop over the layers (kept rolled so that
+// this rare path needs few registers); partners come from registers for layers 1-3 and from the
+// lanes lane^1, lane^2, lane^7, lane^8 for layers 4-7.
+template <int K, bool kInverse>
+__device__ __noinline__ void slow_small(float (&u)[8], const float2 *__restrict__ cs_head, int idx)
+{
+    constexpr int n = 1 << K;
+#pragma unroll 1
+    for (int step = 0; step < K; ++step) {
+        const int i = kInverse ? (K - step) : (step + 1);
+        const int h = 1 << (i - 1);
+        float p[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            float v;
+            switch (i) {
+                case 1: v = u[r ^ 1]; break;
+                case 2: v = u[r ^ 2]; break;
+                case 3: v = u[r ^ 4]; break;
+                case 4: v = dpp_read<0xB1>(u[r]); break;   // quad_perm [1,0,3,2]
+                case 5: v = dpp_read<0x4E>(u[r]); break;   // quad_perm [2,3,0,1]
+                case 6: v = dpp_read<0x141>(u[r]); break;  // row_half_mirror
+                default: v = dpp_read<0x128>(u[r]); break; // row_ror:8
+            }
+            p[r] = v;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int e = idx + r;
+            const int a = e & ~h;
+            const int pr = ((a >> i) << (i - 1)) | (a & (h - 1));
+            const float2 w = cs_head[(size_t)(i - 1) * (n >> 1) + pr];
+            const bool upper = (e & h) != 0;
+            // forward: lower  c x - s p, upper  c x + s p ; transposed: the signs swap
+            const float sgn = (upper != kInverse) ? w.y : -w.y;
+            u[r] = __builtin_fmaf(w.x, u[r], sgn * p[r]);
+        }
+    }
+}
+
+template <int K, bool kInverse>
+__device__ __forceinline__ void fast_small(float (&u)[8], const float (&c)[7][8], const float (&d)[8])
+{
+    if (!kInverse) {
+        reg_layer_first<0>(u, c[0]);
+        reg_layer<1>(u, c[1]);
+        reg_layer<2>(u, c[2]);
+        if (K >= 4) dpp_layer_xor1(u, c[3]);
+        if (K >= 5) dpp_layer_xor2(u, c[4]);
+        if (K >= 6) dpp_layer_xor7(u, c[5]);
+        if (K >= 7) dpp_layer_xor8(u, c[6]);
+    } else {
+        if (K >= 7) dpp_layer_xor8(u, c[6]);
+        if (K >= 6) dpp_layer_xor7(u, c[5]);
+        if (K >= 5) dpp_layer_xor2(u, c[4]);
+        if (K >= 4) dpp_layer_xor1(u, c[3]);
+        reg_layer<2>(u, c[2]);
+        reg_layer<1>(u, c[1]);
+        reg_layer<0>(u, c[0]);
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) u[r] *= d[r];
+}
+
+template <typename T, int K, int kMode, int kBits>
+__global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
+{
+    constexpr int n = 1 << K;
+    constexpr bool kInverse = (kMode == kInv);
+    const int tid = threadIdx.x;
+    const int chunk = (tid & ~15) | lane_chunk(tid & 15);  // chunk of 8 elements inside the workgroup's span
+    const int e0 = chunk * 8;
+    int row_in_block, col;
+    int64_t grp_first, grp_step;
+    if (A.slices > 1) {
+        row_in_block = 0;
+        col = (int)(blockIdx.x % A.slices) * kSmallSpan + e0;
+        grp_first = blockIdx.x / A.slices;
+        grp_step = gridDim.x / A.slices;
+    } else {
+        row_in_block = e0 / A.width;
+        col = e0 - row_in_block * A.width;
+        grp_first = blockIdx.x;
+        grp_step = gridDim.x;
+    }
+    const int head = col >> K;
+    const int idx = col & (n - 1);
+    const bool fast = (*A.fast_bad == 0);
+
+    const float2 *cs_head = A.cs + (size_t)head * K * (n >> 1);
+    const T *in = (const T *)A.in;
+    const uint32_t col_bytes = (uint32_t)col * (uint32_t)sizeof(T);
+
+    auto row_of = [&](int64_t g) { return g * A.rows_per_block + row_in_block; };
+    auto load_row = [&](int64_t g) {
+        int64_t row = row_of(g);
+        if (row >= A.rows) row = A.rows - 1;  // clamp: the value is not used
+        uint32_t off = col_bytes;
+        asm volatile("" : "+v"(off));
+        return load8((const T *)((const char *)(in + row * A.ld_in) + off));
+    };
+    auto finish = [&](const float (&y)[8], int64_t g) {
+        const int64_t row = row_of(g);
+        if (row >= A.rows) return;
+        if (kMode != kFwdQuant) {
+            uint32_t off = col_bytes;
+            asm volatile("" : "+v"(off));
+            store8((T *)((char *)((T *)A.out + row * A.ld_out) + off), y);
+        } else {
+            const int lanes = A.group >> 3;
+            float s;
+            const uint32_t packed = quant8<kBits>(y, lanes, A.scale_f16 != 0, &s);
+            uint8_t *codes_row = A.codes + row * (int64_t)(A.width * kBits / 8);
+            const uint32_t coff = (uint32_t)col * kBits / 8;
+            if (kBits == 2)
+                *(uint16_t *)(codes_row + coff) = (uint16_t)packed;
+            else
+                *(uint32_t *)(codes_row + coff) = packed;
+            const int64_t sidx = row * (int64_t)(A.width / A.group) + (uint32_t)col / (uint32_t)A.group;
+            if (A.scale_f16)
+                ((__half *)A.scales)[sidx] = __float2half_rn(s);
+            else
+                ((float *)A.scales)[sidx] = s;
+        }
+    };
+
+    if (grp_first >= A.n_groups) return;
+    if (!fast) {  // rare
+        for (int64_t g = grp_first; g < A.n_groups; g += grp_step) {
+            float u[8];
+            unpack8(load_row(g), u, (const T *)nullptr);
+            slow_small<K, kInverse>(u, cs_head, idx);
+            finish(u, g);
+        }
+        return;
+    }
+    float c[7][8], d[8];
+    {
+        const float *fg = A.fg + (size_t)head * K * n;
+#pragma unroll
+        for (int j = 0; j < 7; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c[j][r] = (j < K) ? fg[j * n + idx + r] : 0.0f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) d[r] = A.fd[(size_t)head * n + idx + r];
+    }
+    Raw8 raw0 = load_row(grp_first);
+    Raw8 raw1 = load_row(grp_first + grp_step);
+    for (int64_t g = grp_first; g < A.n_groups; g += 2 * grp_step) {
+        float u0[8], u1[8];
+        unpack8(raw0, u0, (const T *)nullptr);
+        unpack8(raw1, u1, (const T *)nullptr);
+        raw0 = load_row(g + 2 * grp_step);
+        raw1 = load_row(g + 3 * grp_step);
+        fast_small<K, kInverse>(u0, c, d);
+        fast_small<K, kInverse>(u1, c, d);
+        finish(u0, g);
+        if (g + grp_step < A.n_groups) finish(u1, g + grp_step);
+    }
+}
+
+template <typename T, int K>
+static void (*pick_small(Mode mode, int bits))(SmallArgs)
+{
+    if (mode == kFwd) return small_kernel<T, K, kFwd, 4>;
+    if (mode == kInv) return small_kernel<T, K, kInv, 4>;
+    return bits == 2 ? small_kernel<T, K, kFwdQuant, 2> : small_kernel<T, K, kFwdQuant, 4>;
+}
+
+template <typename T>
+static void (*pick_small_k(int k, Mode mode, int bits))(SmallArgs)
+{
+    switch (k) {
+        case 3: return pick_small<T, 3>(mode, bits);
+        case 4: return pick_small<T, 4>(mode, bits);
+        case 5: return pick_small<T, 5>(mode, bits);
+        case 6: return pick_small<T, 6>(mode, bits);
+        default: return pick_small<T, 7>(mode, bits);
+    }
+}
+
+bool small_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q)
+{
+    if (s.k < 3 || s.k > 7) return false;
+    const int64_t width = (int64_t)s.n * s.heads;
+    if (!((width < kSmallSpan && kSmallSpan % width == 0) || (width >= kSmallSpan && width % kSmallSpan == 0)))
+        return false;
+    const int isz = s.dtype == BQ_F32 ? 4 : 2;
+    const int vec = 16 / isz;
+    if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
+    if (mode != kFwdQuant && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
+    if (mode == kFwdQuant) {
+        if (q->group > s.n) return false;
+        if (((uintptr_t)q->codes & 3)) return false;
+    }
+    return true;
+}
+
+hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
+                        const QuantArgs *q, hipStream_t stream)
+{
+    SmallArgs A{};
+    A.in = in;
+    A.out = out;
+    A.fg = mode == kInv ? pv.fg_inv : pv.fg_fwd;
+    A.fd = mode == kInv ? pv.fd_inv : pv.fd_fwd;
+    A.cs = pv.cs;
+    A.fast_bad = mode == kInv ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
+    A.rows = s.rows;
+    A.ld_in = s.ld_x;
+    A.ld_out = s.ld_y;
+    A.heads = s.heads;
+    A.width = s.n * s.heads;
+    A.rows_per_block = A.width < kSmallSpan ? kSmallSpan / A.width : 1;
+    A.slices = A.width >= kSmallSpan ? A.width / kSmallSpan : 1;
+    A.n_groups = (s.rows + A.rows_per_block - 1) / A.rows_per_block;
+    int bits = 4;
+    if (q) {
+        A.codes = q->codes;
+        A.scales = q->scales;
+        A.group = q->group;
+        A.scale_f16 = q->scale_f16;
+        bits = q->bits;
+    }
+    // persistent workgroups: up to 8 per compute unit, a multiple of the slice count
+    int64_t per_slice = 2048 / A.slices > 0 ? 2048 / A.slices : 1;
+    if (per_slice > A.n_groups) per_slice = A.n_groups;
+    const unsigned grid = (unsigned)(per_slice * A.slices);
+    void (*kern)(SmallArgs) = s.dtype == BQ_F32   ? pick_small_k<float>(s.k, mode, bits)
+                              : s.dtype == BQ_F16 ? pick_small_k<__half>(s.k, mode, bits)
+                                                  : pick_small_k<bf16_t>(s.k, mode, bits);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kSmallThreads), 0, stream, A);
+    return hipGetLastError();
+}
+
+}  // namespace bq

@@ -95,12 +95,33 @@ def test_cosines_near_zero_take_the_safe_path():
                          oracle.inverse(synth.to_f64(x, dtype), th, n), dtype, f"pi/2 inv n={n}")
 
 
+@pytest.mark.parametrize("n,heads,rows,dtype", [(8, 1, 1000, "f16"), (16, 4, 301, "bf16"), (32, 64, 77, "f16"),
+                                                 (64, 2, 515, "f32"), (128, 16, 130, "f16"), (128, 2, 49, "bf16"),
+                                                 (64, 32, 3, "f32")])
+def test_small_transforms_many_heads_ragged_rows(n, heads, rows, dtype):
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=21)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype), _ref_fwd(x, th, n, heads, dtype), dtype,
+                     f"small fwd n={n} H={heads}")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, inverse=True),
+                     oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"small inv n={n} H={heads}")
+
+
+@pytest.mark.parametrize("n,heads,bits,group,scale_dtype,rows", [(64, 4, 4, 16, "f16", 100), (128, 16, 2, 64, "f32", 37),
+                                                                  (32, 8, 4, 32, "f32", 250), (16, 2, 2, 8, "f16", 999)])
+def test_small_transforms_fused_quant(n, heads, bits, group, scale_dtype, rows):
+    x, th, _ = synth.small_case(n, rows, "bf16", heads=heads, seed=22)
+    y_ref = _ref_fwd(x, th, n, heads, "bf16")
+    codes, scales = gu.run_fwd_quant(x, th, n, heads, "bf16", bits, group, scale_dtype)
+    gu.check_fused_codes(codes, scales, y_ref, bits, group, scale_dtype, "bf16", f"small n={n}")
+
+
 # ---- quantiser: bit-exact when fed the oracle's rotated values ---------------------------------
 
 @pytest.mark.parametrize("n,heads,bits,group,scale_dtype",
                          [(128, 1, 4, 128, "f32"), (4096, 1, 4, 128, "f16"), (4096, 1, 2, 128, "f16"),
                           (128, 32, 4, 128, "f32"), (4096, 1, 4, 4096, "f32"), (256, 2, 2, 8, "f16"),
-                          (4096, 1, 2, 32, "f32"), (1024, 1, 4, 64, "f16")])
+                          (4096, 1, 2, 32, "f32"), (1024, 1, 4, 64, "f16"), (64, 32, 4, 8, "f16"),
+                          (128, 16, 2, 128, "f16"), (4096, 1, 4, 8, "f16"), (4096, 1, 4, 128, "f32")])
 def test_quantiser_bit_exact_on_oracle_rotated_values(n, heads, bits, group, scale_dtype):
     rows = 29
     x, th, _ = synth.small_case(n, rows, "f16", heads=heads, seed=11)
