@@ -1,0 +1,541 @@
+// Backward pass for n = 4096 and n = 8192 (k = 12, 13), one head: dx = B^T dy and
+// dtheta[i][p] = sum over rows of  g_i[b] x_i[a] - g_i[a] x_i[b]   (x_i, g_i at the output of layer i;
+// paper, "Gradient Flow Through Butterfly Layers": d y_a / d theta = -y_b, d y_b / d theta = y_a).
+//
+// Registers cannot hold the coefficients of all layers, the dtheta accumulators of all layers and
+// two rows at once, so the pass is cut at layer 7 into three kernels; a batch is processed in row
+// chunks small enough for the float32 intermediates of a chunk to stay in the 256 MB last-level cache:
+//
+//   F: x -> x_k            forward cascade (same structure as the forward kernels), float32 out
+//   P: (x_k, dy) -> layers k..8 transposed on BOTH vectors with the same coefficients, accumulating
+//      the angle gradients of those layers; writes (x_7, g_7) in scale-deferred units, float32
+//   N: (x_7, g_7) -> layers 7..1 transposed on both, accumulating their angle gradients; dx out
+//
+// Orthogonality makes stored activations unnecessary: x_{i-1} = B_i^T x_i.  Both x and g start the
+// transposed cascade with scale 1, so they share the scale-deferred coefficients and, before layer i,
+// the scales D_i[e] (plan table fw_inv).  Sums are accumulated in deferred units,
+//   acc += v_g[b] v_x[a] - v_g[a] v_x[b],   dtheta = D_i[a] D_i[b] acc,
+// the factor being applied once per workgroup at the end.  For a layer that pairs lanes each lane keeps
+// the partial sum of its own element (one v_fmac_f32 with a DPP operand per element); the two lanes'
+// sums are combined at the end.
+//
+// Every workgroup owns one slice of `partial` ([slices][k*n/2]); a slice entry is written by exactly
+// one thread, chunks add to it in stream order, and a last kernel sums the slices in double in a fixed
+// order: no atomics, the result does not depend on scheduling.
+//
+// All kernels exit at once when the plan flags the scale-deferred tables as unusable; the generic
+// backward kernel, launched behind them with the opposite condition, then does the work.
+#include "bq_cascade.h"
+
+namespace bq {
+
+template <int K>
+struct Geo {
+    static constexpr int n = 1 << K;
+    static constexpr int threads = n / 8;
+    static constexpr int kPDpp = K - 9;  // lane-pairing layers of phase P (layers 8 .. 8+kPDpp-1)
+    static constexpr int kStepR1 = (1 << (K - 2)) + 2 * (1 << (K - 7)) + 2 * (1 << (K - 11));
+    static constexpr int kStepR2 = 2 * kStepR1;
+    static constexpr int kRowFloats = ((n - 1) + 2 * ((n - 1) >> 5) + 2 * ((n - 1) >> 9) + 1 + 3) & ~3;
+};
+
+__device__ __forceinline__ int lds_addr2(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
+
+// base index of a thread in layout P: idx bits 7.. are the chunk bits of the low lane bits (DPP
+// masks 1, 2, 7, 8), idx bit 0 and the two top bits are register bits, the rest lanes 3..5 / waves.
+template <int K>
+__device__ __forceinline__ int base_p2(int wave, int lane)
+{
+    if (K == 12) {
+        const int c3 = lane_chunk(lane & 15) & 7;
+        return (c3 << 7) | (((lane >> 3) & 1) << 2) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 3) | (wave << 4);
+    } else {
+        const int c4 = lane_chunk(lane & 15);
+        return (c4 << 7) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 2) | (wave << 3);
+    }
+}
+template <int K>
+__device__ __forceinline__ int p_reg_idx2(int r)
+{
+    return (r & 1) + ((r >> 1) & 1) * (1 << (K - 2)) + (r >> 2) * (1 << (K - 1));
+}
+
+template <int K>
+__device__ __forceinline__ void lds_write_p2(float *buf, int ap, const float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        *(float2 *)&buf[ap + (j & 1) * Geo<K>::kStepR1 + (j >> 1) * Geo<K>::kStepR2] = make_float2(u[2 * j], u[2 * j + 1]);
+}
+template <int K>
+__device__ __forceinline__ void lds_read_p2(const float *buf, int ap, float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 v = *(const float2 *)&buf[ap + (j & 1) * Geo<K>::kStepR1 + (j >> 1) * Geo<K>::kStepR2];
+        u[2 * j] = v.x;
+        u[2 * j + 1] = v.y;
+    }
+}
+__device__ __forceinline__ void lds_write_n2(float *buf, int an, const float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(float2 *)&buf[an + 2 * j] = make_float2(u[2 * j], u[2 * j + 1]);
+}
+__device__ __forceinline__ void lds_read_n2(const float *buf, int an, float (&u)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 v = *(const float2 *)&buf[an + 2 * j];
+        u[2 * j] = v.x;
+        u[2 * j + 1] = v.y;
+    }
+}
+
+// acc[r] += vg[r] of lane (lane ^ mask) * vx[r]
+#define BQ_DPP_ACC8(MOD)                                                                                     \
+    asm volatile("s_nop 1\n\t"                                                                              \
+                 "v_fmac_f32_dpp %0, %8, %16 " MOD " row_mask:0xf bank_mask:0xf\n\t"                        \
+                 "v_fmac_f32_dpp %1, %9, %17 " MOD " row_mask:0xf bank_mask:0xf\n\t"                        \
+                 "v_fmac_f32_dpp %2, %10, %18 " MOD " row_mask:0xf bank_mask:0xf\n\t"                       \
+                 "v_fmac_f32_dpp %3, %11, %19 " MOD " row_mask:0xf bank_mask:0xf\n\t"                       \
+                 "v_fmac_f32_dpp %4, %12, %20 " MOD " row_mask:0xf bank_mask:0xf\n\t"                       \
+                 "v_fmac_f32_dpp %5, %13, %21 " MOD " row_mask:0xf bank_mask:0xf\n\t"                       \
+                 "v_fmac_f32_dpp %6, %14, %22 " MOD " row_mask:0xf bank_mask:0xf\n\t"                       \
+                 "v_fmac_f32_dpp %7, %15, %23 " MOD " row_mask:0xf bank_mask:0xf"                           \
+                 : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]),        \
+                   "+v"(acc[6]), "+v"(acc[7])                                                                \
+                 : "v"(vg[0]), "v"(vg[1]), "v"(vg[2]), "v"(vg[3]), "v"(vg[4]), "v"(vg[5]), "v"(vg[6]), "v"(vg[7]), \
+                   "v"(vx[0]), "v"(vx[1]), "v"(vx[2]), "v"(vx[3]), "v"(vx[4]), "v"(vx[5]), "v"(vx[6]), "v"(vx[7]))
+
+__device__ __forceinline__ void dpp_acc_xor1(float (&acc)[8], const float (&vg)[8], const float (&vx)[8]) { BQ_DPP_ACC8("quad_perm:[1,0,3,2]"); }
+__device__ __forceinline__ void dpp_acc_xor2(float (&acc)[8], const float (&vg)[8], const float (&vx)[8]) { BQ_DPP_ACC8("quad_perm:[2,3,0,1]"); }
+__device__ __forceinline__ void dpp_acc_xor7(float (&acc)[8], const float (&vg)[8], const float (&vx)[8]) { BQ_DPP_ACC8("row_half_mirror"); }
+__device__ __forceinline__ void dpp_acc_xor8(float (&acc)[8], const float (&vg)[8], const float (&vx)[8]) { BQ_DPP_ACC8("row_ror:8"); }
+
+// register-pair layer J: acc[q] (q = index of the pair among the 4 pairs) += vg[b] vx[a] - vg[a] vx[b]
+template <int J>
+__device__ __forceinline__ void reg_acc(float (&acc)[4], const float (&vg)[8], const float (&vx)[8])
+{
+    int q = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (!(r & (1 << J))) {
+            const int a = r, b = r | (1 << J);
+            acc[q] = __builtin_fmaf(vg[b], vx[a], acc[q]);
+            acc[q] = __builtin_fmaf(-vg[a], vx[b], acc[q]);
+            ++q;
+        }
+    }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+struct BwdFastArgs {
+    const void *x, *dy;
+    void *dx;
+    float *xk, *vx7, *vg7;  // chunk intermediates, [chunk_rows][n] float32
+    float *partial;         // [slices][k * n / 2]
+    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv, *fw_inv;
+    const int *bad_fwd, *bad_inv;
+    int64_t row0, rows;  // this chunk: rows [row0, row0 + rows) of the batch
+    int64_t ld_in, ld_out;
+    int first_chunk;     // != 0: slices are overwritten, else added to
+};
+
+__device__ __forceinline__ bool plan_is_bad(const BwdFastArgs &A) { return (*A.bad_fwd | *A.bad_inv) != 0; }
+
+__device__ __forceinline__ void put_partial(float *p, float v, int first)
+{
+    if (first)
+        *p = v;
+    else
+        *p += v;
+}
+
+// ---- F: forward cascade to float32 ----------------------------------------------------------------
+template <typename T, int K>
+__global__ __launch_bounds__(Geo<K>::threads) void bwd_f_kernel(BwdFastArgs A)
+{
+    using G = Geo<K>;
+    extern __shared__ float lds[];  // [row buffer][output scales]
+    if (plan_is_bad(A)) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int chunk = wave * 64 + lane_chunk(lane);
+    const int idx_n = chunk * 8;
+    const int idx_p = base_p2<K>(wave, lane);
+    const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
+    float *buf = lds, *dtab = lds + G::kRowFloats;
+    float cn[7][8], cp[K - 7][8];
+#pragma unroll
+    for (int j = 0; j < 7; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cn[j][r] = A.fg_fwd[j * G::n + idx_n + r];
+#pragma unroll
+    for (int j = 0; j < K - 7; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_fwd[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
+    {
+        float d[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) d[r] = A.fd_fwd[idx_n + r];
+        lds_write_n2(dtab, an, d);
+    }
+    const T *x = (const T *)A.x + A.row0 * A.ld_in + idx_n;
+    int64_t row = blockIdx.x;
+    if (row >= A.rows) return;
+    Raw8 raw = load8(x + row * A.ld_in);
+    for (; row < A.rows; row += gridDim.x) {
+        float u[8];
+        unpack8(raw, u, (const T *)nullptr);
+        const int64_t next = row + gridDim.x;
+        if (next < A.rows) raw = load8(x + next * A.ld_in);
+        reg_layer_first<0>(u, cn[0]);
+        reg_layer<1>(u, cn[1]);
+        reg_layer<2>(u, cn[2]);
+        dpp_layer_xor1(u, cn[3]);
+        dpp_layer_xor2(u, cn[4]);
+        dpp_layer_xor7(u, cn[5]);
+        dpp_layer_xor8(u, cn[6]);
+        __syncthreads();  // the previous row's reads of buf are complete
+        lds_write_n2(buf, an, u);
+        __syncthreads();
+        lds_read_p2<K>(buf, ap, u);
+        dpp_layer_xor1(u, cp[0]);
+        dpp_layer_xor2(u, cp[1]);
+        dpp_layer_xor7(u, cp[2]);
+        if (K == 13) dpp_layer_xor8(u, cp[K - 10]);
+        reg_layer<1>(u, cp[K - 9]);
+        reg_layer<2>(u, cp[K - 8]);
+        lds_write_p2<K>(buf, ap, u);
+        __syncthreads();
+        lds_read_n2(buf, an, u);
+        float d[8];
+        lds_read_n2(dtab, an, d);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) u[r] *= d[r];
+        store8(A.xk + row * G::n + idx_n, u);
+    }
+}
+
+// ---- P: layers k..8 transposed on x and g, accumulating their angle gradients -----------------------
+template <typename T, int K>
+__global__ __launch_bounds__(Geo<K>::threads) void bwd_p_kernel(BwdFastArgs A)
+{
+    using G = Geo<K>;
+    extern __shared__ float lds[];  // [parity][x row, g row]
+    if (plan_is_bad(A)) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int chunk = wave * 64 + lane_chunk(lane);
+    const int idx_n = chunk * 8;
+    const int idx_p = base_p2<K>(wave, lane);
+    const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
+    constexpr int nd = G::kPDpp;  // 3 or 4 lane layers: layers 8 .. 7+nd; register layers K-1 (bit 1), K (bit 2)
+    float cp[K - 7][8];
+#pragma unroll
+    for (int j = 0; j < K - 7; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_inv[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
+    float acc_d[nd][8], acc_r1[4], acc_r2[4];
+#pragma unroll
+    for (int j = 0; j < nd; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc_d[j][r] = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc_r1[q] = acc_r2[q] = 0.0f;
+
+    const T *dy = (const T *)A.dy + A.row0 * A.ld_in + idx_n;
+    int par = 0;
+    for (int64_t row = blockIdx.x; row < A.rows; row += gridDim.x) {
+        float *bx = lds + par * 2 * G::kRowFloats, *bg = bx + G::kRowFloats;
+        par ^= 1;
+        float vx[8], vg[8];
+        {
+            const float4 a = *(const float4 *)(A.xk + row * G::n + idx_n);
+            const float4 b = *((const float4 *)(A.xk + row * G::n + idx_n) + 1);
+            vx[0] = a.x; vx[1] = a.y; vx[2] = a.z; vx[3] = a.w; vx[4] = b.x; vx[5] = b.y; vx[6] = b.z; vx[7] = b.w;
+            unpack8(load8(dy + row * A.ld_in), vg, (const T *)nullptr);
+        }
+        lds_write_n2(bx, an, vx);
+        lds_write_n2(bg, an, vg);
+        __syncthreads();
+        lds_read_p2<K>(bx, ap, vx);
+        lds_read_p2<K>(bg, ap, vg);
+        // layer K (register bit 2), layer K-1 (register bit 1)
+        reg_acc<2>(acc_r2, vg, vx);
+        reg_layer_first<2>(vx, cp[K - 8]);
+        reg_layer_first<2>(vg, cp[K - 8]);
+        reg_acc<1>(acc_r1, vg, vx);
+        reg_layer<1>(vx, cp[K - 9]);
+        reg_layer<1>(vg, cp[K - 9]);
+        if (K == 13) {
+            dpp_acc_xor8(acc_d[nd - 1], vg, vx);
+            dpp_layer_xor8(vx, cp[K - 10]);
+            dpp_layer_xor8(vg, cp[K - 10]);
+        }
+        dpp_acc_xor7(acc_d[2], vg, vx);
+        dpp_layer_xor7(vx, cp[2]);
+        dpp_layer_xor7(vg, cp[2]);
+        dpp_acc_xor2(acc_d[1], vg, vx);
+        dpp_layer_xor2(vx, cp[1]);
+        dpp_layer_xor2(vg, cp[1]);
+        dpp_acc_xor1(acc_d[0], vg, vx);
+        dpp_layer_xor1(vx, cp[0]);
+        dpp_layer_xor1(vg, cp[0]);
+        lds_write_p2<K>(bx, ap, vx);
+        lds_write_p2<K>(bg, ap, vg);
+        __syncthreads();
+        lds_read_n2(bx, an, vx);
+        lds_read_n2(bg, an, vg);
+        store8(A.vx7 + row * G::n + idx_n, vx);
+        store8(A.vg7 + row * G::n + idx_n, vg);
+    }
+
+    // deferred sums -> dtheta partials of this workgroup
+    float *part = A.partial + (size_t)blockIdx.x * (K * (G::n / 2));
+    auto pair_index = [](int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); };
+    {  // register layers
+#pragma unroll
+        for (int J = 1; J <= 2; ++J) {
+            const int i = (J == 2) ? K : K - 1;
+            const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
+            int q = 0;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if (!(r & (1 << J))) {
+                    const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
+                    const float v = (J == 2 ? acc_r2[q] : acc_r1[q]) * (fw[a] * fw[b]);
+                    put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), v, A.first_chunk);
+                    ++q;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < nd; ++j) {  // lane layers: layer 8 + j, lane mask 1, 2, 7, 8
+        const int i = 8 + j;
+        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float mine = acc_d[j][r];
+            const float other = j == 0   ? dpp_get<0xB1>(mine)
+                                : j == 1 ? dpp_get<0x4E>(mine)
+                                : j == 2 ? dpp_get<0x141>(mine)
+                                         : dpp_get<0x128>(mine);
+            const int e = idx_p + p_reg_idx2<K>(r);
+            if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
+                const int b = e | (1 << (i - 1));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]),
+                            A.first_chunk);
+            }
+        }
+    }
+}
+
+// ---- N: layers 7..1 transposed on x and g, accumulating their angle gradients; dx out ----------------
+constexpr int kNThreads = 256;
+constexpr int kNSpan = kNThreads * 8;
+
+template <typename T, int K>
+__global__ __launch_bounds__(kNThreads) void bwd_n_kernel(BwdFastArgs A, int spans)
+{
+    using G = Geo<K>;
+    if (plan_is_bad(A)) return;
+    const int tid = threadIdx.x;
+    const int span = blockIdx.x % spans;
+    const int slice = blockIdx.x / spans, n_slices = gridDim.x / spans;
+    const int idx = span * kNSpan + ((tid & ~15) | lane_chunk(tid & 15)) * 8;  // column of element 0
+    float cn[7][8], d[8];
+#pragma unroll
+    for (int j = 0; j < 7; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cn[j][r] = A.fg_inv[j * G::n + idx + r];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) d[r] = A.fd_inv[idx + r];
+    float acc_d[4][8], acc_r[3][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc_d[j][r] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc_r[j][q] = 0.0f;
+
+    auto load_f32 = [&](const float *base, int64_t row, float (&v)[8]) {
+        const float4 a = *(const float4 *)(base + row * G::n + idx);
+        const float4 b = *((const float4 *)(base + row * G::n + idx) + 1);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    };
+    T *dx = A.dx ? (T *)A.dx + A.row0 * A.ld_out + idx : nullptr;
+    for (int64_t row = slice; row < A.rows; row += n_slices) {
+        float vx[8], vg[8];
+        load_f32(A.vx7, row, vx);
+        load_f32(A.vg7, row, vg);
+        dpp_acc_xor8(acc_d[3], vg, vx);  // layer 7
+        dpp_layer_xor8(vx, cn[6]);
+        dpp_layer_xor8(vg, cn[6]);
+        dpp_acc_xor7(acc_d[2], vg, vx);  // layer 6
+        dpp_layer_xor7(vx, cn[5]);
+        dpp_layer_xor7(vg, cn[5]);
+        dpp_acc_xor2(acc_d[1], vg, vx);  // layer 5
+        dpp_layer_xor2(vx, cn[4]);
+        dpp_layer_xor2(vg, cn[4]);
+        dpp_acc_xor1(acc_d[0], vg, vx);  // layer 4
+        dpp_layer_xor1(vx, cn[3]);
+        dpp_layer_xor1(vg, cn[3]);
+        reg_acc<2>(acc_r[2], vg, vx);  // layer 3
+        reg_layer<2>(vx, cn[2]);
+        reg_layer<2>(vg, cn[2]);
+        reg_acc<1>(acc_r[1], vg, vx);  // layer 2
+        reg_layer<1>(vx, cn[1]);
+        reg_layer<1>(vg, cn[1]);
+        reg_acc<0>(acc_r[0], vg, vx);  // layer 1 (x is not needed below it)
+        reg_layer<0>(vg, cn[0]);
+        if (dx) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) vg[r] *= d[r];
+            store8(dx + row * A.ld_out, vg);
+        }
+    }
+
+    float *part = A.partial + (size_t)slice * (K * (G::n / 2));
+    auto pair_index = [](int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); };
+#pragma unroll
+    for (int J = 0; J < 3; ++J) {  // layers 1..3
+        const int i = J + 1;
+        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
+        int q = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (!(r & (1 << J))) {
+                const int a = idx + r, b = idx + (r | (1 << J));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), acc_r[J][q] * (fw[a] * fw[b]),
+                            A.first_chunk);
+                ++q;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
+        const int i = 4 + j;
+        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float mine = acc_d[j][r];
+            const float other = j == 0   ? dpp_get<0xB1>(mine)
+                                : j == 1 ? dpp_get<0x4E>(mine)
+                                : j == 2 ? dpp_get<0x141>(mine)
+                                         : dpp_get<0x128>(mine);
+            const int e = idx + r;
+            if (!(e & (1 << (i - 1)))) {
+                const int b = e | (1 << (i - 1));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]),
+                            A.first_chunk);
+            }
+        }
+    }
+}
+
+// dtheta[q] = sum over slices of partial[s][q], in double, slice order; skipped for flagged plans
+__global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dtheta, size_t n_angles,
+                                  int n_parts, const int *bad_fwd, const int *bad_inv)
+{
+    if ((*bad_fwd | *bad_inv) != 0) return;
+    const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n_angles) return;
+    double acc = 0.0;
+    for (int w = 0; w < n_parts; ++w) acc += (double)partial[(size_t)w * n_angles + q];
+    dtheta[q] = (float)acc;
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+static int bwd_fast_slices(int k) { return k == 12 ? 512 : 256; }
+static int64_t bwd_fast_chunk_rows(int k) { return k == 12 ? 4096 : 2048; }  // ~192 MB of float32 intermediates
+
+bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
+{
+    if (!(s.k == 12 || s.k == 13) || s.heads != 1 || dtheta == nullptr || s.rows == 0) return false;
+    const int vec = s.dtype == BQ_F32 ? 4 : 8;
+    if (((uintptr_t)x & 15) || ((uintptr_t)dy & 15) || (dx && ((uintptr_t)dx & 15))) return false;
+    if ((s.ld_x % vec) || (s.ld_y % vec)) return false;
+    return true;
+}
+
+size_t bwd_fast_workspace_bytes(const Shape &s)
+{
+    const size_t angles = (size_t)s.k * (s.n / 2);
+    const size_t chunk = (size_t)(s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k));
+    return align256((size_t)bwd_fast_slices(s.k) * angles * sizeof(float)) + 3 * align256(chunk * s.n * sizeof(float));
+}
+
+template <typename T, int K>
+static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta, char *ws, hipStream_t stream)
+{
+    using G = Geo<K>;
+    const size_t angles = (size_t)K * (G::n / 2);
+    const int slices = bwd_fast_slices(K);
+    const int64_t chunk_rows = s.rows < bwd_fast_chunk_rows(K) ? s.rows : bwd_fast_chunk_rows(K);
+    const size_t inter = align256((size_t)chunk_rows * G::n * sizeof(float));
+    A.partial = (float *)ws;
+    char *p = ws + align256((size_t)slices * angles * sizeof(float));
+    A.xk = (float *)p;
+    A.vx7 = (float *)(p + inter);
+    A.vg7 = (float *)(p + 2 * inter);
+    const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_p = 4 * G::kRowFloats * sizeof(float);
+    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)bwd_p_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_p);
+    if (e != hipSuccess) return e;
+    const int spans = G::n / kNSpan;
+    for (int64_t r0 = 0; r0 < s.rows; r0 += chunk_rows) {
+        A.row0 = r0;
+        A.rows = s.rows - r0 < chunk_rows ? s.rows - r0 : chunk_rows;
+        A.first_chunk = (r0 == 0);
+        // every slice must be written by the first chunk, so the grids do not shrink with the row count
+        hipLaunchKernelGGL((bwd_f_kernel<T, K>), dim3(slices), dim3(G::threads), lds_f, stream, A);
+        hipLaunchKernelGGL((bwd_p_kernel<T, K>), dim3(slices), dim3(G::threads), lds_p, stream, A);
+        hipLaunchKernelGGL((bwd_n_kernel<T, K>), dim3(slices * spans), dim3(kNThreads), 0, stream, A, spans);
+    }
+    const unsigned blocks = (unsigned)((angles + 255) / 256);
+    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, angles, slices,
+                       A.bad_fwd, A.bad_inv);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
+                           const Shape &s, hipStream_t stream)
+{
+    BwdFastArgs A{};
+    A.x = x;
+    A.dy = dy;
+    A.dx = dx;
+    A.fg_fwd = pv.fg_fwd;
+    A.fd_fwd = pv.fd_fwd;
+    A.fg_inv = pv.fg_inv;
+    A.fd_inv = pv.fd_inv;
+    A.fw_inv = pv.fw_inv;
+    A.bad_fwd = &pv.hdr->fast_bad_fwd;
+    A.bad_inv = &pv.hdr->fast_bad_inv;
+    A.ld_in = s.ld_x;
+    A.ld_out = s.ld_y;
+    char *w = (char *)ws;
+    if (s.k == 12) {
+        switch (s.dtype) {
+            case BQ_F32: return launch_bwd_fast_t<float, 12>(A, s, dtheta, w, stream);
+            case BQ_F16: return launch_bwd_fast_t<__half, 12>(A, s, dtheta, w, stream);
+            default: return launch_bwd_fast_t<bf16_t, 12>(A, s, dtheta, w, stream);
+        }
+    }
+    switch (s.dtype) {
+        case BQ_F32: return launch_bwd_fast_t<float, 13>(A, s, dtheta, w, stream);
+        case BQ_F16: return launch_bwd_fast_t<__half, 13>(A, s, dtheta, w, stream);
+        default: return launch_bwd_fast_t<bf16_t, 13>(A, s, dtheta, w, stream);
+    }
+}
+
+}  // namespace bq

@@ -11,11 +11,28 @@ hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView
     return launch_generic(mode, in, out, pv, s, q, stream);
 }
 
-size_t bwd_workspace_bytes(const Shape &s) { return bwd_workspace_bytes_generic(s); }
+size_t bwd_workspace_bytes(const Shape &s)
+{
+    size_t need = bwd_workspace_bytes_generic(s);
+    if ((s.k == 12 || s.k == 13) && s.heads == 1 && s.rows > 0) {
+        const size_t fast = bwd_fast_workspace_bytes(s);
+        if (fast > need) need = fast;
+    }
+    return need;
+}
 
 hipError_t launch_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
                       const Shape &s, hipStream_t stream)
 {
+    if (!dtheta) {  // dx alone is the transposed transform of dy
+        Shape t = s;
+        return launch_transform(kInv, dy, dx, pv, t, nullptr, stream);
+    }
+    if (bwd_fast_supported(x, dy, dx, dtheta, s)) {
+        hipError_t e = launch_bwd_fast(x, dy, pv, dx, dtheta, ws, s, stream);
+        if (e != hipSuccess) return e;
+        return launch_generic_bwd(x, dy, pv, dx, dtheta, ws, s, stream, /*only_if_bad=*/true);
+    }
     return launch_generic_bwd(x, dy, pv, dx, dtheta, ws, s, stream);
 }
 

@@ -212,12 +212,14 @@ struct BwdArgs {
     int64_t rows, ld_in, ld_out;
     int n, heads, k, rows_per_tile;
     int64_t n_tiles;
+    const int *bad_a, *bad_b;  // if not NULL: run only when one of the flags is set
 };
 
 template <typename T>
 __global__ __launch_bounds__(kGenThreads) void generic_bwd_kernel(BwdArgs A)
 {
     extern __shared__ float lds[];
+    if (A.bad_a && (*A.bad_a | *A.bad_b) == 0) return;
     const int n = A.n, k = A.k, heads = A.heads, U = A.rows_per_tile;
     float *xb = lds;
     float *gb = lds + (size_t)U * n;
@@ -289,8 +291,9 @@ __global__ __launch_bounds__(kGenThreads) void generic_bwd_kernel(BwdArgs A)
 
 // dtheta[q] = sum over workgroups of partial[w][q], accumulated in double in workgroup order.
 __global__ void reduce_partials_kernel(const float *__restrict__ partial, float *__restrict__ dtheta,
-                                       size_t n_angles, int n_parts)
+                                       size_t n_angles, int n_parts, const int *bad_a, const int *bad_b)
 {
+    if (bad_a && (*bad_a | *bad_b) == 0) return;
     size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= n_angles) return;
     double acc = 0.0;
@@ -323,7 +326,7 @@ size_t bwd_workspace_bytes_generic(const Shape &s)
 }
 
 hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
-                              void *ws, const Shape &s, hipStream_t stream)
+                              void *ws, const Shape &s, hipStream_t stream, bool only_if_bad)
 {
     BwdArgs A{};
     unsigned grid;
@@ -339,6 +342,8 @@ hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv,
     A.n = s.n;
     A.heads = s.heads;
     A.k = s.k;
+    A.bad_a = only_if_bad ? &pv.hdr->fast_bad_fwd : nullptr;
+    A.bad_b = only_if_bad ? &pv.hdr->fast_bad_inv : nullptr;
     size_t lds_bytes = (size_t)2 * A.rows_per_tile * s.n * sizeof(float);
     void (*kern)(BwdArgs) = s.dtype == BQ_F32   ? generic_bwd_kernel<float>
                             : s.dtype == BQ_F16 ? generic_bwd_kernel<__half>
@@ -355,7 +360,7 @@ hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv,
         size_t n_angles = (size_t)s.heads * s.k * (s.n / 2);
         unsigned blocks = (unsigned)((n_angles + 255) / 256);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta,
-                           n_angles, (int)grid);
+                           n_angles, (int)grid, A.bad_a, A.bad_b);
         e = hipGetLastError();
     }
     return e;

@@ -19,6 +19,9 @@ namespace bq {
 //   [fd_fwd  : float  [heads][n]]      forward output scales
 //   [fg_inv  : float  [heads][k][n]]   the same for the transposed cascade
 //   [fd_inv  : float  [heads][n]]
+//   [fw_inv  : float  [heads][k][n]]   scale D of every element just BEFORE transposed layer i is applied
+//                                      (row i-1); the backward kernels turn sums accumulated in deferred
+//                                      units into dtheta with the factor D[a] * D[b] of the pair
 //   [dwork   : double [heads][n]]      scratch of the plan build
 //
 // Scale-deferred form.  A rotation  ya = c xa - s xb, yb = s xa + c xb  with t = s / c is
@@ -43,7 +46,7 @@ struct PlanHeader {
 static_assert(sizeof(PlanHeader) == 256, "header is 256 bytes");
 
 struct PlanLayout {
-    size_t cs, fg_fwd, fd_fwd, fg_inv, fd_inv, dwork, total;
+    size_t cs, fg_fwd, fd_fwd, fg_inv, fd_inv, fw_inv, dwork, total;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -58,6 +61,7 @@ inline PlanLayout plan_layout(int n, int heads, int k)
     L.fd_fwd = off;  off = align256(off + H * N * sizeof(float));
     L.fg_inv = off;  off = align256(off + H * K * N * sizeof(float));
     L.fd_inv = off;  off = align256(off + H * N * sizeof(float));
+    L.fw_inv = off;  off = align256(off + H * K * N * sizeof(float));
     L.dwork = off;   off = align256(off + H * N * sizeof(double));
     L.total = off;
     return L;
@@ -74,7 +78,7 @@ inline int ilog2_exact(int n)
 struct PlanView {  // device pointers into a plan
     const PlanHeader *hdr;
     const float2 *cs;
-    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv;
+    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv, *fw_inv;
 };
 
 inline PlanView plan_view(const void *plan, int n, int heads, int k)
@@ -88,6 +92,7 @@ inline PlanView plan_view(const void *plan, int n, int heads, int k)
     v.fd_fwd = (const float *)(p + L.fd_fwd);
     v.fg_inv = (const float *)(p + L.fg_inv);
     v.fd_inv = (const float *)(p + L.fd_inv);
+    v.fw_inv = (const float *)(p + L.fw_inv);
     return v;
 }
 
@@ -113,8 +118,16 @@ enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2 };
 hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                           const QuantArgs *q, hipStream_t stream);
 size_t bwd_workspace_bytes_generic(const Shape &s);
+// only_if_bad: run only when the plan flags its scale-deferred tables as unusable (the specialised
+// backward kernels, launched before, then did nothing)
 hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
-                              void *ws, const Shape &s, hipStream_t stream);
+                              void *ws, const Shape &s, hipStream_t stream, bool only_if_bad = false);
+
+// n = 4096 / 8192 backward: bq_bwd.hip
+bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s);
+size_t bwd_fast_workspace_bytes(const Shape &s);
+hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
+                           const Shape &s, hipStream_t stream);
 
 // n = 4096 specialised kernels: bq_k12.hip
 bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q);

@@ -181,6 +181,27 @@ def test_backward_workload5_sample_and_determinism():
     assert np.array_equal(dth, dth2) and np.array_equal(dx, dx2)  # no atomics: run-to-run bit equality
 
 
+@pytest.mark.parametrize("n,rows,dtype", [(8192, 2300, "bf16"), (4096, 4500, "f16"), (4096, 700, "f32")])
+def test_backward_several_chunks(n, rows, dtype):
+    # more rows than one chunk of the three-kernel backward pipeline: slices are added to across chunks
+    x, th, dy = synth.small_case(n, rows, dtype, seed=17, with_dy=True, outliers=0)
+    dx, dth = gu.run_bwd(x, dy, th, n, 1, dtype)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n)
+    gu.check_rotated(dx, rdx, dtype, f"dx n={n}")
+    gu.check_dtheta(dth, rdth, ab, what=f"n={n} rows={rows}")
+
+
+def test_backward_flagged_plan_takes_the_plain_path():
+    n = 4096
+    th = np.full((1, 12, n // 2), np.float32(math.pi / 2), np.float32)
+    th[0, 1::2, ::5] = np.float32(-math.pi / 2)
+    x, _, dy = synth.small_case(n, 40, "bf16", seed=19, with_dy=True, outliers=0)
+    dx, dth = gu.run_bwd(x, dy, th, n, 1, "bf16")
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, "bf16"), synth.to_f64(dy, "bf16"), th, n)
+    gu.check_rotated(dx, rdx, "bf16", "dx flagged")
+    gu.check_dtheta(dth, rdth, ab, what="flagged plan")
+
+
 def test_backward_optional_outputs_and_zero_rows():
     x, th, dy = synth.small_case(256, 10, "f32", seed=2, with_dy=True)
     dx, _ = gu.run_bwd(x, dy, th, 256, 1, "f32", want_dtheta=False)
