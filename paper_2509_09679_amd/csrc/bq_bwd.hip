@@ -3,8 +3,8 @@
 // paper, "Gradient Flow Through Butterfly Layers": d y_a / d theta = -y_b, d y_b / d theta = y_a).
 //
 // Registers cannot hold the coefficients of all layers, the dtheta accumulators of all layers and
-// two rows at once, so the pass is cut at layer 7 into three kernels; a batch is processed in row
-// chunks small enough for the float32 intermediates of a chunk to stay in the 256 MB last-level cache:
+// two rows at once, so the pass is cut at layer 7 into three kernels that hand float32 intermediates
+// to each other through the workspace; a batch is processed in row chunks to bound that workspace:
 //
 //   F: x -> x_k            forward cascade (same structure as the forward kernels), float32 out
 //   P: (x_k, dy) -> layers k..8 transposed on BOTH vectors with the same coefficients, accumulating
@@ -455,7 +455,10 @@ __global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__re
 
 // ---- host side -----------------------------------------------------------------------------------
 static int bwd_fast_slices(int k) { return k == 12 ? 512 : 256; }
-static int64_t bwd_fast_chunk_rows(int k) { return k == 12 ? 4096 : 2048; }  // ~192 MB of float32 intermediates
+// Rows per chunk: 2^28 elements, i.e. 3 GiB of float32 intermediates at most.  Small chunks that would
+// stay in the last-level cache measured slower: every launch re-reads the coefficients and rewrites the
+// partial slices, which only amortises over many rows per workgroup.
+static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (28 - k); }
 
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
 {

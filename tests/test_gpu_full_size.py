@@ -1,0 +1,114 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times: inputs are
+drawn on the device, the library runs on the whole batch, and the oracle checks sampled rows (rows are
+independent) or, where it is cheap enough, the whole result (dtheta summed over all rows, in chunks)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_09679_amd import binding as B
+from paper_2509_09679_amd import synth
+
+pytestmark = pytest.mark.gpu
+gu = pytest.importorskip("gpu_util")
+
+DEV = "cuda:0"
+
+
+def _sample_rows(T, count, seed):
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, 1, T // 2, T - 2, T - 1], rng.integers(0, T, size=count)]))
+    return rows
+
+
+def test_workload3_full_size_fused_forward_inverse():
+    cfg, T = 3, 262144
+    x, th, _ = synth.device_rows(cfg, T, DEV)
+    wl = synth.make_workload(cfg, rows=1)
+    n = wl.n
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, 1)
+    rows = B.make_rows(x, n, 1)
+    pick = _sample_rows(T, 96, 1)
+    xs = synth.torch_to_storage(x[torch.as_tensor(pick, device=DEV)], wl.dtype)
+    y_ref = oracle.forward(synth.to_f64(xs, wl.dtype), th, n)
+    for bits in (2, 4):
+        codes, scales = B.alloc_quant_outputs(T, n, 1, bits, 128, "f16", DEV)
+        codes.fill_(0x5A)
+        B.bq_butterfly_fwd_quant(x, plan, codes, scales, B.make_quant(bits, 128, "f16"), rows)
+        torch.cuda.synchronize()
+        c = codes[torch.as_tensor(pick, device=DEV)].cpu().numpy()
+        s = scales[torch.as_tensor(pick, device=DEV)].float().cpu().numpy()
+        gu.check_fused_codes(c, s, y_ref, bits, 128, "f16", wl.dtype, f"c3 full int{bits}")
+        # properties that hold for every row: codes in range, every non-zero group reaches +-qmax
+        qmax = 2 ** (bits - 1) - 1
+        blk = codes[:4096].cpu().numpy()
+        q = oracle.unpack_codes(blk, bits).reshape(4096, -1, 128)
+        assert np.abs(q).max() <= qmax
+        nz = scales[:4096].float().cpu().numpy() > 0
+        assert (np.abs(q).max(axis=2)[nz] == qmax).all()
+        del codes, scales
+    y = torch.empty_like(x)
+    B.bq_butterfly_fwd(x, y, plan, rows)
+    torch.cuda.synchronize()
+    ys = synth.torch_to_storage(y[torch.as_tensor(pick, device=DEV)], wl.dtype)
+    gu.check_rotated(ys, y_ref, wl.dtype, "c3 full fwd")
+    xi = torch.empty_like(x)
+    B.bq_butterfly_inv(y, xi, plan, rows)
+    torch.cuda.synchronize()
+    xis = synth.torch_to_storage(xi[torch.as_tensor(pick, device=DEV)], wl.dtype)
+    gu.check_rotated(xis, oracle.inverse(synth.to_f64(ys, wl.dtype), th, n), wl.dtype, "c3 full inv")
+    # norm preservation on a large block of rows (any row): |Bx| = |x| up to output rounding
+    nx = torch.linalg.vector_norm(x[:65536].float(), dim=1)
+    ny = torch.linalg.vector_norm(y[:65536].float(), dim=1)
+    assert torch.all((nx - ny).abs() <= 2e-3 * nx)
+
+
+def test_workload4_full_size_per_head_quant():
+    cfg, T = 4, 8192
+    x, th, _ = synth.device_rows(cfg, T, DEV)
+    wl = synth.make_workload(cfg, rows=1)
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, wl.n, wl.heads)
+    codes, scales = B.alloc_quant_outputs(T, wl.n, wl.heads, 4, wl.n, "f32", DEV)
+    B.bq_butterfly_fwd_quant(x, plan, codes, scales, B.make_quant(4, wl.n, "f32"), B.make_rows(x, wl.n, wl.heads))
+    torch.cuda.synchronize()
+    xs = synth.torch_to_storage(x, wl.dtype)
+    y_ref = oracle.forward(synth.to_f64(xs, wl.dtype), th, wl.n, wl.heads)  # the whole batch
+    gu.check_fused_codes(codes.cpu().numpy(), scales.cpu().numpy(), y_ref, 4, wl.n, "f32", wl.dtype, "c4 full")
+
+
+def _oracle_dtheta_in_chunks(x, dy, th, n, dtype, chunk=8192):
+    T = x.shape[0]
+    acc = None
+    ab = None
+    for r0 in range(0, T, chunk):
+        xs = synth.to_f64(synth.torch_to_storage(x[r0:r0 + chunk], dtype), dtype)
+        gs = synth.to_f64(synth.torch_to_storage(dy[r0:r0 + chunk], dtype), dtype)
+        _, d, a = oracle.backward(xs, gs, th, n)
+        acc = d if acc is None else acc + d
+        ab = a if ab is None else ab + a
+    return acc, ab
+
+
+@pytest.mark.parametrize("cfg,T", [(5, 65536), (3, 262144)])
+def test_backward_full_size(cfg, T):
+    # cfg 5: n=8192 bf16 (two chunks of the backward pipeline); cfg 3 shape: n=4096 f16 (four chunks)
+    x, th, dy = synth.device_rows(cfg, T, DEV, want_dy=True)
+    wl = synth.make_workload(cfg, rows=1)
+    n, dtype = wl.n, wl.dtype
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, 1)
+    rows = B.make_rows(x, n, 1)
+    dx = torch.empty_like(x)
+    dth = torch.empty_like(theta)
+    ws = torch.empty(B.bq_butterfly_bwd_workspace_bytes(rows), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
+    torch.cuda.synchronize()
+    del ws
+    pick = _sample_rows(T, 48, 2)
+    gs = synth.torch_to_storage(dy[torch.as_tensor(pick, device=DEV)], dtype)
+    dxs = synth.torch_to_storage(dx[torch.as_tensor(pick, device=DEV)], dtype)
+    gu.check_rotated(dxs, oracle.inverse(synth.to_f64(gs, dtype), th, n), dtype, f"cfg {cfg} full dx")
+    ref, ab = _oracle_dtheta_in_chunks(x, dy, th, n, dtype)
+    gu.check_dtheta(dth.cpu().numpy(), ref, ab, what=f"cfg {cfg} full dtheta")
