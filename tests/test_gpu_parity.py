@@ -136,6 +136,50 @@ def test_quantiser_bit_exact_on_oracle_rotated_values(n, heads, bits, group, sca
     assert np.array_equal(codes, oracle.pack_codes(ref_codes, bits))
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quantiser_every_binary16_scale_bit_exact(bits):
+    # The fused kernels compute 1/s with a hardware estimate plus one Newton step and, for INT4, amax/7
+    # with a multiply-remainder-correct sequence; both must reproduce correctly rounded division.
+    # Sweep every positive finite binary16 scale value: one group per value, amax = qmax * s exactly.
+    n, group = 4096, 128
+    qmax = 2 ** (bits - 1) - 1
+    hbits = np.arange(1, 0x7C00, dtype=np.uint16)  # all positive finite binary16 values
+    pad = (-len(hbits)) % 32
+    hbits = np.concatenate([hbits, np.full(pad, 0x3C00, np.uint16)])
+    s_vals = hbits.view(np.float16).astype(np.float32)
+    rng = np.random.default_rng(bits)
+    frac = rng.uniform(-1.0, 1.0, size=(len(s_vals), group)).astype(np.float32)
+    # plant exact rounding boundaries (k + 1/2) * s and values just around them
+    ks = rng.integers(0, qmax + 1, size=(len(s_vals), 8)).astype(np.float32)
+    frac[:, 1:9] = (ks + np.float32(0.5)) / np.float32(qmax) * rng.choice([-1.0, 1.0], size=ks.shape).astype(np.float32)
+    frac[:, 0] = rng.choice([-1.0, 1.0], size=len(s_vals))
+    y = (frac * (np.float32(qmax) * s_vals)[:, None]).astype(np.float32).reshape(-1, n)
+    th = np.zeros((1, 12, n // 2), np.float32)
+    codes, scales = gu.run_fwd_quant(y, th, n, 1, "f32", bits, group, "f16")
+    ref_codes, ref_scales = oracle.quantize(y, group, bits, "f16")
+    assert np.array_equal(scales.view(np.uint32), ref_scales.view(np.uint32))
+    assert np.array_equal(codes, oracle.pack_codes(ref_codes, bits))
+
+
+def test_quantiser_int4_scale_division_bit_exact_on_random_mantissas():
+    n, group, rows = 4096, 128, 4096
+    rng = np.random.default_rng(7)
+    mant = rng.integers(0, 2 ** 23, size=rows * 32, dtype=np.uint32)
+    mant[:64] = np.uint32(2 ** 23 - 1) - np.arange(64, dtype=np.uint32)  # significands near all-ones
+    mant[64:128] = np.arange(64, dtype=np.uint32)                        # and near a power of two
+    expo = rng.integers(127 - 30, 127 + 18, size=rows * 32, dtype=np.uint32)
+    amax = ((expo << np.uint32(23)) | mant).view(np.float32)
+    frac = rng.uniform(-1.0, 1.0, size=(rows * 32, group)).astype(np.float32)
+    frac[:, 0] = 1.0
+    y = (frac * amax[:, None]).astype(np.float32).reshape(rows, n)
+    th = np.zeros((1, 12, n // 2), np.float32)
+    for scale_dtype in ("f16", "f32"):
+        codes, scales = gu.run_fwd_quant(y, th, n, 1, "f32", 4, group, scale_dtype)
+        ref_codes, ref_scales = oracle.quantize(y, group, 4, scale_dtype)
+        assert np.array_equal(scales.view(np.uint32), ref_scales.view(np.uint32)), scale_dtype
+        assert np.array_equal(codes, oracle.pack_codes(ref_codes, 4)), scale_dtype
+
+
 # ---- fused forward + quantisation on the five workloads ----------------------------------------
 
 @pytest.mark.parametrize("cfg,rows", [(1, None), (2, 1), (2, 8), (2, 64), (3, 300), (4, 200)])
