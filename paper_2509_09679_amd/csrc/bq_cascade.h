@@ -183,7 +183,8 @@ __device__ __forceinline__ float rcp_f16_valued(float s)
 // scale.  Same float32 operation sequence as documented in bq.h:
 //   amax -> s = amax / qmax -> (binary16 rounding) -> inv = 1 / s -> q = clip(rint(y * inv)).
 // The clip is applied to y * inv before rounding (the bounds are integers, so clipping and rounding
-// commute); rint is done by adding 1.5 * 2^23: the adder rounds the sum to an integer, ties to even,
+// commute) and only for the rare scales that can make |y * inv| exceed qmax (a zero product needs no
+// clip either); rint is done by adding 1.5 * 2^23: the adder rounds the sum to an integer, ties to even,
 // and the low mantissa bits of the sum hold q in two's complement.  The 8 codes are gathered with one
 // shift-add each:  acc = sum (bits(f_j) << j*BITS)  =  sum q_j 2^(j*BITS) + const.  Adding the bias
 // 2^(BITS-1) to every field makes all fields non-negative (no borrows between fields); the final
@@ -199,6 +200,7 @@ __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool 
     constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
     constexpr float qmin = -(float)(1 << (BITS - 1));
     float s, inv;
+    bool ordinary;  // scale for which |y * inv| <= qmax (1 + 2^-10): the clip cannot act
     if (scale_f16) {
         // qmax = 1 for INT2: the division is the identity.  For INT4, m / 7 correctly rounded with
         // three FMA-class operations (multiply by RN(1/7), exact remainder, correction); exact for
@@ -211,21 +213,30 @@ __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool 
             const float rem = __builtin_fmaf(-qmax, q0, m);
             s = __builtin_fmaf(rem, kRcp, q0);
         }
-        s = __half2float(__float2half_rn(fminf(s, 65504.0f)));
+        const float sh = __half2float(__float2half_rn(fminf(s, 65504.0f)));
+        // binary16 rounding moves a normal scale by at most 2^-11 relative; subnormal and saturated
+        // scales can be far below amax / qmax and need the clip
+        ordinary = (sh >= 6.103515625e-05f) && (s <= 65504.0f);
+        s = sh;
         inv = rcp_f16_valued(s);
     } else {
         s = (BITS == 2) ? m : m / qmax;
         inv = 1.0f / s;
+        ordinary = s >= 0x1p-100f;
     }
     inv = (s == 0.0f) ? 0.0f : inv;
     *scale_out = s;
     constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
+    float t[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) t[r] = y[r] * inv;
+    if (__builtin_expect(!ordinary, 0)) {  // rare: clip before rounding (the bounds are integers)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t[r] = __builtin_amdgcn_fmed3f(t[r], qmin, qmax);
+    }
     uint32_t acc = 0;
 #pragma unroll
-    for (int r = 7; r >= 0; --r) {
-        const float t = __builtin_amdgcn_fmed3f(y[r] * inv, qmin, qmax);
-        acc = (acc << BITS) + __float_as_uint(t + kMagic);
-    }
+    for (int r = 7; r >= 0; --r) acc = (acc << BITS) + __float_as_uint(t[r] + kMagic);
     uint32_t magic_sum = 0, bias = 0;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {

@@ -445,10 +445,11 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
         A.scale_f16 = q->scale_f16;
         bits = q->bits;
     }
-    // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time; four
-    // per compute unit (1024 in all) measured a few percent faster than two on large batches because
-    // the second wave of workgroups evens out the tail.
-    int64_t per_head = 1024 / s.heads > 0 ? 1024 / s.heads : 1;
+    // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  On
+    // large batches the fused kernel (VALU-bound) measured fastest with 1024 workgroups, the plain
+    // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
+    const int target = mode == kFwdQuant ? 1024 : 768;
+    int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
     if (per_head > s.rows) per_head = s.rows;
     unsigned grid = (unsigned)(per_head * s.heads);
     switch (s.dtype) {
