@@ -222,6 +222,235 @@ __global__ __launch_bounds__(Geo<K>::threads) void bwd_f_kernel(BwdFastArgs A)
     }
 }
 
+// ---- building blocks of P and N ---------------------------------------------------------------------
+__device__ __forceinline__ int pair_index(int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); }
+
+template <int K>
+struct PAcc {  // deferred sums of phase P: lane layers 8 .. 7+kPDpp, register layers K-1 and K
+    float d[Geo<K>::kPDpp][8], r1[4], r2[4];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int j = 0; j < Geo<K>::kPDpp; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) d[j][r] = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r1[q] = r2[q] = 0.0f;
+    }
+};
+struct NAcc {  // deferred sums of phase N: lane layers 4..7, register layers 1..3
+    float d[4][8], r[3][4];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) d[j][q] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[j][q] = 0.0f;
+    }
+};
+
+// layers K..8 transposed on (vx, vg) held in layout P; cp[j] = coefficients of layer 8 + j
+template <int K>
+__device__ __forceinline__ void p_phase(float (&vx)[8], float (&vg)[8], const float (&cp)[K - 7][8], PAcc<K> &acc)
+{
+    reg_acc<2>(acc.r2, vg, vx);  // layer K (register bit 2): first layer of the transposed cascade
+    reg_layer_first<2>(vx, cp[K - 8]);
+    reg_layer_first<2>(vg, cp[K - 8]);
+    reg_acc<1>(acc.r1, vg, vx);  // layer K-1 (register bit 1)
+    reg_layer<1>(vx, cp[K - 9]);
+    reg_layer<1>(vg, cp[K - 9]);
+    if (K == 13) {
+        dpp_acc_xor8(acc.d[Geo<K>::kPDpp - 1], vg, vx);
+        dpp_layer_xor8(vx, cp[K - 10]);
+        dpp_layer_xor8(vg, cp[K - 10]);
+    }
+    dpp_acc_xor7(acc.d[2], vg, vx);
+    dpp_layer_xor7(vx, cp[2]);
+    dpp_layer_xor7(vg, cp[2]);
+    dpp_acc_xor2(acc.d[1], vg, vx);
+    dpp_layer_xor2(vx, cp[1]);
+    dpp_layer_xor2(vg, cp[1]);
+    dpp_acc_xor1(acc.d[0], vg, vx);
+    dpp_layer_xor1(vx, cp[0]);
+    dpp_layer_xor1(vg, cp[0]);
+}
+
+// Coefficients of layers 1..7 for the eight elements a thread holds in layout N: all in registers, or the
+// first kLds layers in LDS (written and read by the same thread).
+struct CoefRegs {
+    float c[7][8];
+    __device__ __forceinline__ void load(const float *fg, int n, int idx)
+    {
+#pragma unroll
+        for (int j = 0; j < 7; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c[j][r] = fg[j * n + idx + r];
+    }
+    template <int J>
+    __device__ __forceinline__ void get(float (&o)[8]) const
+    {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) o[r] = c[J][r];
+    }
+};
+template <int kLds>
+struct CoefSplit {
+    float c[7 - kLds][8];
+    const float4 *tab;  // float4 index (2 j + half) * kSlots + slot: consecutive lanes, consecutive banks
+    int first;
+    static constexpr int kSlots = 512;
+    __device__ __forceinline__ void load(const float *fg, int n, int idx, float *lds_tab, int slot)
+    {
+        tab = (const float4 *)lds_tab;
+        first = slot;
+        float4 *t = (float4 *)lds_tab + first;
+#pragma unroll
+        for (int j = 0; j < kLds; ++j) {
+            t[(2 * j) * kSlots] = *(const float4 *)(fg + j * n + idx);
+            t[(2 * j + 1) * kSlots] = *(const float4 *)(fg + j * n + idx + 4);
+        }
+#pragma unroll
+        for (int j = kLds; j < 7; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c[j - kLds][r] = fg[j * n + idx + r];
+    }
+    template <int J>
+    __device__ __forceinline__ void get(float (&o)[8]) const
+    {
+        if (J < kLds) {
+            int f = first;
+            asm volatile("" : "+v"(f));  // keeps the reads inside the row loop (hoisted, they would spill)
+            const float4 a = tab[f + 2 * J * kSlots], b = tab[f + (2 * J + 1) * kSlots];
+            o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) o[r] = c[(J < kLds ? kLds : J) - kLds][r];
+        }
+    }
+};
+
+// layers 7..1 transposed on (vx, vg) held in layout N; on return vg holds g_0 in deferred units
+template <class C>
+__device__ __forceinline__ void n_phase(float (&vx)[8], float (&vg)[8], const C &cn, NAcc &acc)
+{
+    float c[8];
+    cn.template get<6>(c);
+    dpp_acc_xor8(acc.d[3], vg, vx);  // layer 7
+    dpp_layer_xor8(vx, c);
+    dpp_layer_xor8(vg, c);
+    cn.template get<5>(c);
+    dpp_acc_xor7(acc.d[2], vg, vx);  // layer 6
+    dpp_layer_xor7(vx, c);
+    dpp_layer_xor7(vg, c);
+    cn.template get<4>(c);
+    dpp_acc_xor2(acc.d[1], vg, vx);  // layer 5
+    dpp_layer_xor2(vx, c);
+    dpp_layer_xor2(vg, c);
+    cn.template get<3>(c);
+    dpp_acc_xor1(acc.d[0], vg, vx);  // layer 4
+    dpp_layer_xor1(vx, c);
+    dpp_layer_xor1(vg, c);
+    cn.template get<2>(c);
+    reg_acc<2>(acc.r[2], vg, vx);  // layer 3
+    reg_layer<2>(vx, c);
+    reg_layer<2>(vg, c);
+    cn.template get<1>(c);
+    reg_acc<1>(acc.r[1], vg, vx);  // layer 2
+    reg_layer<1>(vx, c);
+    reg_layer<1>(vg, c);
+    cn.template get<0>(c);
+    reg_acc<0>(acc.r[0], vg, vx);  // layer 1 (x is not needed below it)
+    reg_layer<0>(vg, c);
+}
+
+__device__ __forceinline__ float lane_partner(float v, int j)
+{
+    return j == 0 ? dpp_get<0xB1>(v) : j == 1 ? dpp_get<0x4E>(v) : j == 2 ? dpp_get<0x141>(v) : dpp_get<0x128>(v);
+}
+
+// deferred sums -> dtheta partials of this workgroup (part: its slice, fw: plan table fw_inv)
+template <int K>
+__device__ __forceinline__ void finalize_p(float *part, const PAcc<K> &acc, int idx_p, const float *fw_inv, int first)
+{
+    using G = Geo<K>;
+#pragma unroll
+    for (int J = 1; J <= 2; ++J) {  // register layers
+        const int i = (J == 2) ? K : K - 1;
+        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        int q = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (!(r & (1 << J))) {
+                const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
+                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw[a] * fw[b]);
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), v, first);
+                ++q;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < G::kPDpp; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7, 8
+        const int i = 8 + j;
+        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float mine = acc.d[j][r];
+            const float other = lane_partner(mine, j);
+            const int e = idx_p + p_reg_idx2<K>(r);
+            if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
+                const int b = e | (1 << (i - 1));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]), first);
+            }
+        }
+    }
+}
+
+template <int K>
+__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int first)
+{
+    using G = Geo<K>;
+#pragma unroll
+    for (int J = 0; J < 3; ++J) {  // layers 1..3
+        const int i = J + 1;
+        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        int q = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (!(r & (1 << J))) {
+                const int a = idx + r, b = idx + (r | (1 << J));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), acc.r[J][q] * (fw[a] * fw[b]), first);
+                ++q;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
+        const int i = 4 + j;
+        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const float mine = acc.d[j][r];
+            const float other = lane_partner(mine, j);
+            const int e = idx + r;
+            if (!(e & (1 << (i - 1)))) {
+                const int b = e | (1 << (i - 1));
+                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]), first);
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void load8_f32(const float *p, float (&v)[8])
+{
+    const float4 a = *(const float4 *)p;
+    const float4 b = *((const float4 *)p + 1);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
 // ---- P: layers k..8 transposed on x and g, accumulating their angle gradients -----------------------
 template <typename T, int K>
 __global__ __launch_bounds__(Geo<K>::threads) void bwd_p_kernel(BwdFastArgs A)
@@ -230,62 +459,30 @@ __global__ __launch_bounds__(Geo<K>::threads) void bwd_p_kernel(BwdFastArgs A)
     extern __shared__ float lds[];  // [parity][x row, g row]
     if (plan_is_bad(A)) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int chunk = wave * 64 + lane_chunk(lane);
-    const int idx_n = chunk * 8;
+    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
     const int idx_p = base_p2<K>(wave, lane);
     const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
-    constexpr int nd = G::kPDpp;  // 3 or 4 lane layers: layers 8 .. 7+nd; register layers K-1 (bit 1), K (bit 2)
     float cp[K - 7][8];
 #pragma unroll
     for (int j = 0; j < K - 7; ++j)
 #pragma unroll
         for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_inv[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
-    float acc_d[nd][8], acc_r1[4], acc_r2[4];
-#pragma unroll
-    for (int j = 0; j < nd; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) acc_d[j][r] = 0.0f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc_r1[q] = acc_r2[q] = 0.0f;
-
+    PAcc<K> acc;
+    acc.clear();
     const T *dy = (const T *)A.dy + A.row0 * A.ld_in + idx_n;
     int par = 0;
     for (int64_t row = blockIdx.x; row < A.rows; row += gridDim.x) {
         float *bx = lds + par * 2 * G::kRowFloats, *bg = bx + G::kRowFloats;
         par ^= 1;
         float vx[8], vg[8];
-        {
-            const float4 a = *(const float4 *)(A.xk + row * G::n + idx_n);
-            const float4 b = *((const float4 *)(A.xk + row * G::n + idx_n) + 1);
-            vx[0] = a.x; vx[1] = a.y; vx[2] = a.z; vx[3] = a.w; vx[4] = b.x; vx[5] = b.y; vx[6] = b.z; vx[7] = b.w;
-            unpack8(load8(dy + row * A.ld_in), vg, (const T *)nullptr);
-        }
+        load8_f32(A.xk + row * G::n + idx_n, vx);
+        unpack8(load8(dy + row * A.ld_in), vg, (const T *)nullptr);
         lds_write_n2(bx, an, vx);
         lds_write_n2(bg, an, vg);
         __syncthreads();
         lds_read_p2<K>(bx, ap, vx);
         lds_read_p2<K>(bg, ap, vg);
-        // layer K (register bit 2), layer K-1 (register bit 1)
-        reg_acc<2>(acc_r2, vg, vx);
-        reg_layer_first<2>(vx, cp[K - 8]);
-        reg_layer_first<2>(vg, cp[K - 8]);
-        reg_acc<1>(acc_r1, vg, vx);
-        reg_layer<1>(vx, cp[K - 9]);
-        reg_layer<1>(vg, cp[K - 9]);
-        if (K == 13) {
-            dpp_acc_xor8(acc_d[nd - 1], vg, vx);
-            dpp_layer_xor8(vx, cp[K - 10]);
-            dpp_layer_xor8(vg, cp[K - 10]);
-        }
-        dpp_acc_xor7(acc_d[2], vg, vx);
-        dpp_layer_xor7(vx, cp[2]);
-        dpp_layer_xor7(vg, cp[2]);
-        dpp_acc_xor2(acc_d[1], vg, vx);
-        dpp_layer_xor2(vx, cp[1]);
-        dpp_layer_xor2(vg, cp[1]);
-        dpp_acc_xor1(acc_d[0], vg, vx);
-        dpp_layer_xor1(vx, cp[0]);
-        dpp_layer_xor1(vg, cp[0]);
+        p_phase<K>(vx, vg, cp, acc);
         lds_write_p2<K>(bx, ap, vx);
         lds_write_p2<K>(bg, ap, vg);
         __syncthreads();
@@ -294,46 +491,7 @@ __global__ __launch_bounds__(Geo<K>::threads) void bwd_p_kernel(BwdFastArgs A)
         store8(A.vx7 + row * G::n + idx_n, vx);
         store8(A.vg7 + row * G::n + idx_n, vg);
     }
-
-    // deferred sums -> dtheta partials of this workgroup
-    float *part = A.partial + (size_t)blockIdx.x * (K * (G::n / 2));
-    auto pair_index = [](int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); };
-    {  // register layers
-#pragma unroll
-        for (int J = 1; J <= 2; ++J) {
-            const int i = (J == 2) ? K : K - 1;
-            const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
-            int q = 0;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                if (!(r & (1 << J))) {
-                    const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
-                    const float v = (J == 2 ? acc_r2[q] : acc_r1[q]) * (fw[a] * fw[b]);
-                    put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), v, A.first_chunk);
-                    ++q;
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < nd; ++j) {  // lane layers: layer 8 + j, lane mask 1, 2, 7, 8
-        const int i = 8 + j;
-        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const float mine = acc_d[j][r];
-            const float other = j == 0   ? dpp_get<0xB1>(mine)
-                                : j == 1 ? dpp_get<0x4E>(mine)
-                                : j == 2 ? dpp_get<0x141>(mine)
-                                         : dpp_get<0x128>(mine);
-            const int e = idx_p + p_reg_idx2<K>(r);
-            if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
-                const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]),
-                            A.first_chunk);
-            }
-        }
-    }
+    finalize_p<K>(A.partial + (size_t)blockIdx.x * (K * (G::n / 2)), acc, idx_p, A.fw_inv, A.first_chunk);
 }
 
 // ---- N: layers 7..1 transposed on x and g, accumulating their angle gradients; dx out ----------------
@@ -349,95 +507,121 @@ __global__ __launch_bounds__(kNThreads) void bwd_n_kernel(BwdFastArgs A, int spa
     const int span = blockIdx.x % spans;
     const int slice = blockIdx.x / spans, n_slices = gridDim.x / spans;
     const int idx = span * kNSpan + ((tid & ~15) | lane_chunk(tid & 15)) * 8;  // column of element 0
-    float cn[7][8], d[8];
-#pragma unroll
-    for (int j = 0; j < 7; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) cn[j][r] = A.fg_inv[j * G::n + idx + r];
+    CoefRegs cn;
+    cn.load(A.fg_inv, G::n, idx);
+    float d[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) d[r] = A.fd_inv[idx + r];
-    float acc_d[4][8], acc_r[3][4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) acc_d[j][r] = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 3; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc_r[j][q] = 0.0f;
-
-    auto load_f32 = [&](const float *base, int64_t row, float (&v)[8]) {
-        const float4 a = *(const float4 *)(base + row * G::n + idx);
-        const float4 b = *((const float4 *)(base + row * G::n + idx) + 1);
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    };
+    NAcc acc;
+    acc.clear();
     T *dx = A.dx ? (T *)A.dx + A.row0 * A.ld_out + idx : nullptr;
     for (int64_t row = slice; row < A.rows; row += n_slices) {
         float vx[8], vg[8];
-        load_f32(A.vx7, row, vx);
-        load_f32(A.vg7, row, vg);
-        dpp_acc_xor8(acc_d[3], vg, vx);  // layer 7
-        dpp_layer_xor8(vx, cn[6]);
-        dpp_layer_xor8(vg, cn[6]);
-        dpp_acc_xor7(acc_d[2], vg, vx);  // layer 6
-        dpp_layer_xor7(vx, cn[5]);
-        dpp_layer_xor7(vg, cn[5]);
-        dpp_acc_xor2(acc_d[1], vg, vx);  // layer 5
-        dpp_layer_xor2(vx, cn[4]);
-        dpp_layer_xor2(vg, cn[4]);
-        dpp_acc_xor1(acc_d[0], vg, vx);  // layer 4
-        dpp_layer_xor1(vx, cn[3]);
-        dpp_layer_xor1(vg, cn[3]);
-        reg_acc<2>(acc_r[2], vg, vx);  // layer 3
-        reg_layer<2>(vx, cn[2]);
-        reg_layer<2>(vg, cn[2]);
-        reg_acc<1>(acc_r[1], vg, vx);  // layer 2
-        reg_layer<1>(vx, cn[1]);
-        reg_layer<1>(vg, cn[1]);
-        reg_acc<0>(acc_r[0], vg, vx);  // layer 1 (x is not needed below it)
-        reg_layer<0>(vg, cn[0]);
+        load8_f32(A.vx7 + row * G::n + idx, vx);
+        load8_f32(A.vg7 + row * G::n + idx, vg);
+        n_phase(vx, vg, cn, acc);
         if (dx) {
 #pragma unroll
             for (int r = 0; r < 8; ++r) vg[r] *= d[r];
             store8(dx + row * A.ld_out, vg);
         }
     }
+    finalize_n<K>(A.partial + (size_t)slice * (K * (G::n / 2)), acc, idx, A.fw_inv, A.first_chunk);
+}
 
-    float *part = A.partial + (size_t)slice * (K * (G::n / 2));
-    auto pair_index = [](int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); };
+// ---- PN: both phases in one kernel (k = 12), split over two groups of eight waves --------------------
+// Waves 0..7 run phase P on row t while waves 8..15 run phase N on row t-1; a row changes hands through an
+// LDS area in layout N.  Each group keeps only its own coefficients and sums in registers (the second
+// group also parks the coefficients of its first kPnLdsLayers layers in LDS), which is what lets 1024
+// threads fit the 128-register budget.  Saves the float32 round trip of (x_7, g_7) through memory.
+// Both groups execute the same number of workgroup barriers:
+//   P, row t:   write area A (layout N) | B1 | read A (layout P), layers 12..8, write area H | B2
+//   N, row t-1: read H                  | B1 | layers 7..1, store dx                        | B2
+constexpr int kPnThreads = 1024;
+constexpr int kPnLdsLayers = 4;
+constexpr size_t kPnLdsFloats = 4 * (size_t)Geo<12>::kRowFloats + (1 + kPnLdsLayers) * (size_t)Geo<12>::n;
+
+template <typename T, bool kDx>
+__global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
+{
+    constexpr int K = 12;
+    using G = Geo<K>;
+    extern __shared__ float lds[];
+    if (plan_is_bad(A)) return;
+    const int role = threadIdx.x >> 9;  // uniform per wave
+    const int tid = threadIdx.x & 511, wave = tid >> 6, lane = tid & 63;
+    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
+    const int an = lds_addr2(idx_n);
+    float *hand = lds + 2 * G::kRowFloats;
+    const int64_t mine = A.rows > (int64_t)blockIdx.x ? (A.rows - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    float *part = A.partial + (size_t)blockIdx.x * (K * (G::n / 2));
+    if (role == 0) {
+        const int idx_p = base_p2<K>(wave, lane);
+        const int ap = lds_addr2(idx_p);
+        float cp[K - 7][8];
 #pragma unroll
-    for (int J = 0; J < 3; ++J) {  // layers 1..3
-        const int i = J + 1;
-        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
-        int q = 0;
+        for (int j = 0; j < K - 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            if (!(r & (1 << J))) {
-                const int a = idx + r, b = idx + (r | (1 << J));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), acc_r[J][q] * (fw[a] * fw[b]),
-                            A.first_chunk);
-                ++q;
-            }
+            for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_inv[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
+        PAcc<K> acc;
+        acc.clear();
+        const T *dy = (const T *)A.dy + A.row0 * A.ld_in + idx_n;
+        const float *xk = A.xk + idx_n;
+        float nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        Raw8 ng = {};
+        int64_t row = blockIdx.x;
+        if (mine > 0) {
+            load8_f32(xk + row * G::n, nx);
+            ng = load8(dy + row * A.ld_in);
         }
-    }
+        for (int64_t it = 0; it < mine; ++it, row += gridDim.x) {
+            float vx[8], vg[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
-        const int i = 4 + j;
-        const float *fw = A.fw_inv + (size_t)(i - 1) * G::n;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const float mine = acc_d[j][r];
-            const float other = j == 0   ? dpp_get<0xB1>(mine)
-                                : j == 1 ? dpp_get<0x4E>(mine)
-                                : j == 2 ? dpp_get<0x141>(mine)
-                                         : dpp_get<0x128>(mine);
-            const int e = idx + r;
-            if (!(e & (1 << (i - 1)))) {
-                const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]),
-                            A.first_chunk);
-            }
+            for (int r = 0; r < 8; ++r) vx[r] = nx[r];
+            unpack8(ng, vg, (const T *)nullptr);
+            const int64_t next = it + 1 < mine ? row + gridDim.x : row;  // the last one reads its own row again
+            load8_f32(xk + next * G::n, nx);
+            ng = load8(dy + next * A.ld_in);
+            lds_write_n2(lds, an, vx);
+            lds_write_n2(lds + G::kRowFloats, an, vg);
+            __syncthreads();  // B1
+            lds_read_p2<K>(lds, ap, vx);
+            lds_read_p2<K>(lds + G::kRowFloats, ap, vg);
+            p_phase<K>(vx, vg, cp, acc);
+            lds_write_p2<K>(hand, ap, vx);
+            lds_write_p2<K>(hand + G::kRowFloats, ap, vg);
+            __syncthreads();  // B2
         }
+        __syncthreads();  // the other group's last row
+        __syncthreads();
+        finalize_p<K>(part, acc, idx_p, A.fw_inv, A.first_chunk);
+    } else {
+        float *dtab = lds + 4 * G::kRowFloats;  // tables written and read by the same thread
+        CoefSplit<kPnLdsLayers> cn;
+        cn.load(A.fg_inv, G::n, idx_n, dtab + G::n, tid);
+        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + idx_n);
+        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + idx_n + 4);
+        NAcc acc;
+        acc.clear();
+        T *dx = (T *)A.dx + A.row0 * A.ld_out + idx_n;  // used only if kDx
+        __syncthreads();  // the other group's first row
+        __syncthreads();
+        int64_t row = blockIdx.x;
+        for (int64_t it = 0; it < mine; ++it, row += gridDim.x) {
+            float vx[8], vg[8];
+            lds_read_n2(hand, an, vx);
+            lds_read_n2(hand + G::kRowFloats, an, vg);
+            __syncthreads();  // B1: the reads above are complete before the other group refills the area
+            n_phase(vx, vg, cn, acc);
+            if (kDx) {
+                const float4 da = ((const float4 *)dtab)[tid], db = ((const float4 *)dtab)[512 + tid];
+                vg[0] *= da.x; vg[1] *= da.y; vg[2] *= da.z; vg[3] *= da.w;
+                vg[4] *= db.x; vg[5] *= db.y; vg[6] *= db.z; vg[7] *= db.w;
+                store8(dx + row * A.ld_out, vg);
+            }
+            __syncthreads();  // B2
+        }
+        finalize_n<K>(part, acc, idx_n, A.fw_inv, A.first_chunk);
     }
 }
 
@@ -454,11 +638,14 @@ __global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__re
 }
 
 // ---- host side -----------------------------------------------------------------------------------
-static int bwd_fast_slices(int k) { return k == 12 ? 512 : 256; }
-// Rows per chunk: 2^28 elements, i.e. 3 GiB of float32 intermediates at most.  Small chunks that would
-// stay in the last-level cache measured slower: every launch re-reads the coefficients and rewrites the
-// partial slices, which only amortises over many rows per workgroup.
-static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (28 - k); }
+static int bwd_fast_slices(int k) { return 256; }  // one per compute unit (k = 12: one fused workgroup each)
+static constexpr int kBwdFGrid = 512;
+// Rows per chunk bound the float32 intermediates in the workspace: x_k alone for k = 12 (2^30 elements,
+// 4 GiB), x_k, x_7 and g_7 for k = 13 (2^28 elements each, 3 GiB).  Small chunks that would stay in the
+// last-level cache measured slower: every launch re-reads the coefficients and rewrites the partial
+// slices, which only amortises over many rows per workgroup.
+static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << ((k == 12 ? 30 : 28) - k); }
+static int bwd_fast_intermediates(int k) { return k == 12 ? 1 : 3; }
 
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
 {
@@ -473,7 +660,7 @@ size_t bwd_fast_workspace_bytes(const Shape &s)
 {
     const size_t angles = (size_t)s.k * (s.n / 2);
     const size_t chunk = (size_t)(s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k));
-    return align256((size_t)bwd_fast_slices(s.k) * angles * sizeof(float)) + 3 * align256(chunk * s.n * sizeof(float));
+    return align256((size_t)bwd_fast_slices(s.k) * angles * sizeof(float)) + bwd_fast_intermediates(s.k) * align256(chunk * s.n * sizeof(float));
 }
 
 template <typename T, int K>
@@ -487,22 +674,36 @@ static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta
     A.partial = (float *)ws;
     char *p = ws + align256((size_t)slices * angles * sizeof(float));
     A.xk = (float *)p;
-    A.vx7 = (float *)(p + inter);
-    A.vg7 = (float *)(p + 2 * inter);
+    A.vx7 = K == 12 ? nullptr : (float *)(p + inter);  // k = 12 keeps (x_7, g_7) on chip
+    A.vg7 = K == 12 ? nullptr : (float *)(p + 2 * inter);
     const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_p = 4 * G::kRowFloats * sizeof(float);
     hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)bwd_p_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_p);
     if (e != hipSuccess) return e;
     const int spans = G::n / kNSpan;
+    const size_t lds_pn = kPnLdsFloats * sizeof(float);
+    if (K == 12) {
+        e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
+        if (e != hipSuccess) return e;
+    }
     for (int64_t r0 = 0; r0 < s.rows; r0 += chunk_rows) {
         A.row0 = r0;
         A.rows = s.rows - r0 < chunk_rows ? s.rows - r0 : chunk_rows;
         A.first_chunk = (r0 == 0);
         // every slice must be written by the first chunk, so the grids do not shrink with the row count
-        hipLaunchKernelGGL((bwd_f_kernel<T, K>), dim3(slices), dim3(G::threads), lds_f, stream, A);
-        hipLaunchKernelGGL((bwd_p_kernel<T, K>), dim3(slices), dim3(G::threads), lds_p, stream, A);
-        hipLaunchKernelGGL((bwd_n_kernel<T, K>), dim3(slices * spans), dim3(kNThreads), 0, stream, A, spans);
+        hipLaunchKernelGGL((bwd_f_kernel<T, K>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
+        if (K == 12) {
+            if (A.dx)
+                hipLaunchKernelGGL((bwd_pn_kernel<T, true>), dim3(slices), dim3(kPnThreads), lds_pn, stream, A);
+            else
+                hipLaunchKernelGGL((bwd_pn_kernel<T, false>), dim3(slices), dim3(kPnThreads), lds_pn, stream, A);
+        } else {
+            hipLaunchKernelGGL((bwd_p_kernel<T, K>), dim3(slices), dim3(G::threads), lds_p, stream, A);
+            hipLaunchKernelGGL((bwd_n_kernel<T, K>), dim3(slices * spans), dim3(kNThreads), 0, stream, A, spans);
+        }
     }
     const unsigned blocks = (unsigned)((angles + 255) / 256);
     hipLaunchKernelGGL(bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, angles, slices,
