@@ -104,8 +104,8 @@ def cpu_baseline(sample_rows: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rows", type=int, default=262144, help="rows of the batch (default: the full workload)")
     ap.add_argument("--cpu-rows", type=int, default=262144, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the decode / per-head / n=8192 backward figures")
@@ -183,7 +183,7 @@ def main() -> int:
     for name in order:
         ts = [a.elapsed_time(b) for a, b in events[name]]
         avg = sum(ts) / len(ts)
-        rec = {"avg_ms": round(avg, 4)}
+        rec = {"avg_ms": round(avg, 4), "median_ms": round(sorted(ts)[len(ts) // 2], 4)}
         if name != "plan_build":
             bpr = alg_bytes_per_row(name, n, heads, itemsize, bits, group, 2)
             fpr = alg_flops_per_row(name, n, heads)
