@@ -2,26 +2,35 @@
 // dtheta[i][p] = sum over rows of  g_i[b] x_i[a] - g_i[a] x_i[b]   (x_i, g_i at the output of layer i;
 // paper, "Gradient Flow Through Butterfly Layers": d y_a / d theta = -y_b, d y_b / d theta = y_a).
 //
-// Registers cannot hold the coefficients of all layers, the dtheta accumulators of all layers and
-// two rows at once, so the pass is cut at layer 7 into three kernels that hand float32 intermediates
-// to each other through the workspace; a batch is processed in row chunks to bound that workspace:
-//
-//   F: x -> x_k            forward cascade (same structure as the forward kernels), float32 out
-//   P: (x_k, dy) -> layers k..8 transposed on BOTH vectors with the same coefficients, accumulating
-//      the angle gradients of those layers; writes (x_7, g_7) in scale-deferred units, float32
-//   N: (x_7, g_7) -> layers 7..1 transposed on both, accumulating their angle gradients; dx out
-//
-// Orthogonality makes stored activations unnecessary: x_{i-1} = B_i^T x_i.  Both x and g start the
-// transposed cascade with scale 1, so they share the scale-deferred coefficients and, before layer i,
-// the scales D_i[e] (plan table fw_inv).  Sums are accumulated in deferred units,
+// Orthogonality makes stored activations unnecessary: x_{i-1} = B_i^T x_i.  The forward state is
+// recomputed once, then the transposed cascade runs on x and g together.  Both start it with scale 1, so
+// they share the scale-deferred coefficients and, before layer i, the scales D_i[e] (plan table fw_inv).
+// Sums are accumulated in deferred units,
 //   acc += v_g[b] v_x[a] - v_g[a] v_x[b],   dtheta = D_i[a] D_i[b] acc,
 // the factor being applied once per workgroup at the end.  For a layer that pairs lanes each lane keeps
 // the partial sum of its own element (one v_fmac_f32 with a DPP operand per element); the two lanes'
 // sums are combined at the end.
 //
-// Every workgroup owns one slice of `partial` ([slices][k*n/2]); a slice entry is written by exactly
-// one thread, chunks add to it in stream order, and a last kernel sums the slices in double in a fixed
-// order: no atomics, the result does not depend on scheduling.
+// All kernels work on 4096 points with 8 points per thread.  Registers cannot hold the coefficients of
+// all layers in both directions plus the sums, so the pass is two kernels, and the second one splits
+// its work over two groups of waves:
+//
+//   F:  x -> forward cascade of layers 1..12, float32 result into the workspace
+//   PN: waves 0..7  (phase P): layers 12..8 transposed on (x, g), sums of those layers
+//       waves 8..15 (phase N): layers 7..1 transposed on the row that phase P finished one step
+//                              earlier (handed over through LDS), sums of those layers, dx out
+//
+// n = 8192: layers 1..12 act inside each half of a row, only layer 13 couples the halves.  A workgroup
+// takes one half of its rows.  F stops before layer 13 and writes the state in the units the transposed
+// cascade has after its first layer (plan table fm_fwd); phase P reads both halves of dy, forms its own
+// half of g_12 and, for the sum of layer 13, the other half as well:
+//   dtheta_13[p] = sum over rows of  g_12[b] x_12[a] - g_12[a] x_12[b]
+// (the same expression one layer further down: rotating both vectors of a pair leaves it unchanged),
+// the lower-half workgroup contributing the first term and the upper-half one the second.
+//
+// Every workgroup owns one slice of `partial`; a slice entry is written by exactly one thread, chunks
+// of rows add to it in stream order, and a last kernel sums the slices in double in a fixed order: no
+// atomics, the result does not depend on scheduling.
 //
 // All kernels exit at once when the plan flags the scale-deferred tables as unusable; the generic
 // backward kernel, launched behind them with the opposite condition, then does the work.
@@ -138,13 +147,14 @@ __device__ __forceinline__ float dpp_get(float v)
 struct BwdFastArgs {
     const void *x, *dy;
     void *dx;
-    float *xk, *vx7, *vg7;  // chunk intermediates, [chunk_rows][n] float32
-    float *partial;         // [slices][k * n / 2]
-    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv, *fw_inv;
+    float *xk;       // chunk intermediate, [chunk_rows][n] float32
+    float *partial;  // [slices][slice_floats]
+    const float *fg_fwd, *fd_fwd, *fm_fwd, *fg_inv, *fd_inv, *fw_inv;
     const int *bad_fwd, *bad_inv;
     int64_t row0, rows;  // this chunk: rows [row0, row0 + rows) of the batch
     int64_t ld_in, ld_out;
-    int first_chunk;     // != 0: slices are overwritten, else added to
+    int64_t slice_floats;
+    int first_chunk;  // != 0: slices are overwritten, else added to
 };
 
 __device__ __forceinline__ bool plan_is_bad(const BwdFastArgs &A) { return (*A.bad_fwd | *A.bad_inv) != 0; }
@@ -157,42 +167,64 @@ __device__ __forceinline__ void put_partial(float *p, float v, int first)
         *p += v;
 }
 
-// ---- F: forward cascade to float32 ----------------------------------------------------------------
-template <typename T, int K>
-__global__ __launch_bounds__(Geo<K>::threads) void bwd_f_kernel(BwdFastArgs A)
+constexpr int K = 12;  // layers inside one 4096-point block
+using G = Geo<K>;
+
+// Which rows and which part of them a workgroup takes.  kHalf (n = 8192): blocks 16 j + 8 h + c take half h
+// of the rows of slot 8 j + c, so that the two workgroups of a slot, which read the same dy rows at about
+// the same time, sit on the same die (blocks go round the eight dies) and share its L2.
+template <bool kHalf>
+struct Part {
+    int half, slot, nslots, c0;
+    static constexpr int stride = kHalf ? 2 * G::n : G::n;  // row length of the tables and of x_k
+    __device__ __forceinline__ Part()
+    {
+        half = kHalf ? (blockIdx.x >> 3) & 1 : 0;
+        slot = kHalf ? (int)((blockIdx.x & 7) | ((blockIdx.x >> 4) << 3)) : (int)blockIdx.x;
+        nslots = kHalf ? (int)(gridDim.x >> 1) : (int)gridDim.x;
+        c0 = half * G::n;
+    }
+};
+
+// ---- F: forward cascade of layers 1..12 to float32 ------------------------------------------------------
+template <typename T, bool kHalf>
+__global__ __launch_bounds__(G::threads) void bwd_f_kernel(BwdFastArgs A)
 {
-    using G = Geo<K>;
     extern __shared__ float lds[];  // [row buffer][output scales]
     if (plan_is_bad(A)) return;
+    const Part<kHalf> part;
+    constexpr int ts = Part<kHalf>::stride;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int chunk = wave * 64 + lane_chunk(lane);
-    const int idx_n = chunk * 8;
+    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
     const int idx_p = base_p2<K>(wave, lane);
     const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
     float *buf = lds, *dtab = lds + G::kRowFloats;
+    const float *fg = A.fg_fwd + part.c0;
     float cn[7][8], cp[K - 7][8];
 #pragma unroll
     for (int j = 0; j < 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) cn[j][r] = A.fg_fwd[j * G::n + idx_n + r];
+        for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * ts + idx_n + r];
 #pragma unroll
     for (int j = 0; j < K - 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_fwd[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
+        for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * ts + idx_p + p_reg_idx2<K>(r)];
     {
+        const float *scale = (kHalf ? A.fm_fwd : A.fd_fwd) + part.c0;
         float d[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) d[r] = A.fd_fwd[idx_n + r];
+        for (int r = 0; r < 8; ++r) d[r] = scale[idx_n + r];
         lds_write_n2(dtab, an, d);
     }
-    const T *x = (const T *)A.x + A.row0 * A.ld_in + idx_n;
-    int64_t row = blockIdx.x;
+    const T *x = (const T *)A.x + A.row0 * A.ld_in + part.c0 + idx_n;
+    float *xk = A.xk + part.c0 + idx_n;
+    int64_t row = part.slot;
     if (row >= A.rows) return;
     Raw8 raw = load8(x + row * A.ld_in);
-    for (; row < A.rows; row += gridDim.x) {
+    for (; row < A.rows; row += part.nslots) {
         float u[8];
         unpack8(raw, u, (const T *)nullptr);
-        const int64_t next = row + gridDim.x;
+        const int64_t next = row + part.nslots;
         if (next < A.rows) raw = load8(x + next * A.ld_in);
         reg_layer_first<0>(u, cn[0]);
         reg_layer<1>(u, cn[1]);
@@ -208,9 +240,8 @@ __global__ __launch_bounds__(Geo<K>::threads) void bwd_f_kernel(BwdFastArgs A)
         dpp_layer_xor1(u, cp[0]);
         dpp_layer_xor2(u, cp[1]);
         dpp_layer_xor7(u, cp[2]);
-        if (K == 13) dpp_layer_xor8(u, cp[K - 10]);
-        reg_layer<1>(u, cp[K - 9]);
-        reg_layer<2>(u, cp[K - 8]);
+        reg_layer<1>(u, cp[3]);
+        reg_layer<2>(u, cp[4]);
         lds_write_p2<K>(buf, ap, u);
         __syncthreads();
         lds_read_n2(buf, an, u);
@@ -218,20 +249,19 @@ __global__ __launch_bounds__(Geo<K>::threads) void bwd_f_kernel(BwdFastArgs A)
         lds_read_n2(dtab, an, d);
 #pragma unroll
         for (int r = 0; r < 8; ++r) u[r] *= d[r];
-        store8(A.xk + row * G::n + idx_n, u);
+        store8(xk + row * ts, u);
     }
 }
 
-// ---- building blocks of P and N ---------------------------------------------------------------------
+// ---- building blocks of PN ------------------------------------------------------------------------------
 __device__ __forceinline__ int pair_index(int a, int i) { return ((a >> i) << (i - 1)) | (a & ((1 << (i - 1)) - 1)); }
 
-template <int K>
-struct PAcc {  // deferred sums of phase P: lane layers 8 .. 7+kPDpp, register layers K-1 and K
-    float d[Geo<K>::kPDpp][8], r1[4], r2[4];
+struct PAcc {  // deferred sums of phase P: lane layers 8..10, register layers 11 and 12
+    float d[3][8], r1[4], r2[4];
     __device__ __forceinline__ void clear()
     {
 #pragma unroll
-        for (int j = 0; j < Geo<K>::kPDpp; ++j)
+        for (int j = 0; j < 3; ++j)
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[j][r] = 0.0f;
 #pragma unroll
@@ -253,70 +283,55 @@ struct NAcc {  // deferred sums of phase N: lane layers 4..7, register layers 1.
     }
 };
 
-// layers K..8 transposed on (vx, vg) held in layout P; cp[j] = coefficients of layer 8 + j
-template <int K>
-__device__ __forceinline__ void p_phase(float (&vx)[8], float (&vg)[8], const float (&cp)[K - 7][8], PAcc<K> &acc)
+// layers 12..8 transposed on (vx, vg) held in layout P; cp[j] = coefficients of layer 8 + j.  kFirst: layer
+// 12 is the first layer of the transposed cascade (scales still 1).
+template <bool kFirst>
+__device__ __forceinline__ void p_phase(float (&vx)[8], float (&vg)[8], const float (&cp)[5][8], PAcc &acc)
 {
-    reg_acc<2>(acc.r2, vg, vx);  // layer K (register bit 2): first layer of the transposed cascade
-    reg_layer_first<2>(vx, cp[K - 8]);
-    reg_layer_first<2>(vg, cp[K - 8]);
-    reg_acc<1>(acc.r1, vg, vx);  // layer K-1 (register bit 1)
-    reg_layer<1>(vx, cp[K - 9]);
-    reg_layer<1>(vg, cp[K - 9]);
-    if (K == 13) {
-        dpp_acc_xor8(acc.d[Geo<K>::kPDpp - 1], vg, vx);
-        dpp_layer_xor8(vx, cp[K - 10]);
-        dpp_layer_xor8(vg, cp[K - 10]);
+    reg_acc<2>(acc.r2, vg, vx);  // layer 12 (register bit 2)
+    if (kFirst) {
+        reg_layer_first<2>(vx, cp[4]);
+        reg_layer_first<2>(vg, cp[4]);
+    } else {
+        reg_layer<2>(vx, cp[4]);
+        reg_layer<2>(vg, cp[4]);
     }
-    dpp_acc_xor7(acc.d[2], vg, vx);
+    reg_acc<1>(acc.r1, vg, vx);  // layer 11 (register bit 1)
+    reg_layer<1>(vx, cp[3]);
+    reg_layer<1>(vg, cp[3]);
+    dpp_acc_xor7(acc.d[2], vg, vx);  // layer 10
     dpp_layer_xor7(vx, cp[2]);
     dpp_layer_xor7(vg, cp[2]);
-    dpp_acc_xor2(acc.d[1], vg, vx);
+    dpp_acc_xor2(acc.d[1], vg, vx);  // layer 9
     dpp_layer_xor2(vx, cp[1]);
     dpp_layer_xor2(vg, cp[1]);
-    dpp_acc_xor1(acc.d[0], vg, vx);
+    dpp_acc_xor1(acc.d[0], vg, vx);  // layer 8
     dpp_layer_xor1(vx, cp[0]);
     dpp_layer_xor1(vg, cp[0]);
 }
 
-// Coefficients of layers 1..7 for the eight elements a thread holds in layout N: all in registers, or the
-// first kLds layers in LDS (written and read by the same thread).
-struct CoefRegs {
-    float c[7][8];
-    __device__ __forceinline__ void load(const float *fg, int n, int idx)
-    {
-#pragma unroll
-        for (int j = 0; j < 7; ++j)
-#pragma unroll
-            for (int r = 0; r < 8; ++r) c[j][r] = fg[j * n + idx + r];
-    }
-    template <int J>
-    __device__ __forceinline__ void get(float (&o)[8]) const
-    {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) o[r] = c[J][r];
-    }
-};
+// Coefficients of layers 1..7 for the eight points a thread holds in layout N: the first kLds layers in
+// LDS (written and read by the same thread), the others in registers.
 template <int kLds>
 struct CoefSplit {
     float c[7 - kLds][8];
     const float4 *tab;  // float4 index (2 j + half) * kSlots + slot: consecutive lanes, consecutive banks
     int first;
     static constexpr int kSlots = 512;
-    __device__ __forceinline__ void load(const float *fg, int n, int idx, float *lds_tab, int slot)
+    __device__ __forceinline__ void load(const float *fg, int stride, int idx, float *lds_tab, int slot)
     {
         tab = (const float4 *)lds_tab;
         first = slot;
         float4 *t = (float4 *)lds_tab + first;
 #pragma unroll
         for (int j = 0; j < kLds; ++j) {
-            t[(2 * j) * kSlots] = *(const float4 *)(fg + j * n + idx);
-            t[(2 * j + 1) * kSlots] = *(const float4 *)(fg + j * n + idx + 4);
+            t[(2 * j) * kSlots] = *(const float4 *)(fg + j * stride + idx);
+            t[(2 * j + 1) * kSlots] = *(const float4 *)(fg + j * stride + idx + 4);
         }
 #pragma unroll
         for (int j = kLds; j < 7; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) c[j - kLds][r] = fg[j * n + idx + r];
+            for (int r = 0; r < 8; ++r) c[j - kLds][r] = fg[j * stride + idx + r];
     }
     template <int J>
     __device__ __forceinline__ void get(float (&o)[8]) const
@@ -372,30 +387,30 @@ __device__ __forceinline__ float lane_partner(float v, int j)
     return j == 0 ? dpp_get<0xB1>(v) : j == 1 ? dpp_get<0x4E>(v) : j == 2 ? dpp_get<0x141>(v) : dpp_get<0x128>(v);
 }
 
-// deferred sums -> dtheta partials of this workgroup (part: its slice, fw: plan table fw_inv)
-template <int K>
-__device__ __forceinline__ void finalize_p(float *part, const PAcc<K> &acc, int idx_p, const float *fw_inv, int first)
+// Deferred sums -> dtheta partials of this workgroup.  part: its slice; fw: plan table fw_inv at this block's
+// first column, rows `stride` apart; c0: that column; a slice holds stride / 2 angles per layer.
+__device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx_p, const float *fw_inv, int stride, int c0,
+                                           int first)
 {
-    using G = Geo<K>;
 #pragma unroll
     for (int J = 1; J <= 2; ++J) {  // register layers
         const int i = (J == 2) ? K : K - 1;
-        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        const float *fw = fw_inv + (size_t)(i - 1) * stride;
         int q = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
                 const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw[a] * fw[b]);
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), v, first);
+                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + a, i), v, first);
                 ++q;
             }
         }
     }
 #pragma unroll
-    for (int j = 0; j < G::kPDpp; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7, 8
+    for (int j = 0; j < 3; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7
         const int i = 8 + j;
-        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        const float *fw = fw_inv + (size_t)(i - 1) * stride;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const float mine = acc.d[j][r];
@@ -403,26 +418,25 @@ __device__ __forceinline__ void finalize_p(float *part, const PAcc<K> &acc, int 
             const int e = idx_p + p_reg_idx2<K>(r);
             if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + e, i), (mine - other) * (fw[e] * fw[b]), first);
             }
         }
     }
 }
 
-template <int K>
-__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int first)
+__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int stride, int c0,
+                                           int first)
 {
-    using G = Geo<K>;
 #pragma unroll
     for (int J = 0; J < 3; ++J) {  // layers 1..3
         const int i = J + 1;
-        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        const float *fw = fw_inv + (size_t)(i - 1) * stride;
         int q = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx + r, b = idx + (r | (1 << J));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(a, i), acc.r[J][q] * (fw[a] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + a, i), acc.r[J][q] * (fw[a] * fw[b]), first);
                 ++q;
             }
         }
@@ -430,7 +444,7 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
 #pragma unroll
     for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
         const int i = 4 + j;
-        const float *fw = fw_inv + (size_t)(i - 1) * G::n;
+        const float *fw = fw_inv + (size_t)(i - 1) * stride;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const float mine = acc.d[j][r];
@@ -438,7 +452,7 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
             const int e = idx + r;
             if (!(e & (1 << (i - 1)))) {
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (G::n / 2) + pair_index(e, i), (mine - other) * (fw[e] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + e, i), (mine - other) * (fw[e] * fw[b]), first);
             }
         }
     }
@@ -451,163 +465,122 @@ __device__ __forceinline__ void load8_f32(const float *p, float (&v)[8])
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
-// ---- P: layers k..8 transposed on x and g, accumulating their angle gradients -----------------------
-template <typename T, int K>
-__global__ __launch_bounds__(Geo<K>::threads) void bwd_p_kernel(BwdFastArgs A)
-{
-    using G = Geo<K>;
-    extern __shared__ float lds[];  // [parity][x row, g row]
-    if (plan_is_bad(A)) return;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
-    const int idx_p = base_p2<K>(wave, lane);
-    const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
-    float cp[K - 7][8];
-#pragma unroll
-    for (int j = 0; j < K - 7; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_inv[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
-    PAcc<K> acc;
-    acc.clear();
-    const T *dy = (const T *)A.dy + A.row0 * A.ld_in + idx_n;
-    int par = 0;
-    for (int64_t row = blockIdx.x; row < A.rows; row += gridDim.x) {
-        float *bx = lds + par * 2 * G::kRowFloats, *bg = bx + G::kRowFloats;
-        par ^= 1;
-        float vx[8], vg[8];
-        load8_f32(A.xk + row * G::n + idx_n, vx);
-        unpack8(load8(dy + row * A.ld_in), vg, (const T *)nullptr);
-        lds_write_n2(bx, an, vx);
-        lds_write_n2(bg, an, vg);
-        __syncthreads();
-        lds_read_p2<K>(bx, ap, vx);
-        lds_read_p2<K>(bg, ap, vg);
-        p_phase<K>(vx, vg, cp, acc);
-        lds_write_p2<K>(bx, ap, vx);
-        lds_write_p2<K>(bg, ap, vg);
-        __syncthreads();
-        lds_read_n2(bx, an, vx);
-        lds_read_n2(bg, an, vg);
-        store8(A.vx7 + row * G::n + idx_n, vx);
-        store8(A.vg7 + row * G::n + idx_n, vg);
-    }
-    finalize_p<K>(A.partial + (size_t)blockIdx.x * (K * (G::n / 2)), acc, idx_p, A.fw_inv, A.first_chunk);
-}
-
-// ---- N: layers 7..1 transposed on x and g, accumulating their angle gradients; dx out ----------------
-constexpr int kNThreads = 256;
-constexpr int kNSpan = kNThreads * 8;
-
-template <typename T, int K>
-__global__ __launch_bounds__(kNThreads) void bwd_n_kernel(BwdFastArgs A, int spans)
-{
-    using G = Geo<K>;
-    if (plan_is_bad(A)) return;
-    const int tid = threadIdx.x;
-    const int span = blockIdx.x % spans;
-    const int slice = blockIdx.x / spans, n_slices = gridDim.x / spans;
-    const int idx = span * kNSpan + ((tid & ~15) | lane_chunk(tid & 15)) * 8;  // column of element 0
-    CoefRegs cn;
-    cn.load(A.fg_inv, G::n, idx);
-    float d[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) d[r] = A.fd_inv[idx + r];
-    NAcc acc;
-    acc.clear();
-    T *dx = A.dx ? (T *)A.dx + A.row0 * A.ld_out + idx : nullptr;
-    for (int64_t row = slice; row < A.rows; row += n_slices) {
-        float vx[8], vg[8];
-        load8_f32(A.vx7 + row * G::n + idx, vx);
-        load8_f32(A.vg7 + row * G::n + idx, vg);
-        n_phase(vx, vg, cn, acc);
-        if (dx) {
-#pragma unroll
-            for (int r = 0; r < 8; ++r) vg[r] *= d[r];
-            store8(dx + row * A.ld_out, vg);
-        }
-    }
-    finalize_n<K>(A.partial + (size_t)slice * (K * (G::n / 2)), acc, idx, A.fw_inv, A.first_chunk);
-}
-
-// ---- PN: both phases in one kernel (k = 12), split over two groups of eight waves --------------------
+// ---- PN: the transposed cascade, split over two groups of eight waves -----------------------------------
 // Waves 0..7 run phase P on row t while waves 8..15 run phase N on row t-1; a row changes hands through an
 // LDS area in layout N.  Each group keeps only its own coefficients and sums in registers (the second
 // group also parks the coefficients of its first kPnLdsLayers layers in LDS), which is what lets 1024
-// threads fit the 128-register budget.  Saves the float32 round trip of (x_7, g_7) through memory.
-// Both groups execute the same number of workgroup barriers:
+// threads fit the 128-register budget.  Both groups execute the same number of workgroup barriers:
 //   P, row t:   write area A (layout N) | B1 | read A (layout P), layers 12..8, write area H | B2
 //   N, row t-1: read H                  | B1 | layers 7..1, store dx                        | B2
+// A slice of `partial` holds k n / 2 sums in dtheta order; for n = 8192 another 4096 follow, the
+// upper-half workgroup's (negative) share of layer 13.
 constexpr int kPnThreads = 1024;
 constexpr int kPnLdsLayers = 4;
-constexpr size_t kPnLdsFloats = 4 * (size_t)Geo<12>::kRowFloats + (1 + kPnLdsLayers) * (size_t)Geo<12>::n;
+constexpr size_t kPnLdsFloats = 4 * (size_t)G::kRowFloats + (1 + kPnLdsLayers) * (size_t)G::n;
 
-template <typename T, bool kDx>
+template <typename T, bool kDx, bool kHalf>
 __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
 {
-    constexpr int K = 12;
-    using G = Geo<K>;
     extern __shared__ float lds[];
     if (plan_is_bad(A)) return;
+    const Part<kHalf> pt;
+    constexpr int ts = Part<kHalf>::stride;
     const int role = threadIdx.x >> 9;  // uniform per wave
     const int tid = threadIdx.x & 511, wave = tid >> 6, lane = tid & 63;
     const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
     const int an = lds_addr2(idx_n);
     float *hand = lds + 2 * G::kRowFloats;
-    const int64_t mine = A.rows > (int64_t)blockIdx.x ? (A.rows - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
-    float *part = A.partial + (size_t)blockIdx.x * (K * (G::n / 2));
+    const int64_t mine = A.rows > (int64_t)pt.slot ? (A.rows - pt.slot + pt.nslots - 1) / pt.nslots : 0;
+    float *part = A.partial + (size_t)pt.slot * A.slice_floats;
+    const float *fg = A.fg_inv + pt.c0, *fw = A.fw_inv + pt.c0;
     if (role == 0) {
         const int idx_p = base_p2<K>(wave, lane);
         const int ap = lds_addr2(idx_p);
-        float cp[K - 7][8];
+        float cp[5][8];
 #pragma unroll
-        for (int j = 0; j < K - 7; ++j)
+        for (int j = 0; j < 5; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cp[j][r] = A.fg_inv[(7 + j) * G::n + idx_p + p_reg_idx2<K>(r)];
-        PAcc<K> acc;
-        acc.clear();
-        const T *dy = (const T *)A.dy + A.row0 * A.ld_in + idx_n;
-        const float *xk = A.xk + idx_n;
-        float nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        Raw8 ng = {};
-        int64_t row = blockIdx.x;
-        if (mine > 0) {
-            load8_f32(xk + row * G::n, nx);
-            ng = load8(dy + row * A.ld_in);
+            for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * ts + idx_p + p_reg_idx2<K>(r)];
+        float c13[8], acc13[8];  // kHalf only: layer 13 in layout N (it pairs column e with e + 4096)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            c13[r] = kHalf ? fg[12 * ts + idx_n + r] : 0.0f;
+            acc13[r] = 0.0f;
         }
-        for (int64_t it = 0; it < mine; ++it, row += gridDim.x) {
+        PAcc acc;
+        acc.clear();
+        // uniform row pointers + 32-bit per-thread byte offsets: the loads take their base from scalar
+        // registers and no 64-bit per-thread pointer stays live across the loop
+        const T *dy = (const T *)A.dy + A.row0 * A.ld_in + pt.c0;
+        const T *dyo = (const T *)A.dy + A.row0 * A.ld_in + (pt.c0 ^ G::n);  // the other half
+        const float *xk = A.xk + pt.c0;
+        auto fetch = [&](int64_t r, float(&ox)[8], Raw8 &og, Raw8 &ogo) {
+            uint32_t offx = (uint32_t)idx_n * 4u, offg = (uint32_t)idx_n * (uint32_t)sizeof(T);
+            asm volatile("" : "+v"(offx), "+v"(offg));
+            load8_f32((const float *)((const char *)(xk + r * ts) + offx), ox);
+            og = load8((const T *)((const char *)(dy + r * A.ld_in) + offg));
+            if (kHalf) ogo = load8((const T *)((const char *)(dyo + r * A.ld_in) + offg));
+        };
+        float nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        Raw8 ng = {}, ngo = {};
+        int64_t row = pt.slot;
+        if (mine > 0) fetch(row, nx, ng, ngo);
+        for (int64_t it = 0; it < mine; ++it, row += pt.nslots) {
             float vx[8], vg[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) vx[r] = nx[r];
             unpack8(ng, vg, (const T *)nullptr);
-            const int64_t next = it + 1 < mine ? row + gridDim.x : row;  // the last one reads its own row again
-            load8_f32(xk + next * G::n, nx);
-            ng = load8(dy + next * A.ld_in);
+            if (kHalf) {
+                // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
+                // (its coefficient is the negative of this half's: both scales are still 1)
+                float go[8];
+                unpack8(ngo, go, (const T *)nullptr);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float other12 = __builtin_fmaf(-c13[r], vg[r], go[r]);
+                    acc13[r] = __builtin_fmaf(other12, vx[r], acc13[r]);
+                    vg[r] = __builtin_fmaf(c13[r], go[r], vg[r]);
+                }
+            }
+            const int64_t next = it + 1 < mine ? row + pt.nslots : row;  // the last one reads its own row again
+            fetch(next, nx, ng, ngo);
             lds_write_n2(lds, an, vx);
             lds_write_n2(lds + G::kRowFloats, an, vg);
             __syncthreads();  // B1
             lds_read_p2<K>(lds, ap, vx);
             lds_read_p2<K>(lds + G::kRowFloats, ap, vg);
-            p_phase<K>(vx, vg, cp, acc);
+            p_phase<!kHalf>(vx, vg, cp, acc);
             lds_write_p2<K>(hand, ap, vx);
             lds_write_p2<K>(hand + G::kRowFloats, ap, vg);
             __syncthreads();  // B2
         }
         __syncthreads();  // the other group's last row
         __syncthreads();
-        finalize_p<K>(part, acc, idx_p, A.fw_inv, A.first_chunk);
+        finalize_p(part, acc, idx_p, fw, ts, pt.c0, A.first_chunk);
+        if (kHalf) {
+            // sum of layer 13 = (scale after the layer)^2 * deferred sum; the lower half's share goes to the
+            // layer's place in the slice, the upper half's, negated, behind the slice's regular part
+            float *dst = part + (size_t)(pt.half ? 13 : 12) * G::n + idx_n;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const float d = fw[11 * ts + idx_n + r];
+                const float v = acc13[r] * (d * d);
+                put_partial(dst + r, pt.half ? -v : v, A.first_chunk);
+            }
+        }
     } else {
         float *dtab = lds + 4 * G::kRowFloats;  // tables written and read by the same thread
         CoefSplit<kPnLdsLayers> cn;
-        cn.load(A.fg_inv, G::n, idx_n, dtab + G::n, tid);
-        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + idx_n);
-        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + idx_n + 4);
+        cn.load(fg, ts, idx_n, dtab + G::n, tid);
+        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + pt.c0 + idx_n);
+        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + pt.c0 + idx_n + 4);
         NAcc acc;
         acc.clear();
-        T *dx = (T *)A.dx + A.row0 * A.ld_out + idx_n;  // used only if kDx
+        T *dx = (T *)A.dx + A.row0 * A.ld_out + pt.c0;  // used only if kDx
         __syncthreads();  // the other group's first row
         __syncthreads();
-        int64_t row = blockIdx.x;
-        for (int64_t it = 0; it < mine; ++it, row += gridDim.x) {
+        int64_t row = pt.slot;
+        for (int64_t it = 0; it < mine; ++it, row += pt.nslots) {
             float vx[8], vg[8];
             lds_read_n2(hand, an, vx);
             lds_read_n2(hand + G::kRowFloats, an, vg);
@@ -617,35 +590,44 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
                 const float4 da = ((const float4 *)dtab)[tid], db = ((const float4 *)dtab)[512 + tid];
                 vg[0] *= da.x; vg[1] *= da.y; vg[2] *= da.z; vg[3] *= da.w;
                 vg[4] *= db.x; vg[5] *= db.y; vg[6] *= db.z; vg[7] *= db.w;
-                store8(dx + row * A.ld_out, vg);
+                uint32_t off = (uint32_t)idx_n * (uint32_t)sizeof(T);
+                asm volatile("" : "+v"(off));
+                store8((T *)((char *)(dx + row * A.ld_out) + off), vg);
             }
             __syncthreads();  // B2
         }
-        finalize_n<K>(part, acc, idx_n, A.fw_inv, A.first_chunk);
+        finalize_n(part, acc, idx_n, fw, ts, pt.c0, A.first_chunk);
     }
 }
 
-// dtheta[q] = sum over slices of partial[s][q], in double, slice order; skipped for flagged plans
+// dtheta[q] = sum over slices of partial[s][q] (+ the upper-half share of the last layer where a slice has
+// one), in double, slice order; skipped for flagged plans
 __global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dtheta, size_t n_angles,
-                                  int n_parts, const int *bad_fwd, const int *bad_inv)
+                                  size_t slice_floats, size_t last_layer_at, int n_parts, const int *bad_fwd,
+                                  const int *bad_inv)
 {
     if ((*bad_fwd | *bad_inv) != 0) return;
     const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= n_angles) return;
+    const size_t extra = slice_floats - n_angles;  // 0, or the number of angles of the last layer
     double acc = 0.0;
-    for (int w = 0; w < n_parts; ++w) acc += (double)partial[(size_t)w * n_angles + q];
+    for (int w = 0; w < n_parts; ++w) {
+        const float *s = partial + (size_t)w * slice_floats;
+        acc += (double)s[q];
+        if (extra && q >= last_layer_at) acc += (double)s[q + extra];
+    }
     dtheta[q] = (float)acc;
 }
 
 // ---- host side -----------------------------------------------------------------------------------
-static int bwd_fast_slices(int k) { return 256; }  // one per compute unit (k = 12: one fused workgroup each)
+// Slices = row slots of the PN kernel, which runs one workgroup per compute unit (n = 8192: two per slot).
+static int bwd_fast_slices(int k) { return k == 12 ? 256 : 128; }
 static constexpr int kBwdFGrid = 512;
-// Rows per chunk bound the float32 intermediates in the workspace: x_k alone for k = 12 (2^30 elements,
-// 4 GiB), x_k, x_7 and g_7 for k = 13 (2^28 elements each, 3 GiB).  Small chunks that would stay in the
-// last-level cache measured slower: every launch re-reads the coefficients and rewrites the partial
-// slices, which only amortises over many rows per workgroup.
-static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << ((k == 12 ? 30 : 28) - k); }
-static int bwd_fast_intermediates(int k) { return k == 12 ? 1 : 3; }
+// Rows per chunk bound the float32 intermediate in the workspace (2^30 elements, 4 GiB).  Small chunks that
+// would stay in the last-level cache measured slower: every launch re-reads the coefficients and rewrites
+// the partial slices, which only amortises over many rows per workgroup.
+static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (30 - k); }
+static size_t bwd_fast_slice_floats(int k) { return (size_t)k * ((size_t)1 << (k - 1)) + (k == 13 ? 4096 : 0); }
 
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
 {
@@ -658,56 +640,42 @@ bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const flo
 
 size_t bwd_fast_workspace_bytes(const Shape &s)
 {
-    const size_t angles = (size_t)s.k * (s.n / 2);
     const size_t chunk = (size_t)(s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k));
-    return align256((size_t)bwd_fast_slices(s.k) * angles * sizeof(float)) + bwd_fast_intermediates(s.k) * align256(chunk * s.n * sizeof(float));
+    return align256((size_t)bwd_fast_slices(s.k) * bwd_fast_slice_floats(s.k) * sizeof(float)) +
+           align256(chunk * s.n * sizeof(float));
 }
 
-template <typename T, int K>
+template <typename T, bool kHalf>
 static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta, char *ws, hipStream_t stream)
 {
-    using G = Geo<K>;
-    const size_t angles = (size_t)K * (G::n / 2);
-    const int slices = bwd_fast_slices(K);
-    const int64_t chunk_rows = s.rows < bwd_fast_chunk_rows(K) ? s.rows : bwd_fast_chunk_rows(K);
-    const size_t inter = align256((size_t)chunk_rows * G::n * sizeof(float));
+    const size_t angles = (size_t)s.k * (s.n / 2);
+    const int slices = bwd_fast_slices(s.k);
+    const int64_t chunk_rows = s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k);
+    A.slice_floats = (int64_t)bwd_fast_slice_floats(s.k);
     A.partial = (float *)ws;
-    char *p = ws + align256((size_t)slices * angles * sizeof(float));
-    A.xk = (float *)p;
-    A.vx7 = K == 12 ? nullptr : (float *)(p + inter);  // k = 12 keeps (x_7, g_7) on chip
-    A.vg7 = K == 12 ? nullptr : (float *)(p + 2 * inter);
-    const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_p = 4 * G::kRowFloats * sizeof(float);
-    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
+    A.xk = (float *)(ws + align256((size_t)slices * A.slice_floats * sizeof(float)));
+    const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_pn = kPnLdsFloats * sizeof(float);
+    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_p_kernel<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_p);
+    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
     if (e != hipSuccess) return e;
-    const int spans = G::n / kNSpan;
-    const size_t lds_pn = kPnLdsFloats * sizeof(float);
-    if (K == 12) {
-        e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
-        if (e != hipSuccess) return e;
-    }
+    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
+    if (e != hipSuccess) return e;
+    const int pn_grid = kHalf ? 2 * slices : slices;  // kHalf: a multiple of 16 (see Part)
     for (int64_t r0 = 0; r0 < s.rows; r0 += chunk_rows) {
         A.row0 = r0;
         A.rows = s.rows - r0 < chunk_rows ? s.rows - r0 : chunk_rows;
         A.first_chunk = (r0 == 0);
         // every slice must be written by the first chunk, so the grids do not shrink with the row count
-        hipLaunchKernelGGL((bwd_f_kernel<T, K>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
-        if (K == 12) {
-            if (A.dx)
-                hipLaunchKernelGGL((bwd_pn_kernel<T, true>), dim3(slices), dim3(kPnThreads), lds_pn, stream, A);
-            else
-                hipLaunchKernelGGL((bwd_pn_kernel<T, false>), dim3(slices), dim3(kPnThreads), lds_pn, stream, A);
-        } else {
-            hipLaunchKernelGGL((bwd_p_kernel<T, K>), dim3(slices), dim3(G::threads), lds_p, stream, A);
-            hipLaunchKernelGGL((bwd_n_kernel<T, K>), dim3(slices * spans), dim3(kNThreads), 0, stream, A, spans);
-        }
+        hipLaunchKernelGGL((bwd_f_kernel<T, kHalf>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
+        if (A.dx)
+            hipLaunchKernelGGL((bwd_pn_kernel<T, true, kHalf>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
+        else
+            hipLaunchKernelGGL((bwd_pn_kernel<T, false, kHalf>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
     }
     const unsigned blocks = (unsigned)((angles + 255) / 256);
-    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, angles, slices,
-                       A.bad_fwd, A.bad_inv);
+    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, angles,
+                       (size_t)A.slice_floats, (size_t)(s.k - 1) * (s.n / 2), slices, A.bad_fwd, A.bad_inv);
     return hipGetLastError();
 }
 
@@ -720,6 +688,7 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     A.dx = dx;
     A.fg_fwd = pv.fg_fwd;
     A.fd_fwd = pv.fd_fwd;
+    A.fm_fwd = pv.fm_fwd;
     A.fg_inv = pv.fg_inv;
     A.fd_inv = pv.fd_inv;
     A.fw_inv = pv.fw_inv;
@@ -730,15 +699,15 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     char *w = (char *)ws;
     if (s.k == 12) {
         switch (s.dtype) {
-            case BQ_F32: return launch_bwd_fast_t<float, 12>(A, s, dtheta, w, stream);
-            case BQ_F16: return launch_bwd_fast_t<__half, 12>(A, s, dtheta, w, stream);
-            default: return launch_bwd_fast_t<bf16_t, 12>(A, s, dtheta, w, stream);
+            case BQ_F32: return launch_bwd_fast_t<float, false>(A, s, dtheta, w, stream);
+            case BQ_F16: return launch_bwd_fast_t<__half, false>(A, s, dtheta, w, stream);
+            default: return launch_bwd_fast_t<bf16_t, false>(A, s, dtheta, w, stream);
         }
     }
     switch (s.dtype) {
-        case BQ_F32: return launch_bwd_fast_t<float, 13>(A, s, dtheta, w, stream);
-        case BQ_F16: return launch_bwd_fast_t<__half, 13>(A, s, dtheta, w, stream);
-        default: return launch_bwd_fast_t<bf16_t, 13>(A, s, dtheta, w, stream);
+        case BQ_F32: return launch_bwd_fast_t<float, true>(A, s, dtheta, w, stream);
+        case BQ_F16: return launch_bwd_fast_t<__half, true>(A, s, dtheta, w, stream);
+        default: return launch_bwd_fast_t<bf16_t, true>(A, s, dtheta, w, stream);
     }
 }
 

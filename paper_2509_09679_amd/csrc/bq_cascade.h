@@ -163,7 +163,7 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&y)[8])
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        w[i] = (uint32_t)f32_to_bf16_bits(y[2 * i]) | ((uint32_t)f32_to_bf16_bits(y[2 * i + 1]) << 16);
+        w[i] = f32x2_to_bf16x2_bits(y[2 * i], y[2 * i + 1]);
     *(uint4 *)p = make_uint4(w[0], w[1], w[2], w[3]);
 }
 

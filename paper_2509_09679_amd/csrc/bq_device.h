@@ -25,12 +25,14 @@ __device__ __forceinline__ __half from_float<__half>(float v)
 {
     return __float2half_rn(v);
 }
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float v)
+// float32 -> bfloat16, round to nearest even: the hardware conversion (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float v) { return __builtin_bit_cast(uint16_t, (__bf16)v); }
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even
-    return (uint16_t)(u >> 16);
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const float2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 template <>
 __device__ __forceinline__ bf16_t from_float<bf16_t>(float v)

@@ -17,6 +17,9 @@ namespace bq {
 //   [cs      : float2 (cos, sin)  [heads][k][n/2]]            plain twiddles, pair order
 //   [fg_fwd  : float  [heads][k][n]]   scale-deferred ("fast Givens") forward coefficients
 //   [fd_fwd  : float  [heads][n]]      forward output scales
+//   [fm_fwd  : float  [heads][n]]      scale of the forward state before the last layer, divided by that
+//                                      layer's cosine: turns it into the transposed cascade's deferred units
+//                                      after its first layer (the n = 8192 backward pass starts there)
 //   [fg_inv  : float  [heads][k][n]]   the same for the transposed cascade
 //   [fd_inv  : float  [heads][n]]
 //   [fw_inv  : float  [heads][k][n]]   scale D of every element just BEFORE transposed layer i is applied
@@ -46,7 +49,7 @@ struct PlanHeader {
 static_assert(sizeof(PlanHeader) == 256, "header is 256 bytes");
 
 struct PlanLayout {
-    size_t cs, fg_fwd, fd_fwd, fg_inv, fd_inv, fw_inv, dwork, total;
+    size_t cs, fg_fwd, fd_fwd, fm_fwd, fg_inv, fd_inv, fw_inv, dwork, total;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -59,6 +62,7 @@ inline PlanLayout plan_layout(int n, int heads, int k)
     L.cs = off;      off = align256(off + H * K * (N / 2) * sizeof(float2));
     L.fg_fwd = off;  off = align256(off + H * K * N * sizeof(float));
     L.fd_fwd = off;  off = align256(off + H * N * sizeof(float));
+    L.fm_fwd = off;  off = align256(off + H * N * sizeof(float));
     L.fg_inv = off;  off = align256(off + H * K * N * sizeof(float));
     L.fd_inv = off;  off = align256(off + H * N * sizeof(float));
     L.fw_inv = off;  off = align256(off + H * K * N * sizeof(float));
@@ -78,7 +82,7 @@ inline int ilog2_exact(int n)
 struct PlanView {  // device pointers into a plan
     const PlanHeader *hdr;
     const float2 *cs;
-    const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv, *fw_inv;
+    const float *fg_fwd, *fd_fwd, *fm_fwd, *fg_inv, *fd_inv, *fw_inv;
 };
 
 inline PlanView plan_view(const void *plan, int n, int heads, int k)
@@ -90,6 +94,7 @@ inline PlanView plan_view(const void *plan, int n, int heads, int k)
     v.cs = (const float2 *)(p + L.cs);
     v.fg_fwd = (const float *)(p + L.fg_fwd);
     v.fd_fwd = (const float *)(p + L.fd_fwd);
+    v.fm_fwd = (const float *)(p + L.fm_fwd);
     v.fg_inv = (const float *)(p + L.fg_inv);
     v.fd_inv = (const float *)(p + L.fd_inv);
     v.fw_inv = (const float *)(p + L.fw_inv);

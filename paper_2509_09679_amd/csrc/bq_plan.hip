@@ -31,7 +31,8 @@ constexpr int kPlanMaxPerThread = 16;  // n <= 16384
 __global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(const float *__restrict__ theta, int n, int k,
                                                                   int inverse, float *__restrict__ fg,
                                                                   float *__restrict__ fd, float *__restrict__ fw,
-                                                                  double *__restrict__ dwork, int *bad_flag)
+                                                                  float *__restrict__ fm, double *__restrict__ dwork,
+                                                                  int *bad_flag)
 {
     const int head = blockIdx.x;
     const int tid = threadIdx.x;
@@ -62,6 +63,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(const float *__
             newD[j] = nd;
             fgh[(size_t)(i - 1) * n + e] = (float)coef;
             if (fw) fw[((size_t)head * k + (i - 1)) * n + e] = (float)Dself;  // scale before this layer
+            if (fm && step == k - 1) {
+                const double m = Dself / c;
+                fm[(size_t)head * n + e] = (float)m;
+                if (!(fabs(m) > lo_d && fabs(m) < hi_d)) bad = 1;
+            }
             const double ac = fabs(coef), ad = fabs(nd);
             if (!(ad > lo_d && ad < hi_d)) bad = 1;
             if (!(ac == 0.0 || (ac > lo_c && ac < hi_c))) bad = 1;
@@ -85,10 +91,10 @@ hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *
     hipLaunchKernelGGL(plan_cs_kernel, dim3(blocks), dim3(256), 0, stream, theta, (float2 *)(p + L.cs), count,
                        hdr, n, heads, k);
     hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 0,
-                       (float *)(p + L.fg_fwd), (float *)(p + L.fd_fwd), (float *)nullptr, (double *)(p + L.dwork),
-                       &hdr->fast_bad_fwd);
+                       (float *)(p + L.fg_fwd), (float *)(p + L.fd_fwd), (float *)nullptr, (float *)(p + L.fm_fwd),
+                       (double *)(p + L.dwork), &hdr->fast_bad_fwd);
     hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 1,
-                       (float *)(p + L.fg_inv), (float *)(p + L.fd_inv), (float *)(p + L.fw_inv),
+                       (float *)(p + L.fg_inv), (float *)(p + L.fd_inv), (float *)(p + L.fw_inv), (float *)nullptr,
                        (double *)(p + L.dwork), &hdr->fast_bad_inv);
     return hipGetLastError();
 }

@@ -91,10 +91,10 @@ def _oracle_dtheta_in_chunks(x, dy, th, n, dtype, chunk=8192):
     return acc, ab
 
 
-@pytest.mark.parametrize("cfg,T", [(5, 65536), (3, 262144), (3, 262144 + 4500)])
+@pytest.mark.parametrize("cfg,T", [(5, 65536), (5, 131072 + 2500), (3, 262144), (3, 262144 + 4500)])
 def test_backward_full_size(cfg, T):
-    # cfg 5: n=8192 bf16 (two chunks of the backward pipeline); cfg 3 shape: n=4096 f16, one chunk at the
-    # benchmark size and two (the second short and ragged) just above it
+    # cfg 5: n=8192 bf16; cfg 3 shape: n=4096 f16.  Each at its benchmark size (one chunk of the backward
+    # pipeline) and just above the chunk size (two chunks, the second short and ragged)
     x, th, dy = synth.device_rows(cfg, T, DEV, want_dy=True)
     wl = synth.make_workload(cfg, rows=1)
     n, dtype = wl.n, wl.dtype
