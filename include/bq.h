@@ -50,9 +50,10 @@ typedef enum {
 
 typedef enum { BQ_F32 = 0, BQ_F16 = 1, BQ_BF16 = 2 } bq_dtype;
 
-/* One batch of rows.  Element pointers must be aligned to 16 bytes and ld_* must be multiples of
- * 16 bytes worth of elements (4 for f32, 8 for f16/bf16) unless heads * n is smaller than that,
- * in which case natural element alignment suffices. */
+/* One batch of rows.  Element pointers must be aligned to their element size (else BQ_ERR_ALIGN).
+ * The specialised kernels additionally need 16-byte aligned pointers and ld_* that are multiples of
+ * 16 bytes worth of elements (4 for f32, 8 for f16/bf16); rows that do not meet this are processed by
+ * the slower general kernels, with the same results. */
 typedef struct {
     int64_t rows;  /* T >= 0                                                                  */
     int32_t n;     /* transform size, power of two, 2 <= n <= 16384                           */
