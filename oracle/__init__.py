@@ -41,6 +41,11 @@ def lib() -> ctypes.CDLL:
         L.bq_oracle_f16_bits_to_f32.argtypes = [ctypes.c_uint16]
         L.bq_oracle_f16_bits_to_f32.restype = ctypes.c_float
         L.bq_oracle_num_threads.restype = ctypes.c_int
+        L.bq_oracle_dequant.argtypes = [ctypes.POINTER(ctypes.c_int8), fp, ctypes.c_long, ctypes.c_long, ctypes.c_int, fp]
+        L.bq_oracle_bin_histogram.argtypes = [ctypes.POINTER(ctypes.c_int8), ctypes.c_long, ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_uint64)]
+        L.bq_oracle_uniformity_kl.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int]
+        L.bq_oracle_uniformity_kl.restype = ctypes.c_double
         _LIB = L
     return _LIB
 
@@ -122,6 +127,36 @@ def quantize(y32, group, bits, scale_dtype="f32"):
     if rc:
         raise ValueError("bq_oracle_quant: bad argument")
     return codes, scales
+
+
+def dequantize(codes, scales, group):
+    """Dequant(q) = s * q in float32.  codes int8 [rows,width], scales float32 [rows,width/group]."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    rows, width = codes.shape
+    yq = np.empty((rows, width), dtype=np.float32)
+    rc = lib().bq_oracle_dequant(_p(codes, ctypes.c_int8), _p(scales, ctypes.c_float), rows, width, group,
+                                 _p(yq, ctypes.c_float))
+    if rc:
+        raise ValueError("bq_oracle_dequant: bad argument")
+    return yq
+
+
+def bin_histogram(codes, bits):
+    """Occupancy of the 2^bits code bins: hist[c] = #(code == c - 2^(bits-1)), uint64."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    hist = np.zeros(1 << bits, dtype=np.uint64)
+    rc = lib().bq_oracle_bin_histogram(_p(codes, ctypes.c_int8), codes.size, bits, _p(hist, ctypes.c_uint64))
+    if rc:
+        raise ValueError("bq_oracle_bin_histogram: bad argument")
+    return hist
+
+
+def uniformity_kl(hist, bits):
+    """D_KL(P_bins || uniform) of a bin histogram (natural log)."""
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    assert hist.size == 1 << bits
+    return float(lib().bq_oracle_uniformity_kl(_p(hist, ctypes.c_uint64), bits))
 
 
 def pack_codes(codes, bits):

@@ -24,7 +24,8 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (dense-matrix definition
  * on tiny n, printed 8x8 layers, Hadamard special case, Kronecker closed form, orthogonality,
- * finite differences, hand-computed quantiser vectors).  The bit layout of packed codes and the
+ * finite differences, hand-computed quantiser vectors; Dequant, the bin histogram and the uniformity
+ * KL by hand-worked values, closed forms and library routines in tests/test_oracle_fakequant.py).  The bit layout of packed codes and the
  * treatment of an all-zero group are this project's choices, not the paper's: "parity unpinned"
  * for bq_oracle_pack_codes and for the zero-group rule.
  */
@@ -315,6 +316,48 @@ int bq_oracle_quant(const float *y, long rows, long width, int group, int bits, 
         }
     }
     return 0;
+}
+
+/* Dequant(q) = s * q (paper, "Loss Function"): one float multiplication per element, the group's stored
+ * scale times the code.  yq: [rows][width] float.  Returns 0, -1 on a bad argument. */
+int bq_oracle_dequant(const int8_t *codes, const float *scales, long rows, long width, int group, float *yq)
+{
+    if (group < 1 || width % group != 0 || rows < 0) return -1;
+    long ng = width / group;
+    for (long r = 0; r < rows; ++r)
+        for (long j = 0; j < width; ++j)
+            yq[r * width + j] = scales[r * ng + j / group] * (float)codes[r * width + j];
+    return 0;
+}
+
+/* Occupancy of the 2^b quantisation bins (the empirical distribution P_bins of the uniformity
+ * regulariser, before normalisation): hist[c] = number of codes equal to c - 2^(b-1). */
+int bq_oracle_bin_histogram(const int8_t *codes, long count, int bits, uint64_t *hist)
+{
+    if (bits < 2 || bits > 8 || count < 0) return -1;
+    int nb = 1 << bits, off = 1 << (bits - 1);
+    for (int c = 0; c < nb; ++c) hist[c] = 0;
+    for (long i = 0; i < count; ++i) {
+        int c = (int)codes[i] + off;
+        if (c < 0 || c >= nb) return -1;
+        hist[c] += 1;
+    }
+    return 0;
+}
+
+/* L_uniform = D_KL(P_bins || U) = sum_c P_c log(P_c * 2^b), P_c = hist[c] / total, 0 log 0 = 0
+ * (paper, "Uniformity Regularization"); natural logarithm. */
+double bq_oracle_uniformity_kl(const uint64_t *hist, int bits)
+{
+    int nb = 1 << bits;
+    double total = 0.0, kl = 0.0;
+    for (int c = 0; c < nb; ++c) total += (double)hist[c];
+    if (total == 0.0) return 0.0;
+    for (int c = 0; c < nb; ++c) {
+        double pc = (double)hist[c] / total;
+        if (pc > 0.0) kl += pc * log(pc * (double)nb);
+    }
+    return kl;
 }
 
 /* Pack signed codes into bytes: two's-complement fields of `bits` bits, element j of a row in
