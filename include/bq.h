@@ -110,6 +110,18 @@ bq_status bq_butterfly_inv(const void *y, void *x, const void *plan, const bq_ro
 bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes, void *scales,
                                  const bq_quant *quant, const bq_rows *rows, void *stream);
 
+/* Fake-quantised forward: yq = Dequant(Quant(B(theta) x)) = s * q, the activation factor of the
+ * reconstruction loss, and the occupancy of the 2^bits code bins, from which the uniformity regulariser
+ * D_KL(P_bins || U) follows (paper, sections "Loss Function" and "Uniformity Regularization").  Quant is
+ * exactly the quantiser of bq_butterfly_fwd_quant (same operation sequence, same scales and codes);
+ * Dequant is one float32 multiplication of the stored scale with the code.
+ *   yq  : [rows][ld_y] of rows->dtype, the float32 product rounded once to that type; may be NULL
+ *   hist: 2^bits uint64 counters on the device, OVERWRITTEN: hist[c] = number of channels, over all rows
+ *         and heads of this call, whose code is c - 2^(bits-1); may be NULL
+ * At least one of yq and hist must be given. */
+bq_status bq_butterfly_fwd_fakequant(const void *x, const void *plan, void *yq, uint64_t *hist,
+                                     const bq_quant *quant, const bq_rows *rows, void *stream);
+
 /* Bytes of device scratch bq_butterfly_bwd needs for this batch shape (0 if the shape is invalid). */
 size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows);
 

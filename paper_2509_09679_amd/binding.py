@@ -20,6 +20,7 @@ STATUS_NAMES = {0: "BQ_OK", 1: "BQ_ERR_NULL", 2: "BQ_ERR_SHAPE", 3: "BQ_ERR_DTYP
 DTYPE_CODES = {"f32": BQ_F32, "f16": BQ_F16, "bf16": BQ_BF16}
 
 EXPORTS = ["bq_plan_bytes", "bq_plan_build", "bq_butterfly_fwd", "bq_butterfly_inv", "bq_butterfly_fwd_quant",
+           "bq_butterfly_fwd_fakequant",
            "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_status_string", "bq_last_error",
            "bq_version"]
 
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
             f.argtypes = [vp, vp, vp, ctypes.POINTER(bq_rows), vp]
             f.restype = ctypes.c_int
         L.bq_butterfly_fwd_quant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
+        L.bq_butterfly_fwd_fakequant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
+        L.bq_butterfly_fwd_fakequant.restype = ctypes.c_int
         L.bq_butterfly_fwd_quant.restype = ctypes.c_int
         L.bq_butterfly_bwd_workspace_bytes.argtypes = [ctypes.POINTER(bq_rows)]
         L.bq_butterfly_bwd_workspace_bytes.restype = sz
@@ -131,6 +134,12 @@ def bq_butterfly_inv(y, x, plan, rows: bq_rows, stream=None) -> None:
 def bq_butterfly_fwd_quant(x, plan, codes, scales, quant: bq_quant, rows: bq_rows, stream=None) -> None:
     _check(lib().bq_butterfly_fwd_quant(_ptr(x), _ptr(plan), _ptr(codes), _ptr(scales), ctypes.byref(quant),
                                         ctypes.byref(rows), _stream_ptr(stream)))
+
+
+def bq_butterfly_fwd_fakequant(x, plan, yq, hist, quant: bq_quant, rows: bq_rows, stream=None) -> None:
+    """yq (rows' dtype, or None) and hist (uint64/int64 tensor of 2^bits counters, or None)."""
+    _check(lib().bq_butterfly_fwd_fakequant(_ptr(x), _ptr(plan), _ptr(yq), _ptr(hist), ctypes.byref(quant),
+                                            ctypes.byref(rows), _stream_ptr(stream)))
 
 
 def bq_butterfly_bwd_workspace_bytes(rows: bq_rows) -> int:

@@ -141,7 +141,7 @@ bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes
     if (misaligned(x, itemsize(s.dtype)) || misaligned(scales, quant->scale_dtype == BQ_F32 ? 4 : 2))
         return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
     if (s.rows == 0) return ok();
-    bq::QuantArgs q;
+    bq::QuantArgs q{};
     q.bits = quant->bits;
     q.group = g;
     q.scale_f16 = quant->scale_dtype == BQ_F16;
@@ -149,6 +149,43 @@ bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes
     q.scales = scales;
     bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
     hipError_t e = bq::launch_transform(bq::kFwdQuant, x, nullptr, pv, s, &q, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+bq_status bq_butterfly_fwd_fakequant(const void *x, const void *plan, void *yq, uint64_t *hist,
+                                     const bq_quant *quant, const bq_rows *rows, void *stream)
+{
+    const char *who = "bq_butterfly_fwd_fakequant";
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (!quant) return fail(BQ_ERR_NULL, "%s: quant descriptor is NULL", who);
+    if (!yq && !hist) return fail(BQ_ERR_NULL, "%s: yq and hist are both NULL", who);
+    if (s.rows > 0 && !x) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
+    if ((st = check_plan(plan, who)) != BQ_OK) return st;
+    if (quant->scale_dtype != BQ_F32 && quant->scale_dtype != BQ_F16)
+        return fail(BQ_ERR_DTYPE, "%s: scale_dtype must be BQ_F32 or BQ_F16", who);
+    if (quant->bits != 4 && quant->bits != 2)
+        return fail(BQ_ERR_UNSUPPORTED, "%s: bits=%d (only 4 and 2 are implemented)", who, quant->bits);
+    int g = quant->group;
+    if (g < 8 || g > s.n || (g & (g - 1)) != 0)
+        return fail(BQ_ERR_SHAPE, "%s: group=%d must be a power of two in [8, n]", who, g);
+    if (misaligned(x, itemsize(s.dtype)) || misaligned(yq, itemsize(s.dtype)) || misaligned(hist, 8))
+        return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
+    hipError_t e;
+    if (hist) {  // also for an empty batch: the counters are an output
+        e = bq::launch_hist_clear((unsigned long long *)hist, quant->bits, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, who);
+    }
+    if (s.rows == 0) return ok();
+    bq::QuantArgs q{};
+    q.bits = quant->bits;
+    q.group = g;
+    q.scale_f16 = quant->scale_dtype == BQ_F16;
+    q.hist = (unsigned long long *)hist;
+    bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
+    e = bq::launch_transform(bq::kFwdFake, x, yq, pv, s, &q, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, who);
     return ok();
 }

@@ -189,8 +189,10 @@ __device__ __forceinline__ float rcp_f16_valued(float s)
 // shift-add each:  acc = sum (bits(f_j) << j*BITS)  =  sum q_j 2^(j*BITS) + const.  Adding the bias
 // 2^(BITS-1) to every field makes all fields non-negative (no borrows between fields); the final
 // XOR takes the bias out again, field by field.
+// Scale, its reciprocal and the products y * inv (clipped where the clip can act) of the thread's 8 channels.
 template <int BITS>
-__device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out)
+__device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool scale_f16, float (&t)[8], float *scale_out,
+                                        bool *ordinary_out)
 {
     float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fabsf(y[2]));
     m = fmaxf(fmaxf(m, fabsf(y[3])), fabsf(y[4]));
@@ -226,17 +228,26 @@ __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool 
     }
     inv = (s == 0.0f) ? 0.0f : inv;
     *scale_out = s;
-    constexpr float kMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
-    float t[8];
+    *ordinary_out = ordinary;
 #pragma unroll
     for (int r = 0; r < 8; ++r) t[r] = y[r] * inv;
     if (__builtin_expect(!ordinary, 0)) {  // rare: clip before rounding (the bounds are integers)
 #pragma unroll
         for (int r = 0; r < 8; ++r) t[r] = __builtin_amdgcn_fmed3f(t[r], qmin, qmax);
     }
+}
+
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
+
+template <int BITS>
+__device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out)
+{
+    float t[8];
+    bool ordinary;
+    scaled8<BITS>(y, lanes, scale_f16, t, scale_out, &ordinary);
     uint32_t acc = 0;
 #pragma unroll
-    for (int r = 7; r >= 0; --r) acc = (acc << BITS) + __float_as_uint(t[r] + kMagic);
+    for (int r = 7; r >= 0; --r) acc = (acc << BITS) + __float_as_uint(t[r] + kRoundMagic);
     uint32_t magic_sum = 0, bias = 0;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -246,6 +257,135 @@ __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool 
     uint32_t packed = (acc - magic_sum + bias) ^ bias;
     if (BITS == 2) packed &= 0xFFFFu;
     return packed;
+}
+
+// ---- fake quantisation: Dequant(Quant(y)) and code-bin counting -----------------------------------
+// Per-thread counters of the code bins, cheap enough for the row loop; drained into 2^BITS 64-bit counters
+// of the workgroup in LDS (`wg`, zeroed by the caller) through drain().  Bin c holds code c - 2^(BITS-1).
+template <int BITS>
+struct BinCount;
+
+// INT2: with an ordinary scale the codes are -1, 0, 1, so their sum and their sum of squares give the three
+// counts; code -2 (possible only where the clip acts) is counted explicitly on that cold path.
+//   sum = pos - neg - 2 m2,  squares = pos + neg + 4 m2,  rows * 8 = pos + neg + zero + m2
+template <>
+struct BinCount<2> {
+    int sum, squares, m2, rows;
+    __device__ __forceinline__ void clear() { sum = squares = m2 = rows = 0; }
+    __device__ __forceinline__ void add(const float (&q)[8], bool ordinary)
+    {
+        const float a = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+        float b = q[0] * q[0];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) b = __builtin_fmaf(q[r], q[r], b);
+        sum += (int)a;
+        squares += (int)b;
+        rows += 1;
+        if (__builtin_expect(!ordinary, 0)) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) m2 += (q[r] == -2.0f) ? 1 : 0;
+        }
+    }
+    __device__ __forceinline__ void drain(unsigned long long *wg)
+    {
+        const int pos = (sum + squares - 2 * m2) / 2, neg = (squares - sum - 6 * m2) / 2;
+        const int zero = 8 * rows - pos - neg - m2;
+        if (m2) atomicAdd(&wg[0], (unsigned long long)m2);
+        if (neg) atomicAdd(&wg[1], (unsigned long long)neg);
+        if (zero) atomicAdd(&wg[2], (unsigned long long)zero);
+        if (pos) atomicAdd(&wg[3], (unsigned long long)pos);
+        clear();
+    }
+    __device__ __forceinline__ void skip() {}
+    static constexpr int kDrainEvery = 1 << 24;  // rows; int range
+    __device__ __forceinline__ bool full() const { return rows >= kDrainEvery; }
+};
+
+// INT4: the low four bits of (t + 1.5 * 2^23) are the code in two's complement.  One row's eight codes become
+// a 64-bit word of sixteen 4-bit counts (one-hot adds); its even and odd nibbles are added to four words of
+// 8-bit counts, which hold 31 rows; then the wave adds them up and one lane of it updates the workgroup's
+// counters.
+template <>
+struct BinCount<4> {
+    uint32_t c8[4];  // 8-bit counts: [0] nibbles 0,2,4,6  [1] 1,3,5,7  [2] 8,10,12,14  [3] 9,11,13,15
+    int rows;
+    __device__ __forceinline__ void clear()
+    {
+        c8[0] = c8[1] = c8[2] = c8[3] = 0;
+        rows = 0;
+    }
+    __device__ __forceinline__ void add(const uint32_t (&fbits)[8])
+    {
+        unsigned long long p = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) p += 1ull << ((fbits[r] & 15u) << 2);
+        const uint32_t lo = (uint32_t)p, hi = (uint32_t)(p >> 32);
+        c8[0] += lo & 0x0F0F0F0Fu;
+        c8[1] += (lo >> 4) & 0x0F0F0F0Fu;
+        c8[2] += hi & 0x0F0F0F0Fu;
+        c8[3] += (hi >> 4) & 0x0F0F0F0Fu;
+        rows += 1;
+    }
+    __device__ __forceinline__ void skip() { rows += 1; }  // keeps `rows` uniform over the wave
+    __device__ __forceinline__ bool full() const { return rows >= 31; }
+    // every lane of the wave must call this together
+    __device__ __forceinline__ void drain(unsigned long long *wg)
+    {
+        // 16-bit counts (a wave's total is at most 64 * 248), two per word, added across the 64 lanes
+        uint32_t w[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            w[2 * j] = c8[j] & 0x00FF00FFu;             // fields 0 and 2 of c8[j]
+            w[2 * j + 1] = (c8[j] >> 8) & 0x00FF00FFu;  // fields 1 and 3
+        }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] += (uint32_t)__shfl_xor((int)w[j], m, 64);
+        if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    // field f of c8[j] counts nibble: (j >> 1) * 8 + 2 f + (j & 1); bin = nibble ^ 8
+                    const int nibble = (j >> 1) * 8 + 2 * f + (j & 1);
+                    const uint32_t word = w[2 * j + (f & 1)];
+                    const uint32_t v = (f >> 1) ? (word >> 16) : (word & 0xFFFFu);
+                    if (v) atomicAdd(&wg[nibble ^ 8], (unsigned long long)v);
+                }
+        }
+        clear();
+    }
+};
+
+// Dequant(Quant(y)) for the thread's 8 channels: yq = s * q in float32 (one rounding), with the same scale
+// and codes as quant8.  qf receives the codes as floats, fbits the bit patterns of (t + 1.5 * 2^23).
+template <int BITS>
+__device__ __forceinline__ void fake8(const float (&y)[8], int lanes, bool scale_f16, float (&yq)[8], float (&qf)[8],
+                                      uint32_t (&fbits)[8], bool *ordinary)
+{
+    float t[8], s;
+    scaled8<BITS>(y, lanes, scale_f16, t, &s, ordinary);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const float f = t[r] + kRoundMagic;
+        fbits[r] = __float_as_uint(f);
+        qf[r] = f - kRoundMagic;
+        yq[r] = qf[r] * s;
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void count8(BinCount<BITS> &bc, const float (&qf)[8], const uint32_t (&fbits)[8], bool ordinary);
+template <>
+__device__ __forceinline__ void count8<2>(BinCount<2> &bc, const float (&qf)[8], const uint32_t (&)[8], bool ordinary)
+{
+    bc.add(qf, ordinary);
+}
+template <>
+__device__ __forceinline__ void count8<4>(BinCount<4> &bc, const float (&)[8], const uint32_t (&fbits)[8], bool)
+{
+    bc.add(fbits);
 }
 
 }  // namespace bq

@@ -25,6 +25,7 @@ struct GenArgs {
     // quantiser
     uint8_t *codes;
     void *scales;
+    unsigned long long *hist;
     int bits, group, scale_f16;
 };
 
@@ -64,6 +65,8 @@ __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
     extern __shared__ float lds[];
     float *buf = lds;
     float *inv_lds = lds + A.tile_elems;  // one reciprocal scale per group of the tile
+    float *s_lds = inv_lds + A.tile_elems / (A.group > 0 ? A.group : 1);  // kFwdFake: the scales themselves
+    __shared__ unsigned hist_lds[16];
     const T *__restrict__ in = (const T *)A.in;
     T *__restrict__ out = (T *)A.out;
     const int n = A.n, k = A.k, heads = A.heads;
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
                 __syncthreads();
             }
         }
-        if (kMode != kFwdQuant) {
+        if (kMode == kFwd || kMode == kInv) {
             for (int e = threadIdx.x; e < A.tile_elems; e += kGenThreads) {
                 const int64_t unit = unit0 + (e >> k);
                 if (unit < total_units) {
@@ -116,8 +119,9 @@ __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
                 float inv;
                 const float s = group_scale(amax, qmax, A.scale_f16 != 0, &inv);
                 inv_lds[g] = inv;
+                if (kMode == kFwdFake) s_lds[g] = s;
                 const int64_t unit = unit0 + g / groups_per_unit;
-                if (unit < total_units) {
+                if (kMode == kFwdQuant && unit < total_units) {
                     const int64_t sidx = unit * groups_per_unit + (g % groups_per_unit);
                     if (A.scale_f16)
                         ((__half *)A.scales)[sidx] = __float2half_rn(s);
@@ -125,7 +129,30 @@ __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
                         ((float *)A.scales)[sidx] = s;
                 }
             }
+            if (kMode == kFwdFake && threadIdx.x < 16) hist_lds[threadIdx.x] = 0;
             __syncthreads();
+            if (kMode == kFwdFake) {
+                // Dequant(Quant(v)) = s * q, one float32 multiplication, then one rounding to the row type;
+                // bin occupancy through LDS counters, added to the caller's once per tile
+                const int off = 1 << (A.bits - 1);
+                for (int e = threadIdx.x; e < A.tile_elems; e += kGenThreads) {
+                    const int64_t unit = unit0 + (e >> k);
+                    if (unit >= total_units) continue;
+                    const int g = e / group;
+                    const int q = quant_code(buf[e], inv_lds[g], qmin, qmax);
+                    if (out) {
+                        const int64_t row = unit / heads;
+                        const int head = (int)(unit - row * heads);
+                        out[row * A.ld_out + (int64_t)head * n + (e & (n - 1))] = from_float<T>(s_lds[g] * (float)q);
+                    }
+                    if (A.hist) atomicAdd(&hist_lds[q + off], 1u);
+                }
+                __syncthreads();
+                if (A.hist && threadIdx.x < (1 << A.bits) && hist_lds[threadIdx.x] != 0)
+                    atomicAdd(&A.hist[threadIdx.x], (unsigned long long)hist_lds[threadIdx.x]);
+                __syncthreads();
+                continue;
+            }
             const int per = 8 / A.bits;
             const int tile_bytes = A.tile_elems / per;
             const int64_t unit_bytes = n / per;
@@ -152,6 +179,7 @@ static hipError_t launch_generic_t(Mode mode, GenArgs &A, size_t lds_bytes, unsi
         case kFwd: kern = generic_kernel<T, kFwd>; break;
         case kInv: kern = generic_kernel<T, kInv>; break;
         case kFwdQuant: kern = generic_kernel<T, kFwdQuant>; break;
+        case kFwdFake: kern = generic_kernel<T, kFwdFake>; break;
     }
     if (lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -182,18 +210,31 @@ hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &
     if (q) {
         A.codes = q->codes;
         A.scales = q->scales;
+        A.hist = q->hist;
         A.bits = q->bits;
         A.group = q->group;
         A.scale_f16 = q->scale_f16;
     }
     size_t lds_bytes = (size_t)A.tile_elems * sizeof(float);
     if (mode == kFwdQuant) lds_bytes += (size_t)(A.tile_elems / q->group) * sizeof(float);
+    if (mode == kFwdFake) lds_bytes += 2 * (size_t)(A.tile_elems / q->group) * sizeof(float);
     unsigned grid = (unsigned)(A.n_tiles < 4096 ? A.n_tiles : 4096);
     switch (s.dtype) {
         case BQ_F32: return launch_generic_t<float>(mode, A, lds_bytes, grid, stream);
         case BQ_F16: return launch_generic_t<__half>(mode, A, lds_bytes, grid, stream);
         default: return launch_generic_t<bf16_t>(mode, A, lds_bytes, grid, stream);
     }
+}
+
+__global__ void hist_clear_kernel(unsigned long long *hist, int count)
+{
+    if ((int)threadIdx.x < count) hist[threadIdx.x] = 0ull;
+}
+
+hipError_t launch_hist_clear(unsigned long long *hist, int bits, hipStream_t stream)
+{
+    hipLaunchKernelGGL(hist_clear_kernel, dim3(1), dim3(64), 0, stream, hist, 1 << bits);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -115,9 +115,11 @@ struct QuantArgs {
     int bits, group, scale_f16;
     uint8_t *codes;
     void *scales;
+    unsigned long long *hist;  // kFwdFake: 2^bits counters, may be NULL
 };
 
-enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2 };
+// kFwdFake: forward + quantise + dequantise (`out` receives s * q, may be NULL) + code-bin histogram
+enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2, kFwdFake = 3 };
 
 // generic (any n) kernels: bq_generic.hip
 hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
@@ -150,6 +152,9 @@ hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView
 size_t bwd_workspace_bytes(const Shape &s);
 hipError_t launch_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
                       const Shape &s, hipStream_t stream);
+
+// clears the 2^bits counters of a histogram (a fill kernel: safe inside a captured graph)
+hipError_t launch_hist_clear(unsigned long long *hist, int bits, hipStream_t stream);
 
 // plan build: bq_plan.hip
 hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *plan, hipStream_t stream);

@@ -53,6 +53,7 @@ struct K12Args {
     // quantiser
     uint8_t *codes;
     void *scales;
+    unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
     int group, scale_f16;
 };
 
@@ -132,10 +133,39 @@ __device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const fl
 // kLanes > 0 fixes the group size (8 * kLanes) and kScale fixes the scale type (0 = float32,
 // 1 = binary16) at compile time; kLanes == 0 reads both from the arguments.
 // Addresses are a uniform row base plus a 32-bit per-thread offset.
-template <typename T, int kMode, int kBits, int kLanes, int kScale>
-__device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk)
+struct NoCount {};
+template <int kMode, int kBits>
+struct CountOf {
+    typedef NoCount type;
+};
+template <int kBits>
+struct CountOf<kFwdFake, kBits> {
+    typedef BinCount<kBits> type;
+};
+
+// kYq (kFwdFake only): the dequantised row is stored; without it only the bins are counted.
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq>
+__device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
+                                           typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins)
 {
-    if (kMode != kFwdQuant) {
+    if (kMode == kFwdFake) {
+        const int lanes = A.group >> 3;  // 1..16 lanes per group
+        float yq[8], qf[8];
+        uint32_t fbits[8];
+        bool ordinary;
+        fake8<kBits>(y, lanes, A.scale_f16 != 0, yq, qf, fbits, &ordinary);
+        if (kYq) {
+            T *out_row = (T *)A.out + row * A.ld_out;
+            uint32_t off = (uint32_t)(head * kN + chunk * 8) * (uint32_t)sizeof(T);
+            asm volatile("" : "+v"(off));
+            store8((T *)((char *)out_row + off), yq);
+        }
+        if (A.hist) {  // uniform
+            auto &bc = (BinCount<kBits> &)bins;
+            count8<kBits>(bc, qf, fbits, ordinary);
+            if (bc.full()) bc.drain(wg_bins);
+        }
+    } else if (kMode != kFwdQuant) {
         T *out_row = (T *)A.out + row * A.ld_out;
         uint32_t off = (uint32_t)(head * kN + chunk * 8) * (uint32_t)sizeof(T);
         asm volatile("" : "+v"(off));
@@ -164,9 +194,24 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
     }
 }
 
-template <typename T, int kMode, int kBits, int kLanes, int kScale>
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true>
 __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 {
+    __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
+    typename CountOf<kMode, kBits>::type bins;
+    if (kMode == kFwdFake) {
+        ((BinCount<kBits> &)bins).clear();
+        if (threadIdx.x < 16) wg_bins[threadIdx.x] = 0;
+        __syncthreads();
+    }
+    // kFwdFake: per-thread counts -> workgroup counts -> the caller's counters (every thread gets here)
+    auto flush_bins = [&]() {
+        if (kMode == kFwdFake && A.hist) {
+            ((BinCount<kBits> &)bins).drain(wg_bins);
+            __syncthreads();
+            if (threadIdx.x < (1 << kBits) && wg_bins[threadIdx.x]) atomicAdd(&A.hist[threadIdx.x], wg_bins[threadIdx.x]);
+        }
+    };
     // LDS: [input ring 3 x 8 KB | output-scale table] first (low addresses), then the row buffers L[0..2]
     extern __shared__ float lds_raw[];
     float *lds = lds_raw + kFrontFloats;
@@ -187,8 +232,9 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
             slow_cascade<kInverse>(u, lds, cs, idx_n);
-            finish_row<T, kMode, kBits, kLanes, kScale>(A, u, row, head, chunk);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row, head, chunk, bins, wg_bins);
         }
+        flush_bins();
         return;
     }
 
@@ -272,7 +318,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
         // earlier, followed by stores, the load of row it+1 and stores again, so at most
         // 2 kStores + 1 younger operations may still be pending when row `it` is consumed.  The
         // first four iterations (pipeline fill, fewer stores issued) wait for everything.
-        constexpr int kStores = (kMode == kFwdQuant) ? 2 : 1;
+        constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : 1;
         constexpr uint32_t kSlotBytes = kN * 2;
         float d[8];
         {
@@ -305,8 +351,11 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
                     if (kStores == 2)
                         asm volatile("s_waitcnt vmcnt(5)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                      : "=v"(v) : "v"(ra) : "memory");
-                    else
+                    else if (kStores == 1)
                         asm volatile("s_waitcnt vmcnt(3)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(ra) : "memory");
+                    else
+                        asm volatile("s_waitcnt vmcnt(1)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
                                      : "=v"(v) : "v"(ra) : "memory");
                 } else {
                     asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
@@ -327,7 +376,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
                 layers_c(u);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                finish_row<T, kMode, kBits, kLanes, kScale>(A, u, row_first + (it - 2) * row_step, head, chunk);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -374,7 +423,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 #pragma unroll
                     for (int r = 0; r < 8; ++r) u[r] *= d[r];
                 }
-                finish_row<T, kMode, kBits, kLanes, kScale>(A, u, row_first + (it - 2) * row_step, head, chunk);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -388,6 +437,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
             if (it + 1 < n_my + 2) iteration(it + 1, raw_odd);
         }
     }
+    flush_bins();
 }
 
 template <typename T>
@@ -398,7 +448,12 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
         kern = k12_kernel<T, kFwd, 4, 0, 0>;
     else if (mode == kInv)
         kern = k12_kernel<T, kInv, 4, 0, 0>;
-    else if (A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
+    else if (mode == kFwdFake) {
+        if (A.out)
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true> : k12_kernel<T, kFwdFake, 4, 0, 0, true>;
+        else
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false> : k12_kernel<T, kFwdFake, 4, 0, 0, false>;
+    } else if (A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1> : k12_kernel<T, kFwdQuant, 4, 16, 1>;
     else
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0> : k12_kernel<T, kFwdQuant, 4, 0, 0>;
@@ -414,11 +469,11 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;  // elements per 16 bytes
     if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
-    if (mode != kFwdQuant && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
+    if (mode != kFwdQuant && out && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
     if (s.heads > 512) return false;
-    if (mode == kFwdQuant) {
+    if (mode == kFwdQuant || mode == kFwdFake) {
         if (q->group > 128) return false;
-        if (((uintptr_t)q->codes & 3)) return false;
+        if (mode == kFwdQuant && ((uintptr_t)q->codes & 3)) return false;
     }
     return true;
 }
@@ -441,6 +496,7 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     if (q) {
         A.codes = q->codes;
         A.scales = q->scales;
+        A.hist = q->hist;
         A.group = q->group;
         A.scale_f16 = q->scale_f16;
         bits = q->bits;
@@ -448,7 +504,7 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  On
     // large batches the fused kernel (VALU-bound) measured fastest with 1024 workgroups, the plain
     // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
-    const int target = mode == kFwdQuant ? 1024 : 768;
+    const int target = (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
     int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
     if (per_head > s.rows) per_head = s.rows;
     unsigned grid = (unsigned)(per_head * s.heads);

@@ -31,6 +31,7 @@ struct SmallArgs {
     int64_t n_groups;    // row groups = ceil(rows / rows_per_block)
     uint8_t *codes;
     void *scales;
+    unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
     int group, scale_f16;
 };
 
@@ -110,6 +111,20 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
     constexpr int n = 1 << K;
     constexpr bool kInverse = (kMode == kInv);
     const int tid = threadIdx.x;
+    __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
+    BinCount<kBits> bins;
+    bins.clear();
+    if (kMode == kFwdFake) {
+        if (tid < 16) wg_bins[tid] = 0;
+        __syncthreads();
+    }
+    auto flush_bins = [&]() {  // every thread gets here
+        if (kMode == kFwdFake && A.hist) {
+            bins.drain(wg_bins);
+            __syncthreads();
+            if (tid < (1 << kBits) && wg_bins[tid]) atomicAdd(&A.hist[tid], wg_bins[tid]);
+        }
+    };
     const int chunk = (tid & ~15) | lane_chunk(tid & 15);  // chunk of 8 elements inside the workgroup's span
     const int e0 = chunk * 8;
     int row_in_block, col;
@@ -143,6 +158,26 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
     };
     auto finish = [&](const float (&y)[8], int64_t g) {
         const int64_t row = row_of(g);
+        if (kMode == kFwdFake) {
+            const bool live = row < A.rows;  // lanes of a wave may hold different rows
+            float yq[8], qf[8];
+            uint32_t fbits[8];
+            bool ordinary;
+            fake8<kBits>(y, A.group >> 3, A.scale_f16 != 0, yq, qf, fbits, &ordinary);
+            if (A.out && live) {
+                uint32_t off = col_bytes;
+                asm volatile("" : "+v"(off));
+                store8((T *)((char *)((T *)A.out + row * A.ld_out) + off), yq);
+            }
+            if (A.hist) {
+                if (live)
+                    count8<kBits>(bins, qf, fbits, ordinary);
+                else
+                    bins.skip();
+                if (bins.full()) bins.drain(wg_bins);
+            }
+            return;
+        }
         if (row >= A.rows) return;
         if (kMode != kFwdQuant) {
             uint32_t off = col_bytes;
@@ -174,6 +209,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
             slow_small<K, kInverse>(u, cs_head, idx);
             finish(u, g);
         }
+        flush_bins();
         return;
     }
     float c[7][8], d[8];
@@ -199,6 +235,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
         finish(u0, g);
         if (g + grp_step < A.n_groups) finish(u1, g + grp_step);
     }
+    flush_bins();
 }
 
 template <typename T, int K>
@@ -206,6 +243,7 @@ static void (*pick_small(Mode mode, int bits))(SmallArgs)
 {
     if (mode == kFwd) return small_kernel<T, K, kFwd, 4>;
     if (mode == kInv) return small_kernel<T, K, kInv, 4>;
+    if (mode == kFwdFake) return bits == 2 ? small_kernel<T, K, kFwdFake, 2> : small_kernel<T, K, kFwdFake, 4>;
     return bits == 2 ? small_kernel<T, K, kFwdQuant, 2> : small_kernel<T, K, kFwdQuant, 4>;
 }
 
@@ -230,10 +268,10 @@ bool small_supported(Mode mode, const void *in, const void *out, const Shape &s,
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;
     if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
-    if (mode != kFwdQuant && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
-    if (mode == kFwdQuant) {
+    if (mode != kFwdQuant && out && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
+    if (mode == kFwdQuant || mode == kFwdFake) {
         if (q->group > s.n) return false;
-        if (((uintptr_t)q->codes & 3)) return false;
+        if (mode == kFwdQuant && ((uintptr_t)q->codes & 3)) return false;
     }
     return true;
 }
@@ -260,6 +298,7 @@ hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv
     if (q) {
         A.codes = q->codes;
         A.scales = q->scales;
+        A.hist = q->hist;
         A.group = q->group;
         A.scale_f16 = q->scale_f16;
         bits = q->bits;

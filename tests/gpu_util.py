@@ -144,3 +144,18 @@ def check_dtheta(dth_gpu, dth_ref, absacc, tol=1e-5, what=""):
     assert worst <= 1.0, f"{what}: dtheta element error {worst:.3f} x the bound"
     assert np.linalg.norm(d) <= tol * np.linalg.norm(absacc), f"{what}: dtheta norm error"
     return float(worst)
+
+
+def run_fwd_fakequant(x_store, theta, n, heads, dtype, bits, group, scale_dtype, want_y=True, want_hist=True):
+    import torch
+
+    rows, w = x_store.shape
+    th = torch.from_numpy(np.ascontiguousarray(theta)).to("cuda:0")
+    plan = B.alloc_plan(th, n, heads)
+    x = _dev(x_store, dtype)
+    yq = torch.full_like(x, 7.0) if want_y else None
+    hist = torch.full((1 << bits,), 12345, dtype=torch.int64, device="cuda:0") if want_hist else None
+    B.bq_butterfly_fwd_fakequant(x, plan, yq, hist, B.make_quant(bits, group, scale_dtype), B.make_rows(x, n, heads))
+    torch.cuda.synchronize()
+    return (synth.torch_to_storage(yq, dtype) if want_y else None,
+            hist.cpu().numpy().astype(np.uint64) if want_hist else None)
