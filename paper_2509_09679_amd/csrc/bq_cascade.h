@@ -358,34 +358,43 @@ struct BinCount<4> {
     }
 };
 
-// Dequant(Quant(y)) for the thread's 8 channels: yq = s * q in float32 (one rounding), with the same scale
-// and codes as quant8.  qf receives the codes as floats, fbits the bit patterns of (t + 1.5 * 2^23).
+// Fake quantisation of the thread's 8 channels, in two steps so that a caller can count before it forms
+// the output (fewer values alive at once): rounded8 gives f = t + 1.5 * 2^23 (the code q is f - 1.5 * 2^23,
+// and the low bits of f's pattern hold q in two's complement); Dequant is s * q, one float32 rounding, with
+// the same scale and codes as quant8.
 template <int BITS>
-__device__ __forceinline__ void fake8(const float (&y)[8], int lanes, bool scale_f16, float (&yq)[8], float (&qf)[8],
-                                      uint32_t (&fbits)[8], bool *ordinary)
+__device__ __forceinline__ void rounded8(const float (&y)[8], int lanes, bool scale_f16, float (&f)[8], float *s,
+                                         bool *ordinary)
 {
-    float t[8], s;
-    scaled8<BITS>(y, lanes, scale_f16, t, &s, ordinary);
+    float t[8];
+    scaled8<BITS>(y, lanes, scale_f16, t, s, ordinary);
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const float f = t[r] + kRoundMagic;
-        fbits[r] = __float_as_uint(f);
-        qf[r] = f - kRoundMagic;
-        yq[r] = qf[r] * s;
-    }
+    for (int r = 0; r < 8; ++r) f[r] = t[r] + kRoundMagic;
 }
 
 template <int BITS>
-__device__ __forceinline__ void count8(BinCount<BITS> &bc, const float (&qf)[8], const uint32_t (&fbits)[8], bool ordinary);
+__device__ __forceinline__ void count8(BinCount<BITS> &bc, const float (&f)[8], bool ordinary);
 template <>
-__device__ __forceinline__ void count8<2>(BinCount<2> &bc, const float (&qf)[8], const uint32_t (&)[8], bool ordinary)
+__device__ __forceinline__ void count8<2>(BinCount<2> &bc, const float (&f)[8], bool ordinary)
 {
-    bc.add(qf, ordinary);
+    float q[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) q[r] = f[r] - kRoundMagic;
+    bc.add(q, ordinary);
 }
 template <>
-__device__ __forceinline__ void count8<4>(BinCount<4> &bc, const float (&)[8], const uint32_t (&fbits)[8], bool)
+__device__ __forceinline__ void count8<4>(BinCount<4> &bc, const float (&f)[8], bool)
 {
+    uint32_t fbits[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) fbits[r] = __float_as_uint(f[r]);
     bc.add(fbits);
+}
+
+__device__ __forceinline__ void dequant8(const float (&f)[8], float s, float (&yq)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) yq[r] = (f[r] - kRoundMagic) * s;
 }
 
 }  // namespace bq

@@ -143,27 +143,28 @@ struct CountOf<kFwdFake, kBits> {
     typedef BinCount<kBits> type;
 };
 
-// kYq (kFwdFake only): the dequantised row is stored; without it only the bins are counted.
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq>
+// kFwdFake only: kYq = the dequantised row is stored, kHist = the bins are counted.
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist>
 __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
                                            typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins)
 {
     if (kMode == kFwdFake) {
         const int lanes = A.group >> 3;  // 1..16 lanes per group
-        float yq[8], qf[8];
-        uint32_t fbits[8];
+        float f[8], s;
         bool ordinary;
-        fake8<kBits>(y, lanes, A.scale_f16 != 0, yq, qf, fbits, &ordinary);
+        rounded8<kBits>(y, lanes, A.scale_f16 != 0, f, &s, &ordinary);
+        if (kHist) {
+            auto &bc = (BinCount<kBits> &)bins;
+            count8<kBits>(bc, f, ordinary);
+            if (bc.full()) bc.drain(wg_bins);
+        }
         if (kYq) {
+            float yq[8];
+            dequant8(f, s, yq);
             T *out_row = (T *)A.out + row * A.ld_out;
             uint32_t off = (uint32_t)(head * kN + chunk * 8) * (uint32_t)sizeof(T);
             asm volatile("" : "+v"(off));
             store8((T *)((char *)out_row + off), yq);
-        }
-        if (A.hist) {  // uniform
-            auto &bc = (BinCount<kBits> &)bins;
-            count8<kBits>(bc, qf, fbits, ordinary);
-            if (bc.full()) bc.drain(wg_bins);
         }
     } else if (kMode != kFwdQuant) {
         T *out_row = (T *)A.out + row * A.ld_out;
@@ -194,19 +195,19 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
     }
 }
 
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true>
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false>
 __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 {
     __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
     typename CountOf<kMode, kBits>::type bins;
-    if (kMode == kFwdFake) {
+    if (kMode == kFwdFake && kHist) {
         ((BinCount<kBits> &)bins).clear();
         if (threadIdx.x < 16) wg_bins[threadIdx.x] = 0;
         __syncthreads();
     }
     // kFwdFake: per-thread counts -> workgroup counts -> the caller's counters (every thread gets here)
     auto flush_bins = [&]() {
-        if (kMode == kFwdFake && A.hist) {
+        if (kMode == kFwdFake && kHist) {
             ((BinCount<kBits> &)bins).drain(wg_bins);
             __syncthreads();
             if (threadIdx.x < (1 << kBits) && wg_bins[threadIdx.x]) atomicAdd(&A.hist[threadIdx.x], wg_bins[threadIdx.x]);
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
             slow_cascade<kInverse>(u, lds, cs, idx_n);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row, head, chunk, bins, wg_bins);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row, head, chunk, bins, wg_bins);
         }
         flush_bins();
         return;
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
                 layers_c(u);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 #pragma unroll
                     for (int r = 0; r < 8; ++r) u[r] *= d[r];
                 }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -449,10 +450,12 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     else if (mode == kInv)
         kern = k12_kernel<T, kInv, 4, 0, 0>;
     else if (mode == kFwdFake) {
-        if (A.out)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true> : k12_kernel<T, kFwdFake, 4, 0, 0, true>;
+        if (A.out && A.hist)
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true>;
+        else if (A.out)
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false>;
         else
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false> : k12_kernel<T, kFwdFake, 4, 0, 0, false>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true>;
     } else if (A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1> : k12_kernel<T, kFwdQuant, 4, 16, 1>;
     else

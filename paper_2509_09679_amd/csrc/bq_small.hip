@@ -160,21 +160,22 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
         const int64_t row = row_of(g);
         if (kMode == kFwdFake) {
             const bool live = row < A.rows;  // lanes of a wave may hold different rows
-            float yq[8], qf[8];
-            uint32_t fbits[8];
+            float f[8], s;
             bool ordinary;
-            fake8<kBits>(y, A.group >> 3, A.scale_f16 != 0, yq, qf, fbits, &ordinary);
-            if (A.out && live) {
-                uint32_t off = col_bytes;
-                asm volatile("" : "+v"(off));
-                store8((T *)((char *)((T *)A.out + row * A.ld_out) + off), yq);
-            }
+            rounded8<kBits>(y, A.group >> 3, A.scale_f16 != 0, f, &s, &ordinary);
             if (A.hist) {
                 if (live)
-                    count8<kBits>(bins, qf, fbits, ordinary);
+                    count8<kBits>(bins, f, ordinary);
                 else
                     bins.skip();
                 if (bins.full()) bins.drain(wg_bins);
+            }
+            if (A.out && live) {
+                float yq[8];
+                dequant8(f, s, yq);
+                uint32_t off = col_bytes;
+                asm volatile("" : "+v"(off));
+                store8((T *)((char *)((T *)A.out + row * A.ld_out) + off), yq);
             }
             return;
         }
