@@ -292,6 +292,34 @@ def extra_figures(B, synth, torch, dev):
                         "hbm_frac": round(bpr * T5 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                         "alg_TFLOPps": round(fpr * T5 / (avg * 1e-3) / 1e12, 2),
                         "valu_frac": round(fpr * T5 / (avg * 1e-3) / 1e12 / VALU_PEAK_TFLOPS, 4)}
+    # fake-quantised forward (Dequant(Quant(Bx)) + code-bin histogram) on the calibration batch, INT2 g128
+    T3 = 262144
+    x3, th3, _ = synth.device_rows(3, T3, dev)
+    theta3 = torch.from_numpy(th3).to(dev)
+    plan3 = B.alloc_plan(theta3, 4096, 1)
+    rows3 = B.make_rows(x3, 4096, 1)
+    yq3 = torch.empty_like(x3)
+    hist3 = torch.zeros(4, dtype=torch.int64, device=dev)
+    q3 = B.make_quant(2, 128, "f16")
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_fakequant(x3, plan3, yq3, hist3, q3, rows3), 10, 3)
+    bpr = alg_bytes_per_row("fwd", 4096, 1, 2)
+    res["fakequant"] = {"workload": "n=4096, T=262144, fp16: Dequant(Quant(Bx)) INT2 g128 + bin histogram",
+                        "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
+                        "GBps": round(bpr * T3 / (avg * 1e-3) / 1e9, 1),
+                        "hbm_frac": round(bpr * T3 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del yq3
+    # weight side: W [11008, 4096] fp16 -> W B^T, group-wise INT2 (g128) and its dtheta contribution
+    m = 11008
+    Wt = x3[:m]
+    dWt = x3[m:2 * m]
+    rw = B.make_rows(Wt, 4096, 1)
+    cw, sw = B.alloc_quant_outputs(m, 4096, 1, 2, 128, "f16", dev)
+    dthw = torch.empty_like(theta3)
+    wsw = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rw)), dtype=torch.uint8, device=dev)
+    a1, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(Wt, plan3, cw, sw, q3, rw), 20, 5)
+    a2, _, _ = time_kernel(lambda: B.bq_butterfly_bwd(Wt, dWt, plan3, None, dthw, wsw, rw), 20, 5)
+    res["weight_side"] = {"workload": "W [11008, 4096] fp16: fused W B^T + INT2 g128; dtheta from (W, dL/dW')",
+                          "fwd_quant_ms": round(a1, 4), "bwd_ms": round(a2, 4)}
     return res
 
 

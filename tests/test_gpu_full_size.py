@@ -113,3 +113,28 @@ def test_backward_full_size(cfg, T):
     gu.check_rotated(dxs, oracle.inverse(synth.to_f64(gs, dtype), th, n), dtype, f"cfg {cfg} full dx")
     ref, ab = _oracle_dtheta_in_chunks(x, dy, th, n, dtype)
     gu.check_dtheta(dth.cpu().numpy(), ref, ab, what=f"cfg {cfg} full dtheta")
+
+
+@pytest.mark.parametrize("m", [4096, 11008])
+def test_weight_side_rotation_quant_and_gradient(m):
+    # W' = W B^T is the forward transform over the rows of W ([m, n], n = 4096, fp16, no outlier channels);
+    # group-wise INT2 quantisation of W' (the weight side of W2A16) and the weight side's dtheta, which is
+    # the same backward call with the rows of W in place of activations.  Checked on the whole matrix.
+    n, dtype = 4096, "f16"
+    W, theta, dW = synth.small_case(n, m, dtype, seed=90 + m % 7, outliers=0, dist="normal", with_dy=True)
+    th = torch.from_numpy(theta).to(DEV)
+    plan = B.alloc_plan(th, n, 1)
+    Wd = synth.storage_to_torch(W, dtype, DEV)
+    dWd = synth.storage_to_torch(dW, dtype, DEV)
+    rows = B.make_rows(Wd, n, 1)
+    codes, scales = B.alloc_quant_outputs(m, n, 1, 2, 128, "f16", DEV)
+    B.bq_butterfly_fwd_quant(Wd, plan, codes, scales, B.make_quant(2, 128, "f16"), rows)
+    dth = torch.empty_like(th)
+    ws = torch.empty(B.bq_butterfly_bwd_workspace_bytes(rows), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(Wd, dWd, plan, None, dth, ws, rows)
+    torch.cuda.synchronize()
+    W64 = synth.to_f64(W, dtype)
+    gu.check_fused_codes(codes.cpu().numpy(), scales.float().cpu().numpy(), oracle.forward(W64, theta, n), 2, 128, "f16",
+                         dtype, f"weight side m={m}")
+    _, ref, ab = oracle.backward(W64, synth.to_f64(dW, dtype), theta, n)
+    gu.check_dtheta(dth.cpu().numpy(), ref, ab, what=f"weight side m={m} dtheta")
