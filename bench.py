@@ -307,7 +307,16 @@ def extra_figures(B, synth, torch, dev):
                         "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
                         "GBps": round(bpr * T3 / (avg * 1e-3) / 1e9, 1),
                         "hbm_frac": round(bpr * T3 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    del yq3
+    # the same forward kernel with every angle at pi/4 (a signed Hadamard transform): in the scale-deferred
+    # form a butterfly layer and a Hadamard layer both cost one FMA-class instruction per element
+    import math
+    y3 = yq3
+    a_rand, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan3, rows3), 10, 3)
+    plan_h = B.alloc_plan(torch.full_like(theta3, math.pi / 4), 4096, 1)
+    a_had, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan_h, rows3), 10, 3)
+    res["hadamard_angles"] = {"workload": "n=4096, T=262144, fp16 forward: learned angles vs all angles pi/4",
+                              "butterfly_ms": round(a_rand, 4), "hadamard_ms": round(a_had, 4)}
+    del yq3, y3
     # weight side: W [11008, 4096] fp16 -> W B^T, group-wise INT2 (g128) and its dtheta contribution
     m = 11008
     Wt = x3[:m]
