@@ -136,6 +136,27 @@ size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows);
 bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
                            void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream);
 
+/* ---- widths that are not powers of two ------------------------------------------------------ */
+
+/* Orthogonal factor for a width d = d1 * d2 with d1 not a power of two (paper, "Concrete Example for
+ * d = 5120"): Q1 = (I - A)(I + A)^-1 with A skew-symmetric.  params: the d1 (d1 - 1) / 2 entries of A's
+ * strict upper triangle, row by row (A[i][j] = p, A[j][i] = -p for i < j), float32 on the device.
+ * q1: [d1][d1] float32, row-major, on the device.  2 <= d1 <= 64.  Evaluated in double (Gauss-Jordan
+ * with partial pivoting; I + A is never singular) and rounded once. */
+bq_status bq_cayley_build(const float *params, int32_t d1, float *q1, void *stream);
+
+/* y = (Q1 (x) B(theta)) x  (paper, "Kronecker Product Formulation": Q_composite = Q1 (x) Q2 with a
+ * butterfly for the power-of-two factor).  A row has d1 * d2 elements, element (i, j) at i * d2 + j:
+ * with X the d1 x d2 matrix of a row, the result is Q1 X B^T.  rows->n = d2, rows->heads must be 1,
+ * rows->ld_x = rows->ld_y = d1 * d2 (dense rows).  plan: a plan for (n = d2, heads = 1).  The butterfly
+ * factor is applied first and its result passes through y in rows->dtype.  y == x is allowed. */
+bq_status bq_kron_fwd(const void *x, void *y, const float *q1, int32_t d1, const void *plan,
+                      const bq_rows *rows, void *stream);
+
+/* x = (Q1 (x) B(theta))^T y, the inverse of bq_kron_fwd; same conventions. */
+bq_status bq_kron_inv(const void *y, void *x, const float *q1, int32_t d1, const void *plan,
+                      const bq_rows *rows, void *stream);
+
 /* ---- helpers ------------------------------------------------------------------------------- */
 
 const char *bq_status_string(bq_status s);

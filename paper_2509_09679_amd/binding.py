@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "BQ_OK", 1: "BQ_ERR_NULL", 2: "BQ_ERR_SHAPE", 3: "BQ_ERR_DTYP
 DTYPE_CODES = {"f32": BQ_F32, "f16": BQ_F16, "bf16": BQ_BF16}
 
 EXPORTS = ["bq_plan_bytes", "bq_plan_build", "bq_butterfly_fwd", "bq_butterfly_inv", "bq_butterfly_fwd_quant",
-           "bq_butterfly_fwd_fakequant",
+           "bq_butterfly_fwd_fakequant", "bq_cayley_build", "bq_kron_fwd", "bq_kron_inv",
            "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_status_string", "bq_last_error",
            "bq_version"]
 
@@ -64,6 +64,11 @@ def lib() -> ctypes.CDLL:
         L.bq_butterfly_fwd_quant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
         L.bq_butterfly_fwd_fakequant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
         L.bq_butterfly_fwd_fakequant.restype = ctypes.c_int
+        L.bq_cayley_build.argtypes = [vp, ctypes.c_int32, vp, vp]
+        L.bq_cayley_build.restype = ctypes.c_int
+        for f in (L.bq_kron_fwd, L.bq_kron_inv):
+            f.argtypes = [vp, vp, vp, ctypes.c_int32, vp, ctypes.POINTER(bq_rows), vp]
+            f.restype = ctypes.c_int
         L.bq_butterfly_fwd_quant.restype = ctypes.c_int
         L.bq_butterfly_bwd_workspace_bytes.argtypes = [ctypes.POINTER(bq_rows)]
         L.bq_butterfly_bwd_workspace_bytes.restype = sz
@@ -111,6 +116,16 @@ def make_rows(x, n: int, heads: int, out=None) -> bq_rows:
     return r
 
 
+def make_kron_rows(x, d2: int) -> bq_rows:
+    """Descriptor for bq_kron_fwd / bq_kron_inv: dense rows of d1 * d2 elements, butterfly size d2."""
+    assert x.dim() == 2 and x.is_contiguous() and x.shape[1] % d2 == 0
+    r = bq_rows()
+    r.rows, r.n, r.heads = x.shape[0], d2, 1
+    r.ld_x = r.ld_y = x.shape[1]
+    r.dtype = _dtype_code(x)
+    return r
+
+
 # --- entry points, same names as the C ABI -----------------------------------------------------
 
 def bq_plan_bytes(n: int, heads: int = 1) -> int:
@@ -140,6 +155,18 @@ def bq_butterfly_fwd_fakequant(x, plan, yq, hist, quant: bq_quant, rows: bq_rows
     """yq (rows' dtype, or None) and hist (uint64/int64 tensor of 2^bits counters, or None)."""
     _check(lib().bq_butterfly_fwd_fakequant(_ptr(x), _ptr(plan), _ptr(yq), _ptr(hist), ctypes.byref(quant),
                                             ctypes.byref(rows), _stream_ptr(stream)))
+
+
+def bq_cayley_build(params, d1: int, q1, stream=None) -> None:
+    _check(lib().bq_cayley_build(_ptr(params), d1, _ptr(q1), _stream_ptr(stream)))
+
+
+def bq_kron_fwd(x, y, q1, d1: int, plan, rows: bq_rows, stream=None) -> None:
+    _check(lib().bq_kron_fwd(_ptr(x), _ptr(y), _ptr(q1), d1, _ptr(plan), ctypes.byref(rows), _stream_ptr(stream)))
+
+
+def bq_kron_inv(y, x, q1, d1: int, plan, rows: bq_rows, stream=None) -> None:
+    _check(lib().bq_kron_inv(_ptr(y), _ptr(x), _ptr(q1), d1, _ptr(plan), ctypes.byref(rows), _stream_ptr(stream)))
 
 
 def bq_butterfly_bwd_workspace_bytes(rows: bq_rows) -> int:

@@ -190,6 +190,66 @@ bq_status bq_butterfly_fwd_fakequant(const void *x, const void *plan, void *yq, 
     return ok();
 }
 
+bq_status bq_cayley_build(const float *params, int32_t d1, float *q1, void *stream)
+{
+    const char *who = "bq_cayley_build";
+    if (d1 < 2 || d1 > 64) return fail(BQ_ERR_SHAPE, "%s: d1=%d outside [2, 64]", who, d1);
+    if (!params || !q1) return fail(BQ_ERR_NULL, "%s: pointer is NULL", who);
+    if (misaligned(params, 4) || misaligned(q1, 4)) return fail(BQ_ERR_ALIGN, "%s: pointer not aligned to 4 bytes", who);
+    hipError_t e = bq::launch_cayley(params, d1, q1, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+static bq_status kron(bool inverse, const void *in, void *out, const float *q1, int32_t d1, const void *plan,
+                      const bq_rows *rows, void *stream, const char *who)
+{
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (d1 < 2 || d1 > 64) return fail(BQ_ERR_SHAPE, "%s: d1=%d outside [2, 64]", who, d1);
+    if (s.heads != 1) return fail(BQ_ERR_SHAPE, "%s: heads must be 1 (the butterfly factor is shared)", who);
+    const int64_t width = (int64_t)d1 * s.n;
+    if (s.ld_x != width || s.ld_y != width)
+        return fail(BQ_ERR_UNSUPPORTED, "%s: rows must be dense (ld_x = ld_y = d1 * d2 = %lld)", who, (long long)width);
+    if (s.rows > 0 && s.rows > ((int64_t)1 << 40) / width) return fail(BQ_ERR_SHAPE, "%s: batch too large", who);
+    if (s.rows == 0) return ok();
+    if (!in || !out || !q1) return fail(BQ_ERR_NULL, "%s: pointer is NULL", who);
+    if ((st = check_plan(plan, who)) != BQ_OK) return st;
+    // two adjacent elements are moved at a time by the mixing kernel
+    if (misaligned(in, 2 * itemsize(s.dtype)) || misaligned(out, 2 * itemsize(s.dtype)) || misaligned(q1, 4))
+        return fail(BQ_ERR_ALIGN, "%s: data pointers must be aligned to two elements", who);
+    bq::Shape sub = s;  // the [rows * d1, d2] view
+    sub.rows = s.rows * d1;
+    sub.ld_x = sub.ld_y = s.n;
+    bq::PlanView pv = bq::plan_view(plan, s.n, 1, s.k);
+    hipStream_t hs = (hipStream_t)stream;
+    hipError_t e;
+    if (bq::kron_fused_supported(in, out, d1, s.n)) {
+        e = bq::launch_kron_fused(inverse, in, out, q1, d1, pv, s.rows, s.dtype, hs);
+    } else if (!inverse) {
+        e = bq::launch_transform(bq::kFwd, in, out, pv, sub, nullptr, hs);
+        if (e == hipSuccess) e = bq::launch_mix(out, out, q1, d1, s.n, s.rows, s.dtype, false, hs);
+    } else {
+        e = bq::launch_mix(in, out, q1, d1, s.n, s.rows, s.dtype, true, hs);
+        if (e == hipSuccess) e = bq::launch_transform(bq::kInv, out, out, pv, sub, nullptr, hs);
+    }
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
+bq_status bq_kron_fwd(const void *x, void *y, const float *q1, int32_t d1, const void *plan, const bq_rows *rows,
+                      void *stream)
+{
+    return kron(false, x, y, q1, d1, plan, rows, stream, "bq_kron_fwd");
+}
+
+bq_status bq_kron_inv(const void *y, void *x, const float *q1, int32_t d1, const void *plan, const bq_rows *rows,
+                      void *stream)
+{
+    return kron(true, y, x, q1, d1, plan, rows, stream, "bq_kron_inv");
+}
+
 size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows)
 {
     bq::Shape s;

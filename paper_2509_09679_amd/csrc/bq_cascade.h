@@ -397,4 +397,75 @@ __device__ __forceinline__ void dequant8(const float (&f)[8], float s, float (&y
     for (int r = 0; r < 8; ++r) yq[r] = (f[r] - kRoundMagic) * s;
 }
 
+// ---- transforms of n = 8 .. 128 inside 16 lanes (8 consecutive elements per lane, no LDS) -----------
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Plain (cos, sin) cascade for flagged plans: a run-time loop over the layers (kept rolled so that
+// this rare path needs few registers); partners come from registers for layers 1-3 and from the
+// lanes lane^1, lane^2, lane^7, lane^8 for layers 4-7.
+template <int K, bool kInverse>
+__device__ __noinline__ void slow_small(float (&u)[8], const float2 *__restrict__ cs_head, int idx)
+{
+    constexpr int n = 1 << K;
+#pragma unroll 1
+    for (int step = 0; step < K; ++step) {
+        const int i = kInverse ? (K - step) : (step + 1);
+        const int h = 1 << (i - 1);
+        float p[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            float v;
+            switch (i) {
+                case 1: v = u[r ^ 1]; break;
+                case 2: v = u[r ^ 2]; break;
+                case 3: v = u[r ^ 4]; break;
+                case 4: v = dpp_read<0xB1>(u[r]); break;   // quad_perm [1,0,3,2]
+                case 5: v = dpp_read<0x4E>(u[r]); break;   // quad_perm [2,3,0,1]
+                case 6: v = dpp_read<0x141>(u[r]); break;  // row_half_mirror
+                default: v = dpp_read<0x128>(u[r]); break; // row_ror:8
+            }
+            p[r] = v;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int e = idx + r;
+            const int a = e & ~h;
+            const int pr = ((a >> i) << (i - 1)) | (a & (h - 1));
+            const float2 w = cs_head[(size_t)(i - 1) * (n >> 1) + pr];
+            const bool upper = (e & h) != 0;
+            // forward: lower  c x - s p, upper  c x + s p ; transposed: the signs swap
+            const float sgn = (upper != kInverse) ? w.y : -w.y;
+            u[r] = __builtin_fmaf(w.x, u[r], sgn * p[r]);
+        }
+    }
+}
+
+template <int K, bool kInverse>
+__device__ __forceinline__ void fast_small(float (&u)[8], const float (&c)[7][8], const float (&d)[8])
+{
+    if (!kInverse) {
+        reg_layer_first<0>(u, c[0]);
+        reg_layer<1>(u, c[1]);
+        reg_layer<2>(u, c[2]);
+        if (K >= 4) dpp_layer_xor1(u, c[3]);
+        if (K >= 5) dpp_layer_xor2(u, c[4]);
+        if (K >= 6) dpp_layer_xor7(u, c[5]);
+        if (K >= 7) dpp_layer_xor8(u, c[6]);
+    } else {
+        if (K >= 7) dpp_layer_xor8(u, c[6]);
+        if (K >= 6) dpp_layer_xor7(u, c[5]);
+        if (K >= 5) dpp_layer_xor2(u, c[4]);
+        if (K >= 4) dpp_layer_xor1(u, c[3]);
+        reg_layer<2>(u, c[2]);
+        reg_layer<1>(u, c[1]);
+        reg_layer<0>(u, c[0]);
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) u[r] *= d[r];
+}
+
 }  // namespace bq

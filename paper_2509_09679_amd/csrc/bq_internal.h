@@ -156,6 +156,14 @@ hipError_t launch_bwd(const void *x, const void *dy, const PlanView &pv, void *d
 // clears the 2^bits counters of a histogram (a fill kernel: safe inside a captured graph)
 hipError_t launch_hist_clear(unsigned long long *hist, int bits, hipStream_t stream);
 
+// composite transform for widths d1 * d2: bq_kron.hip
+hipError_t launch_cayley(const float *params, int d1, float *q, hipStream_t stream);
+hipError_t launch_mix(const void *in, void *out, const float *q, int d1, int d2, int64_t rows, int dtype,
+                      bool transpose, hipStream_t stream);
+bool kron_fused_supported(const void *in, const void *out, int d1, int d2);
+hipError_t launch_kron_fused(bool inverse, const void *in, void *out, const float *q, int d1, const PlanView &pv,
+                             int64_t rows, int dtype, hipStream_t stream);
+
 // plan build: bq_plan.hip
 hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *plan, hipStream_t stream);
 
