@@ -227,16 +227,29 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 }
 
 // ---- fused composite transform for d2 = 128 --------------------------------------------------------------
-// One workgroup per row at a time, 16 lanes per sub-row (8 consecutive elements per lane): the butterfly of
-// every sub-row runs in registers (as in the small-transform kernels), the float32 results go to an LDS tile,
-// and after a barrier wave w mixes: its lane c owns columns 2c, 2c+1 and outputs 4w .. 4w+3, reading column
-// values (8-byte LDS reads, consecutive lanes on consecutive banks) and four coefficients (one 16-byte
-// broadcast read) per input sub-row.  The two factors act on different indices and commute, so the inverse
-// runs the transposed butterfly first and then mixes with Q1^T: same structure.  One rounding to the row type
-// at the end; the tile is double-buffered so that one barrier per row suffices.
-// d1 is padded to D1P = a multiple of 4 (waves = D1P / 4); sub-rows past d1 are idle in the first phase.
+// One workgroup per row at a time, three groups of waves working on different rows, one barrier per step:
+//   * the butterfly group (16 lanes per sub-row, 8 consecutive elements per lane) transforms row t at step t:
+//     the butterfly of every sub-row runs in registers (as in the small-transform kernels) and the float32
+//     results go to an LDS tile Z[d1][128];
+//   * the store group (two waves) stores row t-2: 16-byte pieces read back from that row's tile, one rounding
+//     to the row type;
+//   * the mix group (four waves, one per SIMD) takes row t-1: Y = Q1 Z is a dense product, done on the matrix
+//     cores in float32 (v_mfma_f32_16x16x4_f32: no rounding of Z or Q1, float32 accumulation).  A wave owns two
+//     blocks of 16 columns; per step of four input sub-rows it reads one B operand per block from the tile
+//     (lane l: sub-row 4 s + l / 16, column l % 16 of the block) and issues one MFMA per block of 16 output
+//     sub-rows; Q1 (zero-padded) stays in registers as the A operands (lane l: output 16 i + l % 16, input
+//     4 s + l / 16).  Results (lane l, register r: output 16 i + 4 (l / 16) + r, column l % 16) overwrite
+//     the wave's own columns of the tile.
+// Vector and matrix work of different rows overlap on the same SIMDs.  Three tiles rotate.  The two factors
+// act on different indices and commute, so the inverse runs the transposed butterfly first and then mixes
+// with Q1^T: same structure.
 constexpr int kFusedD2 = 128;
-constexpr int kTileRow = kFusedD2 + 4;  // floats; the pad keeps 16-byte alignment of the lanes' 32-byte writes
+constexpr int kTileRow = kFusedD2 + 16;  // floats: sub-rows 16 banks apart, so a B-operand read (4 sub-rows x 16
+                                         // columns) touches every bank twice, the minimum for 256 bytes
+constexpr int kFusedMaxD1 = 40;  // 40 sub-rows x 16 lanes + six more waves = 1024 threads
+constexpr int kMixWaves = 4;
+constexpr int kStoreWaves = 2;
+constexpr int kFusedMaxThreads = kFusedMaxD1 * 16 + (kMixWaves + kStoreWaves) * 64;
 
 struct FusedArgs {
     const void *in;
@@ -247,102 +260,159 @@ struct FusedArgs {
     const int *fast_bad;
     int64_t rows;
     int d1;
+    int bfly_threads;  // threads of the butterfly group (whole waves); the mix group follows
 };
 
-// kBound: the largest workgroup the instantiation is launched with (640 covers d1 <= 40 and leaves each
-// thread more registers than the 1024-thread variant gets).
-template <typename T, bool kInverse, int kBound>
-__global__ __launch_bounds__(kBound) void kron128_kernel(FusedArgs A)
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// KS: steps of four input sub-rows (d1 <= 4 KS; inputs past d1 carry zero weights and re-read the last
+// sub-row), IT = ceil(KS / 4) blocks of 16 output sub-rows.  kSlow: the variant for plans whose scale-deferred tables
+// are flagged unusable (plain rotations); both variants are launched and the one that does not apply exits at
+// once, which keeps the out-of-line rotation code, and the stack traffic it brings, out of the fast variant.
+template <typename T, bool kInverse, int KS, bool kSlow>
+__global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
 {
-    typedef typename Pair<T>::raw raw_t;
-    extern __shared__ __align__(16) float lds[];
+    constexpr int IT = (KS + 3) / 4;
+    extern __shared__ __align__(16) float tile[];  // 3 x [d1][kTileRow]
+    if ((*A.fast_bad != 0) != kSlow) return;
     const int d1 = A.d1;
-    const int d1p = (d1 + 3) & ~3;
-    float *qs = lds;                       // [d1][d1p]: weight of input sub-row k in output i, zero padded
-    float *tile = lds + d1 * d1p;          // 2 x [d1][kTileRow]
-    const int tid = threadIdx.x, sub = tid >> 4, l16 = tid & 15;
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int e = tid; e < d1 * d1p; e += blockDim.x) {
-        const int k = e / d1p, i = e % d1p;
-        qs[e] = (i < d1) ? (kInverse ? A.q[k * d1 + i] : A.q[i * d1 + k]) : 0.0f;
-    }
-    const int idx = lane_chunk(l16) * 8;  // first column of the thread's 8 elements
-    const bool fast = (*A.fast_bad == 0);
-    float c[7][8], d[8];
-#pragma unroll
-    for (int j = 0; j < 7; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) c[j][r] = A.fg[j * kFusedD2 + idx + r];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) d[r] = A.fd[idx + r];
-    const bool loader = sub < d1;
-    const T *in = (const T *)A.in + (size_t)sub * kFusedD2 + idx;
+    const int tile_floats = d1 * kTileRow;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int64_t mine = A.rows > (int64_t)blockIdx.x ? (A.rows - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
     const int64_t width = (int64_t)d1 * kFusedD2;
-    int64_t row = blockIdx.x;
-    Raw8 raw = {};
-    if (loader && row < A.rows) raw = load8(in + row * width);
-    int par = 0;
-    for (; row < A.rows; row += gridDim.x) {
-        float *t = tile + par * d1 * kTileRow;
-        par ^= 1;
-        if (loader) {
-            float u[8];
-            unpack8(raw, u, (const T *)nullptr);
-            const int64_t next = row + gridDim.x;
-            if (next < A.rows) raw = load8(in + next * width);
-            if (fast)
-                fast_small<7, kInverse>(u, c, d);
-            else
-                slow_small<7, kInverse>(u, A.cs, idx);
-            float4 *dst = (float4 *)&t[sub * kTileRow + idx];
-            dst[0] = make_float4(u[0], u[1], u[2], u[3]);
-            dst[1] = make_float4(u[4], u[5], u[6], u[7]);
-        }
-        __syncthreads();  // also orders this row's tile reads before the writes two rows later
-        float a0[4] = {0, 0, 0, 0}, a1[4] = {0, 0, 0, 0};
-        const float *zc = t + 2 * lane;
-        const float *qc = qs + 4 * wave;
-#pragma unroll 8
-        for (int k = 0; k < d1; ++k) {
-            const float2 z = *(const float2 *)&zc[k * kTileRow];
-            const float4 w = *(const float4 *)&qc[k * d1p];
-            a0[0] = __builtin_fmaf(w.x, z.x, a0[0]);
-            a1[0] = __builtin_fmaf(w.x, z.y, a1[0]);
-            a0[1] = __builtin_fmaf(w.y, z.x, a0[1]);
-            a1[1] = __builtin_fmaf(w.y, z.y, a1[1]);
-            a0[2] = __builtin_fmaf(w.z, z.x, a0[2]);
-            a1[2] = __builtin_fmaf(w.z, z.y, a1[2]);
-            a0[3] = __builtin_fmaf(w.w, z.x, a0[3]);
-            a1[3] = __builtin_fmaf(w.w, z.y, a1[3]);
-        }
-        raw_t *out = (raw_t *)((T *)A.out + row * width) + lane;
+    if (tid < A.bfly_threads) {
+        // ---- butterfly group ---------------------------------------------------------------------------------
+        const int sub = tid >> 4, l16 = tid & 15;
+        const int idx = lane_chunk(l16) * 8;  // first column of the thread's 8 elements
+        const bool live = sub < d1;
+        float c[7][8], d[8];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (4 * wave + j < d1) out[(size_t)(4 * wave + j) * (kFusedD2 / 2)] = Pair<T>::pack(a0[j], a1[j]);
+        for (int j = 0; j < 7; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c[j][r] = A.fg[j * kFusedD2 + idx + r];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) d[r] = A.fd[idx + r];
+        const T *in = (const T *)A.in + (size_t)sub * kFusedD2 + idx;
+        // Two rows are in flight from memory.  This group only loads; the rows are stored by the mix group:
+        // memory operations of a wave retire in order, so a wave that both stores and prefetches ends up
+        // waiting for its stores to be acknowledged before it may use a prefetched row.
+        Raw8 raw = {}, raw_next = {};
+        if (live && mine > 0) raw = load8(in + (int64_t)blockIdx.x * width);
+        if (live && mine > 1) raw_next = load8(in + ((int64_t)blockIdx.x + gridDim.x) * width);
+        for (int64_t it = 0; it < mine + 2; ++it) {
+            if (live && it < mine) {  // transform row it (its tile last held row it-3, stored one step ago)
+                float u[8];
+                unpack8(raw, u, (const T *)nullptr);
+                raw = raw_next;
+                if (it + 2 < mine) raw_next = load8(in + (blockIdx.x + (it + 2) * gridDim.x) * width);
+                if (!kSlow)
+                    fast_small<7, kInverse>(u, c, d);
+                else
+                    slow_small<7, kInverse>(u, A.cs, idx);
+                float4 *dst = (float4 *)&tile[(int)(it % 3) * tile_floats + sub * kTileRow + idx];
+                dst[0] = make_float4(u[0], u[1], u[2], u[3]);
+                dst[1] = make_float4(u[4], u[5], u[6], u[7]);
+            }
+            __syncthreads();
+        }
+    } else if (tid >= A.bfly_threads + kMixWaves * 64) {
+        // ---- store group: row it-2, 16-byte pieces of 8 consecutive elements, one rounding to the row type ------
+        const int stid = tid - A.bfly_threads - kMixWaves * 64;
+        for (int64_t it = 0; it < mine + 2; ++it) {
+            if (it >= 2) {
+                const float *y_tile = tile + (int)((it - 2) % 3) * tile_floats;
+                T *out_row = (T *)A.out + (blockIdx.x + (it - 2) * gridDim.x) * width;
+                for (int piece = stid; piece < d1 * 16; piece += kStoreWaves * 64) {
+                    const int sub = piece >> 4, col = (piece & 15) * 8;
+                    const float4 *src = (const float4 *)&y_tile[sub * kTileRow + col];
+                    const float4 a = src[0], b = src[1];
+                    const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                    store8(out_row + sub * kFusedD2 + col, y);
+                }
+            }
+            __syncthreads();
+        }
+    } else {
+        // ---- mix group ---------------------------------------------------------------------------------------
+        const int mw = (tid - A.bfly_threads) >> 6;  // 0 .. kMixWaves-1: column blocks 2 mw and 2 mw + 1
+        // A operands: the weight of input sub-row k in output sub-row i is Q1[i][k] (forward) or Q1[k][i]
+        float qa[IT][KS];
+#pragma unroll
+        for (int t = 0; t < IT; ++t)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int i = 16 * t + (lane & 15), k = 4 * s + (lane >> 4);
+                qa[t][s] = (i < d1 && k < d1) ? (kInverse ? A.q[k * d1 + i] : A.q[i * d1 + k]) : 0.0f;
+            }
+        for (int64_t it = 0; it < mine + 2; ++it) {
+            if (it >= 1 && it <= mine) {  // mix row it-1 in place
+                float *t = tile + (int)((it - 1) % 3) * tile_floats + 32 * mw + (lane & 15);
+                v4f acc[2][IT];
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                    for (int i = 0; i < IT; ++i) acc[jb][i] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+                // all B operands of the row first (branch-free, so the reads overlap the matrix instructions)
+                float b0[KS], b1[KS];
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    int k = 4 * s + (lane >> 4);
+                    k = k < d1 ? k : d1 - 1;
+                    b0[s] = t[k * kTileRow];
+                    b1[s] = t[k * kTileRow + 16];
+                }
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+#pragma unroll
+                    for (int i = 0; i < IT; ++i) {
+                        acc[0][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[i][s], b0[s], acc[0][i], 0, 0, 0);
+                        acc[1][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[i][s], b1[s], acc[1][i], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                    for (int i = 0; i < IT; ++i)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int o = 16 * i + 4 * (lane >> 4) + r;
+                            if (o < d1) t[o * kTileRow + 16 * jb] = acc[jb][i][r];
+                        }
+            }
+            __syncthreads();
+        }
     }
 }
 
 bool kron_fused_supported(const void *in, const void *out, int d1, int d2)
 {
-    return d2 == kFusedD2 && d1 >= 2 && d1 <= 64 && !((uintptr_t)in & 15) && !((uintptr_t)out & 3);
+    return d2 == kFusedD2 && d1 >= 2 && d1 <= kFusedMaxD1 && !((uintptr_t)in & 15) && !((uintptr_t)out & 15);
 }
 
-template <typename T>
-static hipError_t launch_kron_fused_t(bool inverse, FusedArgs &A, hipStream_t stream)
+template <typename T, bool kInverse>
+static hipError_t launch_kron_fused_t(FusedArgs &A, hipStream_t stream)
 {
-    const int d1p = (A.d1 + 3) & ~3;
-    const int threads = d1p * 16;  // a multiple of 64
-    const size_t lds = ((size_t)A.d1 * d1p + 2 * (size_t)A.d1 * kTileRow) * sizeof(float);
-    void (*kern)(FusedArgs);
-    if (threads <= 640)
-        kern = inverse ? kron128_kernel<T, true, 640> : kron128_kernel<T, false, 640>;
-    else
-        kern = inverse ? kron128_kernel<T, true, 1024> : kron128_kernel<T, false, 1024>;
+    A.bfly_threads = ((A.d1 * 16 + 63) / 64) * 64;  // 16 lanes per sub-row, whole waves
+    const int threads = A.bfly_threads + (kMixWaves + kStoreWaves) * 64;
+    const size_t lds = 3 * (size_t)A.d1 * kTileRow * sizeof(float);
+    void (*kern)(FusedArgs), (*kern_slow)(FusedArgs);
+    if (A.d1 <= 16) {
+        kern = kron128_kernel<T, kInverse, 4, false>;
+        kern_slow = kron128_kernel<T, kInverse, 4, true>;
+    } else if (A.d1 <= 32) {
+        kern = kron128_kernel<T, kInverse, 8, false>;
+        kern_slow = kron128_kernel<T, kInverse, 8, true>;
+    } else {
+        kern = kron128_kernel<T, kInverse, 10, false>;
+        kern_slow = kron128_kernel<T, kInverse, 10, true>;
+    }
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    int64_t grid = 256 * 2;
+    e = hipFuncSetAttribute((const void *)kern_slow, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int64_t grid = 256;  // one workgroup fits a compute unit
     if (grid > A.rows) grid = A.rows;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds, stream, A);
+    hipLaunchKernelGGL(kern_slow, dim3((unsigned)grid), dim3(threads), lds, stream, A);
     return hipGetLastError();
 }
 
@@ -359,10 +429,17 @@ hipError_t launch_kron_fused(bool inverse, const void *in, void *out, const floa
     A.fast_bad = inverse ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
     A.rows = rows;
     A.d1 = d1;
+    if (inverse) {
+        switch (dtype) {
+            case BQ_F32: return launch_kron_fused_t<float, true>(A, stream);
+            case BQ_F16: return launch_kron_fused_t<__half, true>(A, stream);
+            default: return launch_kron_fused_t<bf16_t, true>(A, stream);
+        }
+    }
     switch (dtype) {
-        case BQ_F32: return launch_kron_fused_t<float>(inverse, A, stream);
-        case BQ_F16: return launch_kron_fused_t<__half>(inverse, A, stream);
-        default: return launch_kron_fused_t<bf16_t>(inverse, A, stream);
+        case BQ_F32: return launch_kron_fused_t<float, false>(A, stream);
+        case BQ_F16: return launch_kron_fused_t<__half, false>(A, stream);
+        default: return launch_kron_fused_t<bf16_t, false>(A, stream);
     }
 }
 
