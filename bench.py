@@ -317,6 +317,23 @@ def extra_figures(B, synth, torch, dev):
     res["hadamard_angles"] = {"workload": "n=4096, T=262144, fp16 forward: learned angles vs all angles pi/4",
                               "butterfly_ms": round(a_rand, 4), "hadamard_ms": round(a_had, 4)}
     del yq3, y3
+    # composite transform for a width that is not a power of two: 5120 = 40 x 128, fp16
+    Tk, d1k, d2k = 65536, 40, 128
+    xk = x3.reshape(-1)[: Tk * d1k * d2k].view(Tk, d1k * d2k)
+    yk = torch.empty_like(xk)
+    thk = (torch.rand(1, 7, 64, device=dev) * 2 - 1) * math.pi
+    plank = B.alloc_plan(thk, d2k, 1)
+    q1 = torch.empty(d1k, d1k, dtype=torch.float32, device=dev)
+    B.bq_cayley_build(torch.randn(d1k * (d1k - 1) // 2, device=dev) * 0.3, d1k, q1)
+    rk = B.make_kron_rows(xk, d2k)
+    avg, med, mx = time_kernel(lambda: B.bq_kron_fwd(xk, yk, q1, d1k, plank, rk), 10, 3)
+    bprk = 2 * d1k * d2k * 2
+    res["kron_5120"] = {"workload": "d = 5120 = 40 x 128, T=65536, fp16: (Cayley 40x40) (x) (butterfly 128)",
+                        "avg_ms": round(avg, 4), "rows_per_s": Tk / (avg * 1e-3),
+                        "GBps": round(bprk * Tk / (avg * 1e-3) / 1e9, 1),
+                        "hbm_frac": round(bprk * Tk / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                        "mfma_TFLOPps": round(2 * d1k * d1k * d2k * Tk / (avg * 1e-3) / 1e12, 2)}
+    del yk
     # weight side: W [11008, 4096] fp16 -> W B^T, group-wise INT2 (g128) and its dtheta contribution
     m = 11008
     Wt = x3[:m]
