@@ -138,3 +138,53 @@ def test_status_strings():
     for code, name in B.STATUS_NAMES.items():
         assert L.bq_status_string(code).decode() == name
     assert B.bq_version() >= 100
+
+
+def test_fakequant_validation():
+    L = B.lib()
+
+    def call(q, r=None, yq=FAKE, hist=FAKE, x=FAKE, plan=FAKE):
+        r = _rows(rows=5) if r is None else r
+        return L.bq_butterfly_fwd_fakequant(x, plan, yq, hist, ctypes.byref(q) if q is not None else None,
+                                            ctypes.byref(r), None)
+
+    q = B.make_quant(4, 128, "f16")
+    assert call(None) == 1
+    assert call(q, yq=None, hist=None) == 1
+    assert b"both NULL" in L.bq_last_error()
+    assert call(q, x=None) == 1
+    assert call(q, plan=None) == 1
+    assert call(B.make_quant(3, 128, "f16")) == 6
+    assert call(B.make_quant(4, 48, "f16")) == 2
+    assert call(B.make_quant(4, 256, "f16")) == 2            # group > n
+    assert call(q, hist=FAKE + 4) == 4                        # counters are 64-bit
+    assert call(q, r=_rows(rows=5, dtype=B.BQ_F32), yq=FAKE + 2) == 4
+    assert call(q, r=_rows(rows=-2)) == 2
+    assert call(q, r=_rows(rows=0), hist=None) == 0           # empty batch, nothing to clear: no launch
+
+
+def test_cayley_and_kron_validation():
+    L = B.lib()
+    assert L.bq_cayley_build(FAKE, 1, FAKE, None) == 2
+    assert L.bq_cayley_build(FAKE, 65, FAKE, None) == 2
+    assert L.bq_cayley_build(None, 40, FAKE, None) == 1
+    assert L.bq_cayley_build(FAKE, 40, None, None) == 1
+    assert L.bq_cayley_build(FAKE + 2, 40, FAKE, None) == 4
+
+    def call(fn, d1=40, r=None, x=FAKE, y=FAKE, q1=FAKE, plan=FAKE):
+        r = _rows(rows=3, n=128, ld=40 * 128) if r is None else r
+        return fn(x, y, q1, d1, plan, ctypes.byref(r), None)
+
+    for fn in (L.bq_kron_fwd, L.bq_kron_inv):
+        assert call(fn, d1=1) == 2
+        assert call(fn, d1=65) == 2
+        assert call(fn, r=_rows(rows=3, n=128, heads=2, ld=40 * 128)) == 2      # the butterfly factor is shared
+        assert call(fn, r=_rows(rows=3, n=128, ld=40 * 128 + 8)) == 6            # rows must be dense
+        assert b"dense" in L.bq_last_error()
+        assert call(fn, r=_rows(rows=3, n=100, ld=4000)) == 2
+        assert call(fn, x=None) == 1
+        assert call(fn, q1=None) == 1
+        assert call(fn, plan=None) == 1
+        assert call(fn, plan=FAKE + 32) == 4
+        assert call(fn, r=_rows(rows=3, n=128, ld=40 * 128, dtype=B.BQ_F16), x=FAKE + 2) == 4  # two elements at a time
+        assert call(fn, r=_rows(rows=0, n=128, ld=40 * 128), x=None, y=None) == 0
