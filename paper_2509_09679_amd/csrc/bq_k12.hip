@@ -30,6 +30,8 @@
 //
 // If the plan flags the scale-deferred tables as unusable (a cosine too close to zero), the cascade
 // of a row runs through LDS with plain (cos, sin) rotations instead; everything else is unchanged.
+#include <type_traits>
+
 #include "bq_cascade.h"
 
 namespace bq {
@@ -331,10 +333,11 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
         const uint32_t slice = ring0 + (uint32_t)wave * 1024u;                    // this wave's 1 KB of a slot
         const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * 16u;        // this thread's chunk
         const uint32_t voff = (uint32_t)(head * kN + (wave * 64 + lane) * 8) * 2u;  // lane's bytes in a row
+        const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
         auto ring_load = [&](int64_t j, int slot) {
             const int64_t jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
             const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
-            const uint32_t m0v = __builtin_amdgcn_readfirstlane(slice + (uint32_t)slot * kSlotBytes);
+            const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
                          :
                          : "v"(voff), "s"(m0v), "s"(rowp)
@@ -342,25 +345,29 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
         };
         ring_load(0, 0);
         ring_load(1, 1);
-        for (int64_t it = 0; it < n_my + 2; ++it) {
+        // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
+        // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
+        // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
+        auto step = [&](auto BA, auto BB, auto BC, int64_t it) {
+            constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
             float *la = lds + ba * kLdsRow, *lb = lds + bb * kLdsRow, *lc = lds + bc * kLdsRow;
             if (it < n_my) {  // A(it)
                 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
                 u32x4 v;
-                const uint32_t ra = rd_addr + (uint32_t)ba * kSlotBytes;
+                constexpr int ro = ba * (int)kSlotBytes;
                 if (it >= 4) {
                     if (kStores == 2)
-                        asm volatile("s_waitcnt vmcnt(5)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(ra) : "memory");
+                        asm volatile("s_waitcnt vmcnt(5)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                     else if (kStores == 1)
-                        asm volatile("s_waitcnt vmcnt(3)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(ra) : "memory");
+                        asm volatile("s_waitcnt vmcnt(3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                     else
-                        asm volatile("s_waitcnt vmcnt(1)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(ra) : "memory");
+                        asm volatile("s_waitcnt vmcnt(1)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                 } else {
-                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
-                                 : "=v"(v) : "v"(ra) : "memory");
+                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                 }
                 ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
                 Raw8 raw;
@@ -381,7 +388,15 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
-            rotate_buffers();
+        };
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, 1> I1;
+        typedef std::integral_constant<int, 2> I2;
+        const int64_t end = n_my + 2;
+        for (int64_t it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
+            step(I0{}, I2{}, I1{}, it);
+            if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
+            if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
         }
     } else {
         // ---- 32-bit rows: two rows prefetched in registers, output scales kept in LDS ---------------
