@@ -42,7 +42,6 @@ template <int K>
 struct Geo {
     static constexpr int n = 1 << K;
     static constexpr int threads = n / 8;
-    static constexpr int kPDpp = K - 9;  // lane-pairing layers of phase P (layers 8 .. 8+kPDpp-1)
     static constexpr int kStepR1 = (1 << (K - 2)) + 2 * (1 << (K - 7)) + 2 * (1 << (K - 11));
     static constexpr int kStepR2 = 2 * kStepR1;
     static constexpr int kRowFloats = ((n - 1) + 2 * ((n - 1) >> 5) + 2 * ((n - 1) >> 9) + 1 + 3) & ~3;
@@ -51,17 +50,13 @@ struct Geo {
 __device__ __forceinline__ int lds_addr2(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
 
 // base index of a thread in layout P: idx bits 7.. are the chunk bits of the low lane bits (DPP
-// masks 1, 2, 7, 8), idx bit 0 and the two top bits are register bits, the rest lanes 3..5 / waves.
+// masks 1, 2, 7), idx bit 0 and the two top bits are register bits, the rest lanes 3..5 / waves.
 template <int K>
 __device__ __forceinline__ int base_p2(int wave, int lane)
 {
-    if (K == 12) {
-        const int c3 = lane_chunk(lane & 15) & 7;
-        return (c3 << 7) | (((lane >> 3) & 1) << 2) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 3) | (wave << 4);
-    } else {
-        const int c4 = lane_chunk(lane & 15);
-        return (c4 << 7) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 2) | (wave << 3);
-    }
+    static_assert(K == 12, "4096-point geometry");
+    const int c3 = lane_chunk(lane & 15) & 7;
+    return (c3 << 7) | (((lane >> 3) & 1) << 2) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 3) | (wave << 4);
 }
 template <int K>
 __device__ __forceinline__ int p_reg_idx2(int r)
