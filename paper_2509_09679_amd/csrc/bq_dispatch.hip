@@ -6,7 +6,24 @@ namespace bq {
 hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                             const QuantArgs *q, hipStream_t stream)
 {
-    if (k12_supported(mode, in, out, s, q)) return launch_k12(mode, in, out, pv, s, q, stream);
+    if (k12_supported(mode, in, out, s, q)) {
+        hipError_t e = launch_k12(mode, in, out, pv, s, q, stream);
+        const int64_t done = (s.rows / k12_block_rows(s)) * k12_block_rows(s);
+        if (e != hipSuccess || done == s.rows) return e;
+        // rows that do not fill a block of the kernel: the generic kernel (rows are independent)
+        const size_t isz = s.dtype == BQ_F32 ? 4 : 2;
+        Shape t = s;
+        t.rows = s.rows - done;
+        const void *in_t = (const char *)in + (size_t)done * s.ld_x * isz;
+        void *out_t = out ? (char *)out + (size_t)done * s.ld_y * isz : nullptr;
+        QuantArgs qt;
+        if (q) {
+            qt = *q;
+            if (q->codes) qt.codes = q->codes + (size_t)done * s.n * s.heads * q->bits / 8;
+            if (q->scales) qt.scales = (char *)q->scales + (size_t)done * (s.n * s.heads / q->group) * (q->scale_f16 ? 2 : 4);
+        }
+        return launch_generic(mode, in_t, out_t, pv, t, q ? &qt : nullptr, stream);
+    }
     if (small_supported(mode, in, out, s, q)) return launch_small(mode, in, out, pv, s, q, stream);
     return launch_generic(mode, in, out, pv, s, q, stream);
 }

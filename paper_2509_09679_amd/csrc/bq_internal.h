@@ -136,8 +136,9 @@ size_t bwd_fast_workspace_bytes(const Shape &s);
 hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
                            const Shape &s, hipStream_t stream);
 
-// n = 4096 specialised kernels: bq_k12.hip
+// n = 4096 specialised kernels (also blocks of 4096 / n rows for n = 256 .. 2048): bq_k12.hip
 bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q);
+int k12_block_rows(const Shape &s);  // launch_k12 processes floor(rows / this) * this rows, from the first
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream);
 

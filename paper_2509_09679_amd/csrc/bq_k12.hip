@@ -57,7 +57,19 @@ struct K12Args {
     void *scales;
     unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
     int group, scale_f16;
+    // transforms of n = 2^n_log < 4096 points (kVirt): a "row" of the kernel is a block of 4096 / n consecutive
+    // rows of the caller; ld_in / ld_out are then the strides between blocks, sub_ld_* the caller's strides
+    int n, n_log;
+    int64_t sub_ld_in, sub_ld_out;
 };
+
+// Element offset, inside a kernel row, of the element with index e (a multiple of 8) of the 4096-point block.
+template <bool kVirt>
+__device__ __forceinline__ uint32_t elem_off(const K12Args &A, int head, int e, int64_t sub_ld)
+{
+    if (!kVirt) return (uint32_t)(head * kN + e);
+    return (uint32_t)((e >> A.n_log) * (int)sub_ld + (e & (A.n - 1)));
+}
 
 __device__ __forceinline__ int lds_addr(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
 constexpr int kPStepR1 = 1024 + 2 * 32 + 2 * 2;  // address step of register bit r1 (idx + 1024)
@@ -102,18 +114,21 @@ __device__ __forceinline__ void lds_read_p(const float *buf, int ap, float (&u)[
 }
 
 // slow cascade through LDS with (cos, sin); in: u[] in layout N, out: y[] in layout N (true values)
+// n_log < 12: the block holds 4096 >> n_log independent transforms of 2^n_log points (same angles).
 template <bool kInverse>
-__device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const float2 *__restrict__ cs, int idx_n)
+__device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const float2 *__restrict__ cs, int idx_n,
+                                             int n_log = kK)
 {
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 8; ++r) buf[idx_n + r] = u[r];
     __syncthreads();
-    for (int step = 0; step < kK; ++step) {
-        const int i = kInverse ? (kK - step) : (step + 1);
+    const int half_n = 1 << (n_log - 1);
+    for (int step = 0; step < n_log; ++step) {
+        const int i = kInverse ? (n_log - step) : (step + 1);
         const int h = 1 << (i - 1);
         for (int p = threadIdx.x; p < kN / 2; p += kThreads) {
-            const float2 w = cs[(size_t)(i - 1) * (kN / 2) + p];
+            const float2 w = cs[(size_t)(i - 1) * half_n + (p & (half_n - 1))];
             const int a = ((p >> (i - 1)) << i) | (p & (h - 1));
             const float xa = buf[a], xb = buf[a + h];
             if (!kInverse) {
@@ -146,7 +161,7 @@ struct CountOf<kFwdFake, kBits> {
 };
 
 // kFwdFake only: kYq = the dequantised row is stored, kHist = the bins are counted.
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist>
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt>
 __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
                                            typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins)
 {
@@ -164,13 +179,13 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
             float yq[8];
             dequant8(f, s, yq);
             T *out_row = (T *)A.out + row * A.ld_out;
-            uint32_t off = (uint32_t)(head * kN + chunk * 8) * (uint32_t)sizeof(T);
+            uint32_t off = elem_off<kVirt>(A, head, chunk * 8, A.sub_ld_out) * (uint32_t)sizeof(T);
             asm volatile("" : "+v"(off));
             store8((T *)((char *)out_row + off), yq);
         }
     } else if (kMode != kFwdQuant) {
         T *out_row = (T *)A.out + row * A.ld_out;
-        uint32_t off = (uint32_t)(head * kN + chunk * 8) * (uint32_t)sizeof(T);
+        uint32_t off = elem_off<kVirt>(A, head, chunk * 8, A.sub_ld_out) * (uint32_t)sizeof(T);
         asm volatile("" : "+v"(off));
         store8((T *)((char *)out_row + off), y);
     } else {
@@ -197,7 +212,7 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
     }
 }
 
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false>
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false, bool kVirt = false>
 __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 {
     __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
@@ -225,17 +240,21 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
     const int head = blockIdx.x % A.heads;
     const int64_t row_first = blockIdx.x / A.heads;
     const int64_t row_step = gridDim.x / A.heads;
-    const uint32_t off_n = (uint32_t)(head * kN + idx_n);  // element offset of the thread inside a row
+    const uint32_t off_n = elem_off<kVirt>(A, head, idx_n, A.sub_ld_in);  // element offset of the thread inside a row
+    // tables: rows of n entries, indexed inside the transform the element belongs to
+    const int tn = kVirt ? A.n : kN;
+    const int nk = kVirt ? A.n_log : kK;
+    const int tmask = tn - 1;
     const T *in = (const T *)A.in;
     if (row_first >= A.rows) return;
 
     if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
-        const float2 *cs = A.cs + (size_t)head * kK * (kN / 2);
+        const float2 *cs = A.cs + (size_t)head * kK * (kN / 2);  // kVirt: one head
         for (int64_t row = row_first; row < A.rows; row += row_step) {
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
-            slow_cascade<kInverse>(u, lds, cs, idx_n);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row, head, chunk, bins, wg_bins);
+            slow_cascade<kInverse>(u, lds, cs, idx_n, nk);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row, head, chunk, bins, wg_bins);
         }
         flush_bins();
         return;
@@ -245,15 +264,16 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
     const int idx_p = base_p(wave, lane);
     float cn[7][8], cp[5][8];
     {
-        const float *fg = A.fg + (size_t)head * kK * kN;
+        const float *fg = A.fg + (size_t)head * kK * kN;  // kVirt: one head
 #pragma unroll
         for (int j = 0; j < 7; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * kN + idx_n + r];
+            for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * tn + (idx_n & tmask) + r];
 #pragma unroll
         for (int j = 0; j < 5; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * kN + idx_p + p_reg_idx(r)];
+            for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
+                cp[j][r] = (!kVirt || 8 + j <= nk) ? fg[(7 + j) * tn + ((idx_p + p_reg_idx(r)) & tmask)] : 0.0f;
     }
     const int an = lds_addr(idx_n);
     const int ap = lds_addr(idx_p);
@@ -327,12 +347,12 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
         {
             const float *fd = A.fd + (size_t)head * kN;
 #pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[idx_n + r];
+            for (int r = 0; r < 8; ++r) d[r] = fd[(idx_n & tmask) + r];
         }
         const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
         const uint32_t slice = ring0 + (uint32_t)wave * 1024u;                    // this wave's 1 KB of a slot
         const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * 16u;        // this thread's chunk
-        const uint32_t voff = (uint32_t)(head * kN + (wave * 64 + lane) * 8) * 2u;  // lane's bytes in a row
+        const uint32_t voff = elem_off<kVirt>(A, head, (wave * 64 + lane) * 8, A.sub_ld_in) * 2u;  // lane's bytes in a row
         const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
         auto ring_load = [&](int64_t j, int slot) {
             const int64_t jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
@@ -384,7 +404,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
                 layers_c(u);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -405,7 +425,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
             const float *fd = A.fd + (size_t)head * kN;
             float d[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[idx_n + r];
+            for (int r = 0; r < 8; ++r) d[r] = fd[(idx_n & tmask) + r];
             lds_write_n(dtab, an, d);
         }
         __syncthreads();
@@ -439,7 +459,7 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
 #pragma unroll
                     for (int r = 0; r < 8; ++r) u[r] *= d[r];
                 }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
             }
             if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
             __syncthreads();
@@ -456,38 +476,42 @@ __global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
     flush_bins();
 }
 
-template <typename T>
+template <typename T, bool kVirt>
 static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned grid, hipStream_t stream)
 {
     void (*kern)(K12Args) = nullptr;
     if (mode == kFwd)
-        kern = k12_kernel<T, kFwd, 4, 0, 0>;
+        kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, kVirt>;
     else if (mode == kInv)
-        kern = k12_kernel<T, kInv, 4, 0, 0>;
+        kern = k12_kernel<T, kInv, 4, 0, 0, true, false, kVirt>;
     else if (mode == kFwdFake) {
         if (A.out && A.hist)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true, kVirt>;
         else if (A.out)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false, kVirt>;
         else
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true>;
-    } else if (A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true, kVirt>;
+    } else if (!kVirt && A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1> : k12_kernel<T, kFwdQuant, 4, 16, 1>;
     else
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0> : k12_kernel<T, kFwdQuant, 4, 0, 0>;
+        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, kVirt> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, kVirt>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, A);
     return hipGetLastError();
 }
 
+// n = 4096 with any number of heads, or one head of n = 256 .. 2048, where 4096 / n consecutive rows form one
+// block of the kernel (k12_block_rows; the caller passes whole blocks only).
 bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q)
 {
-    if (s.n != kN) return false;
+    if (s.n > kN || s.n < 256) return false;
+    if (s.n < kN && (s.heads != 1 || s.rows < kN / s.n)) return false;
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;  // elements per 16 bytes
     if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
     if (mode != kFwdQuant && out && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
+    if (s.n < kN && ((int64_t)(kN / s.n) * (s.ld_x > s.ld_y ? s.ld_x : s.ld_y) * isz >= ((int64_t)1 << 31))) return false;
     if (s.heads > 512) return false;
     if (mode == kFwdQuant || mode == kFwdFake) {
         if (q->group > 128) return false;
@@ -495,6 +519,8 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
     }
     return true;
 }
+
+int k12_block_rows(const Shape &s) { return kN / s.n; }
 
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream)
@@ -506,9 +532,15 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.fd = mode == kInv ? pv.fd_inv : pv.fd_fwd;
     A.cs = pv.cs;
     A.fast_bad = mode == kInv ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
-    A.rows = s.rows;
-    A.ld_in = s.ld_x;
-    A.ld_out = s.ld_y;
+    const bool virt = s.n < kN;
+    const int block_rows = kN / s.n;  // rows of the caller per kernel row
+    A.rows = s.rows / block_rows;     // whole blocks only (the caller handles the remainder)
+    A.ld_in = s.ld_x * block_rows;
+    A.ld_out = s.ld_y * block_rows;
+    A.sub_ld_in = s.ld_x;
+    A.sub_ld_out = s.ld_y;
+    A.n = s.n;
+    A.n_log = s.k;
     A.heads = s.heads;
     int bits = 4;
     if (q) {
@@ -524,12 +556,19 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
     const int target = (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
     int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
-    if (per_head > s.rows) per_head = s.rows;
+    if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * s.heads);
+    if (virt) {
+        switch (s.dtype) {
+            case BQ_F32: return launch_k12_t<float, true>(mode, A, bits, grid, stream);
+            case BQ_F16: return launch_k12_t<__half, true>(mode, A, bits, grid, stream);
+            default: return launch_k12_t<bf16_t, true>(mode, A, bits, grid, stream);
+        }
+    }
     switch (s.dtype) {
-        case BQ_F32: return launch_k12_t<float>(mode, A, bits, grid, stream);
-        case BQ_F16: return launch_k12_t<__half>(mode, A, bits, grid, stream);
-        default: return launch_k12_t<bf16_t>(mode, A, bits, grid, stream);
+        case BQ_F32: return launch_k12_t<float, false>(mode, A, bits, grid, stream);
+        case BQ_F16: return launch_k12_t<__half, false>(mode, A, bits, grid, stream);
+        default: return launch_k12_t<bf16_t, false>(mode, A, bits, grid, stream);
     }
 }
 

@@ -227,7 +227,7 @@ def test_backward_workload5_sample_and_determinism():
 
 @pytest.mark.parametrize("n,rows,dtype", [(8192, 2300, "bf16"), (4096, 4500, "f16"), (4096, 700, "f32")])
 def test_backward_several_chunks(n, rows, dtype):
-    # more rows than one chunk of the three-kernel backward pipeline: slices are added to across chunks
+    # many rows per workgroup slice (several chunks of rows are covered at full size in test_gpu_full_size.py)
     x, th, dy = synth.small_case(n, rows, dtype, seed=17, with_dy=True, outliers=0)
     dx, dth = gu.run_bwd(x, dy, th, n, 1, dtype)
     rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n)
@@ -255,3 +255,51 @@ def test_backward_optional_outputs_and_zero_rows():
     gu.check_dtheta(dth, rdth, ab)
     _, dth0 = gu.run_bwd(x[:0], dy[:0], th, 256, 1, "f32", want_dx=False)
     assert not dth0.any()  # dtheta is overwritten, also by an empty batch
+
+
+# n = 256 .. 2048, one head: 4096 / n consecutive rows are processed as one block by the n = 4096 kernels (layers
+# above log2 n get weight zero); rows that do not fill a block go through the general kernel.
+MID = [(256, 16 * 9 + 5, "f16"), (512, 8 * 7 + 3, "bf16"), (1024, 4 * 11 + 1, "f32"), (2048, 2 * 13 + 1, "f16"),
+       (2048, 64, "bf16"), (256, 16, "f32")]
+
+
+@pytest.mark.parametrize("n,rows,dtype", MID)
+def test_mid_sizes_forward_inverse_padded_inplace(n, rows, dtype):
+    x, th, _ = synth.small_case(n, rows, dtype, seed=60 + n)
+    ref = _ref_fwd(x, th, n, 1, dtype)
+    gu.check_rotated(gu.run_transform(x, th, n, 1, dtype), ref, dtype, f"mid fwd n={n}")
+    gu.check_rotated(gu.run_transform(x, th, n, 1, dtype, pad=16), ref, dtype, f"mid fwd padded n={n}")
+    a = gu.run_transform(x, th, n, 1, dtype)
+    b = gu.run_transform(x, th, n, 1, dtype, inplace=True)
+    np.testing.assert_array_equal(a.view(np.uint8), b.view(np.uint8))
+    xi = gu.run_transform(x, th, n, 1, dtype, inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(x, dtype), th, n, 1), dtype, f"mid inv n={n}")
+
+
+@pytest.mark.parametrize("n,rows,dtype", MID)
+@pytest.mark.parametrize("bits,group,sd", [(4, 128, "f16"), (2, 32, "f32")])
+def test_mid_sizes_fused_quant(n, rows, dtype, bits, group, sd):
+    x, th, _ = synth.small_case(n, rows, dtype, seed=61 + n)
+    y_ref = _ref_fwd(x, th, n, 1, dtype)
+    codes, scales = gu.run_fwd_quant(x, th, n, 1, dtype, bits, group, sd)
+    gu.check_fused_codes(codes, scales, y_ref, bits, group, sd, dtype, f"mid quant n={n}")
+    # the fake-quantised forward repeats these codes and scales exactly, block rows and leftover rows alike
+    yq, hist = gu.run_fwd_fakequant(x, th, n, 1, dtype, bits, group, sd)
+    c = oracle.unpack_codes(codes, bits)
+    want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+    u = np.uint16 if dtype != "f32" else np.uint32
+    np.testing.assert_array_equal(yq.view(u), want.view(u))
+    np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits))
+
+
+@pytest.mark.parametrize("n", [256, 1024, 2048])
+def test_mid_sizes_flagged_plan(n):
+    k = n.bit_length() - 1
+    rng = np.random.default_rng(n)
+    th = rng.uniform(-math.pi, math.pi, size=(1, k, n // 2)).astype(np.float32)
+    th[0, 0, ::2] = np.float32(math.pi / 2)
+    th[0, k - 1, :] = np.float32(-math.pi / 2)
+    x, _, _ = synth.small_case(n, 3 * (4096 // n) + 1, "f16", seed=5)
+    gu.check_rotated(gu.run_transform(x, th, n, 1, "f16"), _ref_fwd(x, th, n, 1, "f16"), "f16", "mid flagged fwd")
+    gu.check_rotated(gu.run_transform(x, th, n, 1, "f16", inverse=True),
+                     oracle.inverse(synth.to_f64(x, "f16"), th, n, 1), "f16", "mid flagged inv")
