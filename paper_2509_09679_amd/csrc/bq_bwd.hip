@@ -150,6 +150,11 @@ struct BwdFastArgs {
     int64_t ld_in, ld_out;
     int64_t slice_floats;
     int first_chunk;  // != 0: slices are overwritten, else added to
+    // n = 2^n_log < 4096 (kVirt): a row of the kernels is a block of 4096 / n consecutive rows of the caller;
+    // row0, rows, ld_in, ld_out then count and stride blocks, sub_ld_* are the caller's strides and total_rows
+    // its row count (the last block may be short: its missing rows are given dy = 0 and are not stored)
+    int n, n_log;
+    int64_t sub_ld_in, sub_ld_out, total_rows;
 };
 
 __device__ __forceinline__ bool plan_is_bad(const BwdFastArgs &A) { return (*A.bad_fwd | *A.bad_inv) != 0; }
@@ -165,62 +170,87 @@ __device__ __forceinline__ void put_partial(float *p, float v, int first)
 constexpr int K = 12;  // layers inside one 4096-point block
 using G = Geo<K>;
 
-// Which rows and which part of them a workgroup takes.  kHalf (n = 8192): blocks 16 j + 8 h + c take half h
-// of the rows of slot 8 j + c, so that the two workgroups of a slot, which read the same dy rows at about
-// the same time, sit on the same die (blocks go round the eight dies) and share its L2.
-template <bool kHalf>
+// Which rows and which part of them a workgroup takes, and how it indexes the plan's tables.
+// kHalf (n = 8192): blocks 16 j + 8 h + c take half h of the rows of slot 8 j + c, so that the two workgroups
+// of a slot, which read the same dy rows at about the same time, sit on the same die (blocks go round the
+// eight dies) and share its L2.  kVirt (n < 4096): see BwdFastArgs.
+template <bool kHalf, bool kVirt>
 struct Part {
     int half, slot, nslots, c0;
-    static constexpr int stride = kHalf ? 2 * G::n : G::n;  // row length of the tables and of x_k
-    __device__ __forceinline__ Part()
+    int ts;     // row length of the plan's tables (n)
+    int tmask;  // an element e of the 4096-point block uses table column (c0 + e) & tmask
+    int n_log;
+    int64_t tail_row;  // kVirt: the kernel row (counted from this launch's first) that is the short last block
+    int tail;          // ... and the number of rows it has
+    static constexpr int xs = kHalf ? 2 * G::n : G::n;  // row length of x_k; a slice holds xs / 2 sums per layer
+    __device__ __forceinline__ Part(const BwdFastArgs &A)
     {
         half = kHalf ? (blockIdx.x >> 3) & 1 : 0;
         slot = kHalf ? (int)((blockIdx.x & 7) | ((blockIdx.x >> 4) << 3)) : (int)blockIdx.x;
         nslots = kHalf ? (int)(gridDim.x >> 1) : (int)gridDim.x;
         c0 = half * G::n;
+        ts = kVirt ? A.n : xs;
+        tmask = ts - 1;
+        n_log = kVirt ? A.n_log : (kHalf ? K + 1 : K);
+        tail_row = kVirt ? (A.total_rows >> (K - A.n_log)) - A.row0 : -1;
+        tail = kVirt ? (int)(A.total_rows & ((G::n >> A.n_log) - 1)) : 0;
     }
+    __device__ __forceinline__ int col(int e) const { return (c0 + e) & tmask; }
+    // element offset of block element e (a multiple of 8) from the start of this workgroup's part of a kernel row
+    __device__ __forceinline__ uint32_t off(int e, int64_t sub_ld) const
+    {
+        return kVirt ? (uint32_t)((e >> n_log) * (int)sub_ld + (e & tmask)) : (uint32_t)e;
+    }
+    // kVirt: is the sub-row of element e missing from the short last block?
+    __device__ __forceinline__ bool in_tail_gap(int e) const { return kVirt && (e >> n_log) >= tail; }
 };
 
 // ---- F: forward cascade of layers 1..12 to float32 ------------------------------------------------------
-template <typename T, bool kHalf>
-__global__ __launch_bounds__(G::threads) void bwd_f_kernel(BwdFastArgs A)
+template <typename T, bool kHalf, bool kVirt>
+__global__ __launch_bounds__(G::threads) __attribute__((amdgpu_waves_per_eu(4))) void bwd_f_kernel(BwdFastArgs A)
 {
     extern __shared__ float lds[];  // [row buffer][output scales]
     if (plan_is_bad(A)) return;
-    const Part<kHalf> part;
-    constexpr int ts = Part<kHalf>::stride;
+    const Part<kHalf, kVirt> part(A);
+    const int ts = part.ts;
+    constexpr int xs = Part<kHalf, kVirt>::xs;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
     const int idx_p = base_p2<K>(wave, lane);
     const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
     float *buf = lds, *dtab = lds + G::kRowFloats;
-    const float *fg = A.fg_fwd + part.c0;
+    const float *fg = A.fg_fwd;
     float cn[7][8], cp[K - 7][8];
 #pragma unroll
     for (int j = 0; j < 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * ts + idx_n + r];
+        for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * ts + part.col(idx_n) + r];
 #pragma unroll
     for (int j = 0; j < K - 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * ts + idx_p + p_reg_idx2<K>(r)];
+        for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
+            cp[j][r] = (!kVirt || 8 + j <= part.n_log) ? fg[(7 + j) * ts + part.col(idx_p + p_reg_idx2<K>(r))] : 0.0f;
     {
-        const float *scale = (kHalf ? A.fm_fwd : A.fd_fwd) + part.c0;
+        const float *scale = kHalf ? A.fm_fwd : A.fd_fwd;
         float d[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) d[r] = scale[idx_n + r];
+        for (int r = 0; r < 8; ++r) d[r] = scale[part.col(idx_n) + r];
         lds_write_n2(dtab, an, d);
     }
-    const T *x = (const T *)A.x + A.row0 * A.ld_in + part.c0 + idx_n;
+    const T *x = (const T *)A.x + A.row0 * A.ld_in + part.c0;
+    // kVirt: a sub-row missing from the last block reads the block's first row instead (its dy will be zero)
+    const uint32_t off_x = part.off(idx_n, A.sub_ld_in), off_x0 = part.off(idx_n & part.tmask, A.sub_ld_in);
+    const bool gap = part.in_tail_gap(idx_n);
+    auto load_row = [&](int64_t r) { return load8(x + r * A.ld_in + ((gap && r == part.tail_row) ? off_x0 : off_x)); };
     float *xk = A.xk + part.c0 + idx_n;
     int64_t row = part.slot;
     if (row >= A.rows) return;
-    Raw8 raw = load8(x + row * A.ld_in);
+    Raw8 raw = load_row(row);
     for (; row < A.rows; row += part.nslots) {
         float u[8];
         unpack8(raw, u, (const T *)nullptr);
         const int64_t next = row + part.nslots;
-        if (next < A.rows) raw = load8(x + next * A.ld_in);
+        if (next < A.rows) raw = load_row(next);
         reg_layer_first<0>(u, cn[0]);
         reg_layer<1>(u, cn[1]);
         reg_layer<2>(u, cn[2]);
@@ -244,7 +274,7 @@ __global__ __launch_bounds__(G::threads) void bwd_f_kernel(BwdFastArgs A)
         lds_read_n2(dtab, an, d);
 #pragma unroll
         for (int r = 0; r < 8; ++r) u[r] *= d[r];
-        store8(xk + row * ts, u);
+        store8(xk + row * xs, u);
     }
 }
 
@@ -382,22 +412,24 @@ __device__ __forceinline__ float lane_partner(float v, int j)
     return j == 0 ? dpp_get<0xB1>(v) : j == 1 ? dpp_get<0x4E>(v) : j == 2 ? dpp_get<0x141>(v) : dpp_get<0x128>(v);
 }
 
-// Deferred sums -> dtheta partials of this workgroup.  part: its slice; fw: plan table fw_inv at this block's
-// first column, rows `stride` apart; c0: that column; a slice holds stride / 2 angles per layer.
-__device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx_p, const float *fw_inv, int stride, int c0,
-                                           int first)
+// Deferred sums -> dtheta partials of this workgroup.  part: its slice, `pairs` sums per layer, indexed by the
+// pair's position in the whole kernel row (c0 + element); fw_inv: the plan table, rows `stride` apart, column
+// (c0 + element) & tmask.
+__device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx_p, const float *fw_inv, int stride, int tmask,
+                                           int pairs, int c0, int n_log, int first)
 {
 #pragma unroll
     for (int J = 1; J <= 2; ++J) {  // register layers
         const int i = (J == 2) ? K : K - 1;
+        if (i > n_log) continue;  // a layer the transform does not have: no table row, nothing to write
         const float *fw = fw_inv + (size_t)(i - 1) * stride;
         int q = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
-                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw[a] * fw[b]);
-                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + a, i), v, first);
+                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw[(c0 + a) & tmask] * fw[(c0 + b) & tmask]);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), v, first);
                 ++q;
             }
         }
@@ -405,6 +437,7 @@ __device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx
 #pragma unroll
     for (int j = 0; j < 3; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7
         const int i = 8 + j;
+        if (i > n_log) continue;
         const float *fw = fw_inv + (size_t)(i - 1) * stride;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -413,14 +446,14 @@ __device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx
             const int e = idx_p + p_reg_idx2<K>(r);
             if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + e, i), (mine - other) * (fw[e] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw[(c0 + e) & tmask] * fw[(c0 + b) & tmask]), first);
             }
         }
     }
 }
 
-__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int stride, int c0,
-                                           int first)
+__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int stride, int tmask,
+                                           int pairs, int c0, int n_log, int first)
 {
 #pragma unroll
     for (int J = 0; J < 3; ++J) {  // layers 1..3
@@ -431,7 +464,7 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx + r, b = idx + (r | (1 << J));
-                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + a, i), acc.r[J][q] * (fw[a] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), acc.r[J][q] * (fw[(c0 + a) & tmask] * fw[(c0 + b) & tmask]), first);
                 ++q;
             }
         }
@@ -447,9 +480,37 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
             const int e = idx + r;
             if (!(e & (1 << (i - 1)))) {
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * (stride / 2) + pair_index(c0 + e, i), (mine - other) * (fw[e] * fw[b]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw[(c0 + e) & tmask] * fw[(c0 + b) & tmask]), first);
             }
         }
+    }
+}
+
+// store8 through a raw buffer descriptor: the hardware drops every access that reaches past `bytes` from
+// `base`, which masks lanes without a branch.  off: byte offset of the lane's 8 elements.
+typedef int bwd_v4i __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ void store8_bounded(T *base, uint32_t bytes, uint32_t off, const float (&y)[8])
+{
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+    if constexpr (sizeof(T) == 4) {
+        bwd_v4i a = {(int)__float_as_uint(y[0]), (int)__float_as_uint(y[1]), (int)__float_as_uint(y[2]), (int)__float_as_uint(y[3])};
+        bwd_v4i b = {(int)__float_as_uint(y[4]), (int)__float_as_uint(y[5]), (int)__float_as_uint(y[6]), (int)__float_as_uint(y[7])};
+        __builtin_amdgcn_raw_buffer_store_b128(a, rs, (int)off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(b, rs, (int)off + 16, 0, 0);
+    } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (std::is_same<T, __half>::value) {
+                const __half2 h = __halves2half2(__float2half_rn(y[2 * i]), __float2half_rn(y[2 * i + 1]));
+                w[i] = *(const uint32_t *)&h;
+            } else {
+                w[i] = f32x2_to_bf16x2_bits(y[2 * i], y[2 * i + 1]);
+            }
+        }
+        bwd_v4i a = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(a, rs, (int)off, 0, 0);
     }
 }
 
@@ -473,13 +534,14 @@ constexpr int kPnThreads = 1024;
 constexpr int kPnLdsLayers = 4;
 constexpr size_t kPnLdsFloats = 4 * (size_t)G::kRowFloats + (1 + kPnLdsLayers) * (size_t)G::n;
 
-template <typename T, bool kDx, bool kHalf>
+template <typename T, bool kDx, bool kHalf, bool kVirt>
 __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
 {
     extern __shared__ float lds[];
     if (plan_is_bad(A)) return;
-    const Part<kHalf> pt;
-    constexpr int ts = Part<kHalf>::stride;
+    const Part<kHalf, kVirt> pt(A);
+    const int ts = pt.ts;
+    constexpr int xs = Part<kHalf, kVirt>::xs;
     const int role = threadIdx.x >> 9;  // uniform per wave
     const int tid = threadIdx.x & 511, wave = tid >> 6, lane = tid & 63;
     const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
@@ -487,7 +549,7 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
     float *hand = lds + 2 * G::kRowFloats;
     const int64_t mine = A.rows > (int64_t)pt.slot ? (A.rows - pt.slot + pt.nslots - 1) / pt.nslots : 0;
     float *part = A.partial + (size_t)pt.slot * A.slice_floats;
-    const float *fg = A.fg_inv + pt.c0, *fw = A.fw_inv + pt.c0;
+    const float *fg = A.fg_inv, *fw = A.fw_inv;
     if (role == 0) {
         const int idx_p = base_p2<K>(wave, lane);
         const int ap = lds_addr2(idx_p);
@@ -495,11 +557,12 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
 #pragma unroll
         for (int j = 0; j < 5; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cp[j][r] = fg[(7 + j) * ts + idx_p + p_reg_idx2<K>(r)];
+            for (int r = 0; r < 8; ++r)
+                cp[j][r] = (!kVirt || 8 + j <= pt.n_log) ? fg[(7 + j) * ts + pt.col(idx_p + p_reg_idx2<K>(r))] : 0.0f;
         float c13[8], acc13[8];  // kHalf only: layer 13 in layout N (it pairs column e with e + 4096)
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            c13[r] = kHalf ? fg[12 * ts + idx_n + r] : 0.0f;
+            c13[r] = kHalf ? fg[12 * ts + pt.col(idx_n) + r] : 0.0f;
             acc13[r] = 0.0f;
         }
         PAcc acc;
@@ -507,12 +570,16 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         // uniform row pointers + 32-bit per-thread byte offsets: the loads take their base from scalar
         // registers and no 64-bit per-thread pointer stays live across the loop
         const T *dy = (const T *)A.dy + A.row0 * A.ld_in + pt.c0;
-        const T *dyo = (const T *)A.dy + A.row0 * A.ld_in + (pt.c0 ^ G::n);  // the other half
+        const T *dyo = (const T *)A.dy + A.row0 * A.ld_in + (pt.c0 ^ G::n);  // the other half (kHalf)
         const float *xk = A.xk + pt.c0;
+        // kVirt: a sub-row missing from the last block reads the block's first row; its gradient is zeroed below
+        const uint32_t off_g = pt.off(idx_n, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const uint32_t off_g0 = pt.off(idx_n & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const bool gap = pt.in_tail_gap(idx_n);
         auto fetch = [&](int64_t r, float(&ox)[8], Raw8 &og, Raw8 &ogo) {
-            uint32_t offx = (uint32_t)idx_n * 4u, offg = (uint32_t)idx_n * (uint32_t)sizeof(T);
+            uint32_t offx = (uint32_t)idx_n * 4u, offg = (gap && r == pt.tail_row) ? off_g0 : off_g;
             asm volatile("" : "+v"(offx), "+v"(offg));
-            load8_f32((const float *)((const char *)(xk + r * ts) + offx), ox);
+            load8_f32((const float *)((const char *)(xk + r * xs) + offx), ox);
             og = load8((const T *)((const char *)(dy + r * A.ld_in) + offg));
             if (kHalf) ogo = load8((const T *)((const char *)(dyo + r * A.ld_in) + offg));
         };
@@ -525,6 +592,10 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
 #pragma unroll
             for (int r = 0; r < 8; ++r) vx[r] = nx[r];
             unpack8(ng, vg, (const T *)nullptr);
+            if (gap && row == pt.tail_row) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) vg[r] = 0.0f;
+            }
             if (kHalf) {
                 // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
                 // (its coefficient is the negative of this half's: both scales are still 1)
@@ -551,14 +622,14 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         }
         __syncthreads();  // the other group's last row
         __syncthreads();
-        finalize_p(part, acc, idx_p, fw, ts, pt.c0, A.first_chunk);
+        finalize_p(part, acc, idx_p, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, A.first_chunk);
         if (kHalf) {
             // sum of layer 13 = (scale after the layer)^2 * deferred sum; the lower half's share goes to the
             // layer's place in the slice, the upper half's, negated, behind the slice's regular part
             float *dst = part + (size_t)(pt.half ? 13 : 12) * G::n + idx_n;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                const float d = fw[11 * ts + idx_n + r];
+                const float d = fw[11 * ts + pt.col(idx_n) + r];
                 const float v = acc13[r] * (d * d);
                 put_partial(dst + r, pt.half ? -v : v, A.first_chunk);
             }
@@ -566,12 +637,15 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
     } else {
         float *dtab = lds + 4 * G::kRowFloats;  // tables written and read by the same thread
         CoefSplit<kPnLdsLayers> cn;
-        cn.load(fg, ts, idx_n, dtab + G::n, tid);
-        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + pt.c0 + idx_n);
-        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + pt.c0 + idx_n + 4);
+        cn.load(fg, ts, pt.col(idx_n), dtab + G::n, tid);
+        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + pt.col(idx_n));
+        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + pt.col(idx_n) + 4);
         NAcc acc;
         acc.clear();
         T *dx = (T *)A.dx + A.row0 * A.ld_out + pt.c0;  // used only if kDx
+        const uint32_t off_dx = pt.off(idx_n, A.sub_ld_out) * (uint32_t)sizeof(T);
+        const uint32_t block_bytes = (uint32_t)(((G::n >> pt.n_log) - 1) * A.sub_ld_out + pt.ts) * (uint32_t)sizeof(T);
+        const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.ts) * (uint32_t)sizeof(T) : 0u;
         __syncthreads();  // the other group's first row
         __syncthreads();
         int64_t row = pt.slot;
@@ -585,19 +659,23 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
                 const float4 da = ((const float4 *)dtab)[tid], db = ((const float4 *)dtab)[512 + tid];
                 vg[0] *= da.x; vg[1] *= da.y; vg[2] *= da.z; vg[3] *= da.w;
                 vg[4] *= db.x; vg[5] *= db.y; vg[6] *= db.z; vg[7] *= db.w;
-                uint32_t off = (uint32_t)idx_n * (uint32_t)sizeof(T);
+                uint32_t off = off_dx;
                 asm volatile("" : "+v"(off));
-                store8((T *)((char *)(dx + row * A.ld_out) + off), vg);
+                if (kVirt)  // the short last block stores only the rows it has
+                    store8_bounded(dx + row * A.ld_out, row == pt.tail_row ? tail_bytes : block_bytes, off, vg);
+                else
+                    store8((T *)((char *)(dx + row * A.ld_out) + off), vg);
             }
             __syncthreads();  // B2
         }
-        finalize_n(part, acc, idx_n, fw, ts, pt.c0, A.first_chunk);
+        finalize_n(part, acc, idx_n, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, A.first_chunk);
     }
 }
 
-// dtheta[q] = sum over slices of partial[s][q] (+ the upper-half share of the last layer where a slice has
+// out[q] = sum over slices of partial[s][q] (+ the upper-half share of the last layer where a slice has
 // one), in double, slice order; skipped for flagged plans
-__global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dtheta, size_t n_angles,
+template <typename Out>
+__global__ void bwd_reduce_kernel(const float *__restrict__ partial, Out *__restrict__ out, size_t n_angles,
                                   size_t slice_floats, size_t last_layer_at, int n_parts, const int *bad_fwd,
                                   const int *bad_inv)
 {
@@ -611,67 +689,115 @@ __global__ void bwd_reduce_kernel(const float *__restrict__ partial, float *__re
         acc += (double)s[q];
         if (extra && q >= last_layer_at) acc += (double)s[q + extra];
     }
+    out[q] = (Out)acc;
+}
+
+// n < 4096: the sums of a 4096-point block hold, per layer, the 4096 / n rows of the block side by side;
+// dtheta[i][p] = sum over those rows, in row order
+__global__ void bwd_fold_kernel(const double *__restrict__ sums, float *__restrict__ dtheta, int n_log, const int *bad_fwd,
+                                const int *bad_inv)
+{
+    if ((*bad_fwd | *bad_inv) != 0) return;
+    const int half = 1 << (n_log - 1);
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n_log * half) return;
+    const int layer = q >> (n_log - 1), p = q & (half - 1);
+    double acc = 0.0;
+    for (int sub = 0; sub < (G::n >> n_log); ++sub) acc += sums[layer * (G::n / 2) + sub * half + p];
     dtheta[q] = (float)acc;
 }
 
 // ---- host side -----------------------------------------------------------------------------------
 // Slices = row slots of the PN kernel, which runs one workgroup per compute unit (n = 8192: two per slot).
-static int bwd_fast_slices(int k) { return k == 12 ? 256 : 128; }
+static int bwd_fast_slices(int k) { return k == 13 ? 128 : 256; }
 static constexpr int kBwdFGrid = 512;
-// Rows per chunk bound the float32 intermediate in the workspace (2^30 elements, 4 GiB).  Small chunks that
-// would stay in the last-level cache measured slower: every launch re-reads the coefficients and rewrites
-// the partial slices, which only amortises over many rows per workgroup.
-static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (30 - k); }
-static size_t bwd_fast_slice_floats(int k) { return (size_t)k * ((size_t)1 << (k - 1)) + (k == 13 ? 4096 : 0); }
+// Kernel rows (of 4096 or 8192 elements) per chunk bound the float32 intermediate in the workspace (2^30
+// elements, 4 GiB).  Small chunks that would stay in the last-level cache measured slower: every launch
+// re-reads the coefficients and rewrites the partial slices, which only amortises over many rows per workgroup.
+static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (k == 13 ? 17 : 18); }
+static size_t bwd_fast_slice_floats(int k) { return k == 13 ? (size_t)13 * 4096 + 4096 : (size_t)K * (G::n / 2); }
+static int64_t bwd_fast_kernel_rows(const Shape &s)
+{
+    const int64_t r = s.k < K ? (int64_t)G::n >> s.k : 1;
+    return (s.rows + r - 1) / r;
+}
 
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
 {
-    if (!(s.k == 12 || s.k == 13) || s.heads != 1 || dtheta == nullptr || s.rows == 0) return false;
+    if (s.k < 8 || s.k > 13 || s.heads != 1 || dtheta == nullptr || s.rows == 0) return false;
     const int vec = s.dtype == BQ_F32 ? 4 : 8;
     if (((uintptr_t)x & 15) || ((uintptr_t)dy & 15) || (dx && ((uintptr_t)dx & 15))) return false;
     if ((s.ld_x % vec) || (s.ld_y % vec)) return false;
+    if (s.k < K) {  // offsets inside a block of 4096 / n rows are 32-bit byte offsets
+        const int64_t r = (int64_t)G::n >> s.k;
+        if (r * s.ld_x * 4 >= ((int64_t)1 << 31) || r * s.ld_y * 4 >= ((int64_t)1 << 31)) return false;
+    }
     return true;
 }
 
+static size_t bwd_fast_fold_bytes(int k) { return k < K ? align256((size_t)K * (G::n / 2) * sizeof(double)) : 0; }
+
 size_t bwd_fast_workspace_bytes(const Shape &s)
 {
-    const size_t chunk = (size_t)(s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k));
-    return align256((size_t)bwd_fast_slices(s.k) * bwd_fast_slice_floats(s.k) * sizeof(float)) +
-           align256(chunk * s.n * sizeof(float));
+    const int64_t kr = bwd_fast_kernel_rows(s);
+    const size_t chunk = (size_t)(kr < bwd_fast_chunk_rows(s.k) ? kr : bwd_fast_chunk_rows(s.k));
+    return align256((size_t)bwd_fast_slices(s.k) * bwd_fast_slice_floats(s.k) * sizeof(float)) + bwd_fast_fold_bytes(s.k) +
+           align256(chunk * (s.k == 13 ? 8192 : 4096) * sizeof(float));
 }
 
-template <typename T, bool kHalf>
+template <typename T, bool kHalf, bool kVirt>
 static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta, char *ws, hipStream_t stream)
 {
-    const size_t angles = (size_t)s.k * (s.n / 2);
     const int slices = bwd_fast_slices(s.k);
-    const int64_t chunk_rows = s.rows < bwd_fast_chunk_rows(s.k) ? s.rows : bwd_fast_chunk_rows(s.k);
+    const int64_t kernel_rows = bwd_fast_kernel_rows(s);
+    const int64_t chunk_rows = kernel_rows < bwd_fast_chunk_rows(s.k) ? kernel_rows : bwd_fast_chunk_rows(s.k);
     A.slice_floats = (int64_t)bwd_fast_slice_floats(s.k);
     A.partial = (float *)ws;
-    A.xk = (float *)(ws + align256((size_t)slices * A.slice_floats * sizeof(float)));
+    double *fold = (double *)(ws + align256((size_t)slices * A.slice_floats * sizeof(float)));
+    A.xk = (float *)((char *)fold + bwd_fast_fold_bytes(s.k));
     const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_pn = kPnLdsFloats * sizeof(float);
-    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
+    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
+    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false, kHalf>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
+    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
     if (e != hipSuccess) return e;
     const int pn_grid = kHalf ? 2 * slices : slices;  // kHalf: a multiple of 16 (see Part)
-    for (int64_t r0 = 0; r0 < s.rows; r0 += chunk_rows) {
+    for (int64_t r0 = 0; r0 < kernel_rows; r0 += chunk_rows) {
         A.row0 = r0;
-        A.rows = s.rows - r0 < chunk_rows ? s.rows - r0 : chunk_rows;
+        A.rows = kernel_rows - r0 < chunk_rows ? kernel_rows - r0 : chunk_rows;
         A.first_chunk = (r0 == 0);
         // every slice must be written by the first chunk, so the grids do not shrink with the row count
-        hipLaunchKernelGGL((bwd_f_kernel<T, kHalf>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
+        hipLaunchKernelGGL((bwd_f_kernel<T, kHalf, kVirt>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
         if (A.dx)
-            hipLaunchKernelGGL((bwd_pn_kernel<T, true, kHalf>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
+            hipLaunchKernelGGL((bwd_pn_kernel<T, true, kHalf, kVirt>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
         else
-            hipLaunchKernelGGL((bwd_pn_kernel<T, false, kHalf>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
+            hipLaunchKernelGGL((bwd_pn_kernel<T, false, kHalf, kVirt>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
     }
-    const unsigned blocks = (unsigned)((angles + 255) / 256);
-    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, angles,
-                       (size_t)A.slice_floats, (size_t)(s.k - 1) * (s.n / 2), slices, A.bad_fwd, A.bad_inv);
+    if (kVirt) {
+        const size_t sums = (size_t)s.k * (G::n / 2);  // the layers the transform has
+        hipLaunchKernelGGL(bwd_reduce_kernel<double>, dim3((unsigned)((sums + 255) / 256)), dim3(256), 0, stream,
+                           (const float *)ws, fold, sums, (size_t)A.slice_floats, sums, slices, A.bad_fwd, A.bad_inv);
+        const unsigned angles = (unsigned)(s.k * (s.n / 2));
+        hipLaunchKernelGGL(bwd_fold_kernel, dim3((angles + 255) / 256), dim3(256), 0, stream, (const double *)fold, dtheta, s.k,
+                           A.bad_fwd, A.bad_inv);
+    } else {
+        const size_t angles = (size_t)s.k * (s.n / 2);
+        hipLaunchKernelGGL(bwd_reduce_kernel<float>, dim3((unsigned)((angles + 255) / 256)), dim3(256), 0, stream,
+                           (const float *)ws, dtheta, angles, (size_t)A.slice_floats, (size_t)(s.k - 1) * (s.n / 2), slices,
+                           A.bad_fwd, A.bad_inv);
+    }
     return hipGetLastError();
+}
+
+template <bool kHalf, bool kVirt>
+static hipError_t launch_bwd_fast_d(const BwdFastArgs &A, const Shape &s, float *dtheta, char *ws, hipStream_t stream)
+{
+    switch (s.dtype) {
+        case BQ_F32: return launch_bwd_fast_t<float, kHalf, kVirt>(A, s, dtheta, ws, stream);
+        case BQ_F16: return launch_bwd_fast_t<__half, kHalf, kVirt>(A, s, dtheta, ws, stream);
+        default: return launch_bwd_fast_t<bf16_t, kHalf, kVirt>(A, s, dtheta, ws, stream);
+    }
 }
 
 hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
@@ -689,21 +815,18 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     A.fw_inv = pv.fw_inv;
     A.bad_fwd = &pv.hdr->fast_bad_fwd;
     A.bad_inv = &pv.hdr->fast_bad_inv;
-    A.ld_in = s.ld_x;
-    A.ld_out = s.ld_y;
+    A.n = s.n;
+    A.n_log = s.k;
+    A.total_rows = s.rows;
+    A.sub_ld_in = s.ld_x;
+    A.sub_ld_out = s.ld_y;
+    const int64_t block_rows = s.k < K ? (int64_t)G::n >> s.k : 1;
+    A.ld_in = s.ld_x * block_rows;
+    A.ld_out = s.ld_y * block_rows;
     char *w = (char *)ws;
-    if (s.k == 12) {
-        switch (s.dtype) {
-            case BQ_F32: return launch_bwd_fast_t<float, false>(A, s, dtheta, w, stream);
-            case BQ_F16: return launch_bwd_fast_t<__half, false>(A, s, dtheta, w, stream);
-            default: return launch_bwd_fast_t<bf16_t, false>(A, s, dtheta, w, stream);
-        }
-    }
-    switch (s.dtype) {
-        case BQ_F32: return launch_bwd_fast_t<float, true>(A, s, dtheta, w, stream);
-        case BQ_F16: return launch_bwd_fast_t<__half, true>(A, s, dtheta, w, stream);
-        default: return launch_bwd_fast_t<bf16_t, true>(A, s, dtheta, w, stream);
-    }
+    if (s.k < K) return launch_bwd_fast_d<false, true>(A, s, dtheta, w, stream);
+    if (s.k == K) return launch_bwd_fast_d<false, false>(A, s, dtheta, w, stream);
+    return launch_bwd_fast_d<true, false>(A, s, dtheta, w, stream);
 }
 
 }  // namespace bq

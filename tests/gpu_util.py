@@ -60,20 +60,32 @@ def run_fwd_quant(x_store, theta, n, heads, dtype, bits, group, scale_dtype):
     return codes.cpu().numpy(), scales.float().cpu().numpy()
 
 
-def run_bwd(x_store, dy_store, theta, n, heads, dtype, want_dx=True, want_dtheta=True):
+def run_bwd(x_store, dy_store, theta, n, heads, dtype, want_dx=True, want_dtheta=True, pad=0):
     import torch
 
     th = torch.from_numpy(np.ascontiguousarray(theta)).to("cuda:0")
     plan = B.alloc_plan(th, n, heads)
     x = _dev(x_store, dtype)
     dy = _dev(dy_store, dtype)
-    dx = torch.empty_like(x) if want_dx else None
+    if pad:  # x and dy share one row stride; the padding holds NaN and must be neither read nor written
+        w = x.shape[1]
+        xp = torch.full((x.shape[0], w + pad), float("nan"), dtype=x.dtype, device=x.device)
+        dyp = torch.full_like(xp, float("nan"))
+        xp[:, :w] = x
+        dyp[:, :w] = dy
+        x, dy = xp[:, :w], dyp[:, :w]
+    dx = None
+    if want_dx:
+        dx = torch.full((x.shape[0], x.shape[1] + pad), 7.0, dtype=x.dtype, device=x.device)[:, :x.shape[1]]
     dth = torch.full(theta.shape, 123.0, dtype=torch.float32, device="cuda:0") if want_dtheta else None
-    r = B.make_rows(x, n, heads)
+    r = B.make_rows(x, n, heads, out=dx)
     ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(r)), dtype=torch.uint8, device="cuda:0")
     ws.fill_(0xFF)  # contents on entry must be ignored
     B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, r)
     torch.cuda.synchronize()
+    if want_dx and pad:
+        assert bool((dx._base[:, x.shape[1]:] == 7.0).all()), "padding of dx was written"
+        dx = dx.contiguous()
     return (synth.torch_to_storage(dx, dtype) if want_dx else None,
             dth.cpu().numpy() if want_dtheta else None)
 

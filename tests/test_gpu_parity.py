@@ -303,3 +303,30 @@ def test_mid_sizes_flagged_plan(n):
     gu.check_rotated(gu.run_transform(x, th, n, 1, "f16"), _ref_fwd(x, th, n, 1, "f16"), "f16", "mid flagged fwd")
     gu.check_rotated(gu.run_transform(x, th, n, 1, "f16", inverse=True),
                      oracle.inverse(synth.to_f64(x, "f16"), th, n, 1), "f16", "mid flagged inv")
+
+
+# the backward pass takes the same route: blocks of 4096 / n rows, the last one possibly short
+@pytest.mark.parametrize("n,rows,dtype", MID + [(256, 5, "bf16"), (512, 1, "f32"), (1024, 4 * 300 + 2, "f16")])
+@pytest.mark.parametrize("pad", [0, 24])
+def test_mid_sizes_backward(n, rows, dtype, pad):
+    x, th, dy = synth.small_case(n, rows, dtype, seed=70 + n, with_dy=True, outliers=0)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n)
+    dx, dth = gu.run_bwd(x, dy, th, n, 1, dtype, pad=pad)
+    gu.check_rotated(dx, rdx, dtype, f"mid dx n={n} rows={rows}")
+    gu.check_dtheta(dth, rdth, ab, what=f"mid n={n} rows={rows} {dtype}")
+    _, dth_only = gu.run_bwd(x, dy, th, n, 1, dtype, want_dx=False, pad=pad)
+    np.testing.assert_array_equal(dth, dth_only)
+
+
+@pytest.mark.parametrize("n", [256, 2048])
+def test_mid_sizes_backward_flagged_plan(n):
+    k = n.bit_length() - 1
+    rng = np.random.default_rng(n + 1)
+    th = rng.uniform(-math.pi, math.pi, size=(1, k, n // 2)).astype(np.float32)
+    th[0, 1, ::3] = np.float32(math.pi / 2)
+    th[0, k - 1, :] = np.float32(-math.pi / 2)
+    x, _, dy = synth.small_case(n, 2 * (4096 // n) + 1, "f16", seed=6, with_dy=True, outliers=0)
+    dx, dth = gu.run_bwd(x, dy, th, n, 1, "f16")
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, "f16"), synth.to_f64(dy, "f16"), th, n)
+    gu.check_rotated(dx, rdx, "f16", "mid flagged dx")
+    gu.check_dtheta(dth, rdth, ab, what="mid flagged")
