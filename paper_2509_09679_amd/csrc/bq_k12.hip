@@ -1,511 +1,13 @@
-// Specialised kernels for n = 4096 (k = 12): forward, inverse and fused forward + quantisation.
-//
-// One workgroup of 512 threads owns one transform at a time; thread t holds 8 elements.  All
-// n*k scale-deferred coefficients (bq_internal.h) of the workgroup's head stay in registers (96 + 8
-// per thread) while the workgroup loops over its rows, so a row costs one coalesced 16-byte load per
-// thread, 12 FMAs per element, two LDS transposes and one store.
-//
-//   layout N ("natural"): thread (wave w, lane l) holds idx = 8*chunk + r, chunk = 64 w + e(l),
-//                         r = 0..7.  Layers 1-3 pair registers, layers 4-7 pair lanes of a 16-lane
-//                         row through DPP (bq_cascade.h).
-//   layout P            : thread holds idx = baseP + b0 + 1024 r1 + 2048 r2 (register r' = b0 + 2 r1 +
-//                         4 r2): idx bit 0 and idx bits 10, 11 are register bits, idx bits 7, 8, 9 are
-//                         the chunk bits of lane bits 0..2 (DPP masks 1, 2, 7), idx bit 2 is lane
-//                         bit 3, the remaining idx bits are lane bits 4, 5 and the wave index.
-//                         Layers 8, 9, 10 use DPP, layers 11, 12 pair registers.
-//   forward : A: load N, layers 1..7, write LDS1 | B: read P, layers 8..12, write LDS2 |
-//             C: read N, output scale, quantise or store
-//   inverse : A: load N, write LDS1 | B: read P, layers 12..8, write LDS2 | C: read N, layers 7..1,
-//             output scale, store
-//
-// The three phases of consecutive rows are software-pipelined: iteration `it` of a workgroup runs
-// C(row it-2), B(row it-1), A(row it) and then ONE barrier; LDS1 and LDS2 are double-buffered by row
-// parity, so every read of a buffer is separated from the next write to it by a barrier.
-//
-// LDS accesses are 64-bit (two adjacent floats per lane), which is what reaches the full LDS rate.
-// LDS float address of idx is idx + 2 (idx >> 5) + 2 (idx >> 9).  For a group of 16 lanes the N-side
-// accesses vary idx bits 3..6 and the P-side accesses idx bits 2, 7, 8, 9; in both cases the four
-// bits move the address by 2, 4, 8 and 16 words modulo 32, so the 16 lanes hit 16 different bank
-// pairs (the padding terms supply what the plain index lacks).
-//
-// If the plan flags the scale-deferred tables as unusable (a cosine too close to zero), the cascade
-// of a row runs through LDS with plain (cos, sin) rotations instead; everything else is unchanged.
-#include <type_traits>
-
-#include "bq_cascade.h"
+// n = 256 .. 4096 instantiations of the specialised transform kernels, and the choice between them.
+#include "bq_k12_kernel.h"
 
 namespace bq {
 
-constexpr int kN = 4096, kK = 12, kThreads = 512;
-constexpr int kLdsRow = 4368;  // floats: 4095 + 2*127 + 2*7 + 1, rounded up to a multiple of 4
-// three row buffers plus either the input ring (3 x 8 KB, 16-bit rows) or the output-scale table (32-bit rows)
-constexpr int kFrontFloats = 3 * kN * 2 / 4;  // 6144 floats = 24 KB in front of the row buffers
-static_assert(kFrontFloats >= kLdsRow, "scale table must fit");
-constexpr size_t kLdsBytes = (kFrontFloats + 3 * kLdsRow) * sizeof(float);
-
-struct K12Args {
-    const void *in;
-    void *out;
-    const float *fg;   // [heads][k][n] coefficients of the direction
-    const float *fd;   // [heads][n] output scales
-    const float2 *cs;  // [heads][k][n/2]
-    const int *fast_bad;
-    int64_t rows, ld_in, ld_out;
-    int heads;
-    // quantiser
-    uint8_t *codes;
-    void *scales;
-    unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
-    int group, scale_f16;
-    // transforms of n = 2^n_log < 4096 points (kVirt): a "row" of the kernel is a block of 4096 / n consecutive
-    // rows of the caller; ld_in / ld_out are then the strides between blocks, sub_ld_* the caller's strides
-    int n, n_log;
-    int64_t sub_ld_in, sub_ld_out;
-};
-
-// Element offset, inside a kernel row, of the element with index e (a multiple of 8) of the 4096-point block.
-template <bool kVirt>
-__device__ __forceinline__ uint32_t elem_off(const K12Args &A, int head, int e, int64_t sub_ld)
-{
-    if (!kVirt) return (uint32_t)(head * kN + e);
-    return (uint32_t)((e >> A.n_log) * (int)sub_ld + (e & (A.n - 1)));
-}
-
-__device__ __forceinline__ int lds_addr(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
-constexpr int kPStepR1 = 1024 + 2 * 32 + 2 * 2;  // address step of register bit r1 (idx + 1024)
-constexpr int kPStepR2 = 2 * kPStepR1;           // register bit r2 (idx + 2048)
-
-// thread's base index in layout P
-__device__ __forceinline__ int base_p(int wave, int lane)
-{
-    const int c3 = lane_chunk(lane & 15) & 7;
-    return (c3 << 7) | (((lane >> 3) & 1) << 2) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 3) | (wave << 4);
-}
-__device__ __forceinline__ int p_reg_idx(int r) { return (r & 1) + 1024 * ((r >> 1) & 1) + 2048 * (r >> 2); }
-
-__device__ __forceinline__ void lds_write_n(float *buf, int an, const float (&u)[8])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) *(float2 *)&buf[an + 2 * j] = make_float2(u[2 * j], u[2 * j + 1]);
-}
-__device__ __forceinline__ void lds_read_n(const float *buf, int an, float (&u)[8])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = *(const float2 *)&buf[an + 2 * j];
-        u[2 * j] = v.x;
-        u[2 * j + 1] = v.y;
-    }
-}
-__device__ __forceinline__ void lds_write_p(float *buf, int ap, const float (&u)[8])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        *(float2 *)&buf[ap + (j & 1) * kPStepR1 + (j >> 1) * kPStepR2] = make_float2(u[2 * j], u[2 * j + 1]);
-}
-__device__ __forceinline__ void lds_read_p(const float *buf, int ap, float (&u)[8])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = *(const float2 *)&buf[ap + (j & 1) * kPStepR1 + (j >> 1) * kPStepR2];
-        u[2 * j] = v.x;
-        u[2 * j + 1] = v.y;
-    }
-}
-
-// slow cascade through LDS with (cos, sin); in: u[] in layout N, out: y[] in layout N (true values)
-// n_log < 12: the block holds 4096 >> n_log independent transforms of 2^n_log points (same angles).
-template <bool kInverse>
-__device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const float2 *__restrict__ cs, int idx_n,
-                                             int n_log = kK)
-{
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 8; ++r) buf[idx_n + r] = u[r];
-    __syncthreads();
-    const int half_n = 1 << (n_log - 1);
-    for (int step = 0; step < n_log; ++step) {
-        const int i = kInverse ? (n_log - step) : (step + 1);
-        const int h = 1 << (i - 1);
-        for (int p = threadIdx.x; p < kN / 2; p += kThreads) {
-            const float2 w = cs[(size_t)(i - 1) * half_n + (p & (half_n - 1))];
-            const int a = ((p >> (i - 1)) << i) | (p & (h - 1));
-            const float xa = buf[a], xb = buf[a + h];
-            if (!kInverse) {
-                buf[a] = __builtin_fmaf(w.x, xa, -(w.y * xb));
-                buf[a + h] = __builtin_fmaf(w.y, xa, w.x * xb);
-            } else {
-                buf[a] = __builtin_fmaf(w.x, xa, w.y * xb);
-                buf[a + h] = __builtin_fmaf(w.x, xb, -(w.y * xa));
-            }
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int r = 0; r < 8; ++r) u[r] = buf[idx_n + r];
-    __syncthreads();
-}
-
-// Epilogue shared by the fast and the slow loop: y[] holds the rotated values in layout N.
-// kLanes > 0 fixes the group size (8 * kLanes) and kScale fixes the scale type (0 = float32,
-// 1 = binary16) at compile time; kLanes == 0 reads both from the arguments.
-// Addresses are a uniform row base plus a 32-bit per-thread offset.
-struct NoCount {};
-template <int kMode, int kBits>
-struct CountOf {
-    typedef NoCount type;
-};
-template <int kBits>
-struct CountOf<kFwdFake, kBits> {
-    typedef BinCount<kBits> type;
-};
-
-// kFwdFake only: kYq = the dequantised row is stored, kHist = the bins are counted.
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt>
-__device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
-                                           typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins)
-{
-    if (kMode == kFwdFake) {
-        const int lanes = A.group >> 3;  // 1..16 lanes per group
-        float f[8], s;
-        bool ordinary;
-        rounded8<kBits>(y, lanes, A.scale_f16 != 0, f, &s, &ordinary);
-        if (kHist) {
-            auto &bc = (BinCount<kBits> &)bins;
-            count8<kBits>(bc, f, ordinary);
-            if (bc.full()) bc.drain(wg_bins);
-        }
-        if (kYq) {
-            float yq[8];
-            dequant8(f, s, yq);
-            T *out_row = (T *)A.out + row * A.ld_out;
-            uint32_t off = elem_off<kVirt>(A, head, chunk * 8, A.sub_ld_out) * (uint32_t)sizeof(T);
-            asm volatile("" : "+v"(off));
-            store8((T *)((char *)out_row + off), yq);
-        }
-    } else if (kMode != kFwdQuant) {
-        T *out_row = (T *)A.out + row * A.ld_out;
-        uint32_t off = elem_off<kVirt>(A, head, chunk * 8, A.sub_ld_out) * (uint32_t)sizeof(T);
-        asm volatile("" : "+v"(off));
-        store8((T *)((char *)out_row + off), y);
-    } else {
-        const int lanes = kLanes > 0 ? kLanes : (A.group >> 3);  // 1..16 lanes per group
-        const bool f16 = kLanes > 0 ? (kScale != 0) : (A.scale_f16 != 0);
-        float s;
-        const uint32_t packed = quant8<kBits>(y, lanes, f16, &s);
-        const int64_t unit = row * A.heads + head;
-        uint8_t *codes_row = A.codes + unit * (kN * kBits / 8);
-        uint32_t coff = (uint32_t)(chunk * kBits);
-        asm volatile("" : "+v"(coff));
-        if (kBits == 2)
-            *(uint16_t *)(codes_row + coff) = (uint16_t)packed;
-        else
-            *(uint32_t *)(codes_row + coff) = packed;
-        // every lane of a group stores the group's scale (same value, same address): no divergence
-        const int groups = (kN / 8) / lanes;
-        uint32_t goff = ((uint32_t)chunk / (uint32_t)lanes) * (f16 ? 2u : 4u);
-        asm volatile("" : "+v"(goff));
-        if (f16)
-            *(__half *)((char *)((__half *)A.scales + unit * groups) + goff) = __float2half_rn(s);
-        else
-            *(float *)((char *)((float *)A.scales + unit * groups) + goff) = s;
-    }
-}
-
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false, bool kVirt = false>
-__global__ __launch_bounds__(kThreads, 4) void k12_kernel(K12Args A)
-{
-    __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
-    typename CountOf<kMode, kBits>::type bins;
-    if (kMode == kFwdFake && kHist) {
-        ((BinCount<kBits> &)bins).clear();
-        if (threadIdx.x < 16) wg_bins[threadIdx.x] = 0;
-        __syncthreads();
-    }
-    // kFwdFake: per-thread counts -> workgroup counts -> the caller's counters (every thread gets here)
-    auto flush_bins = [&]() {
-        if (kMode == kFwdFake && kHist) {
-            ((BinCount<kBits> &)bins).drain(wg_bins);
-            __syncthreads();
-            if (threadIdx.x < (1 << kBits) && wg_bins[threadIdx.x]) atomicAdd(&A.hist[threadIdx.x], wg_bins[threadIdx.x]);
-        }
-    };
-    // LDS: [input ring 3 x 8 KB | output-scale table] first (low addresses), then the row buffers L[0..2]
-    extern __shared__ float lds_raw[];
-    float *lds = lds_raw + kFrontFloats;
-    constexpr bool kInverse = (kMode == kInv);
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int chunk = wave * 64 + lane_chunk(lane);
-    const int idx_n = chunk * 8;
-    const int head = blockIdx.x % A.heads;
-    const int64_t row_first = blockIdx.x / A.heads;
-    const int64_t row_step = gridDim.x / A.heads;
-    const uint32_t off_n = elem_off<kVirt>(A, head, idx_n, A.sub_ld_in);  // element offset of the thread inside a row
-    // tables: rows of n entries, indexed inside the transform the element belongs to
-    const int tn = kVirt ? A.n : kN;
-    const int nk = kVirt ? A.n_log : kK;
-    const int tmask = tn - 1;
-    const T *in = (const T *)A.in;
-    if (row_first >= A.rows) return;
-
-    if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
-        const float2 *cs = A.cs + (size_t)head * kK * (kN / 2);  // kVirt: one head
-        for (int64_t row = row_first; row < A.rows; row += row_step) {
-            float u[8];
-            unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
-            slow_cascade<kInverse>(u, lds, cs, idx_n, nk);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row, head, chunk, bins, wg_bins);
-        }
-        flush_bins();
-        return;
-    }
-
-    // coefficients: cn[j][r] for layer j+1 (layout N), cp[j][r'] for layer 8+j (layout P), d[r] (layout N)
-    const int idx_p = base_p(wave, lane);
-    float cn[7][8], cp[5][8];
-    {
-        const float *fg = A.fg + (size_t)head * kK * kN;  // kVirt: one head
-#pragma unroll
-        for (int j = 0; j < 7; ++j)
-#pragma unroll
-            for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * tn + (idx_n & tmask) + r];
-#pragma unroll
-        for (int j = 0; j < 5; ++j)
-#pragma unroll
-            for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
-                cp[j][r] = (!kVirt || 8 + j <= nk) ? fg[(7 + j) * tn + ((idx_p + p_reg_idx(r)) & tmask)] : 0.0f;
-    }
-    const int an = lds_addr(idx_n);
-    const int ap = lds_addr(idx_p);
-    const int64_t n_my = (A.rows - row_first + row_step - 1) / row_step;  // rows of this workgroup
-    int ba = 0, bb = 2, bc = 1;  // buffer (and ring slot) of A(it), B(it-1), C(it-2)
-
-    // Phase B of one row: layers 8..12 (or 12..8) on layout P, in place in its LDS buffer.
-    auto phase_b = [&](float *lb) {
-        float u[8];
-        lds_read_p(lb, ap, u);
-        if (!kInverse) {
-            dpp_layer_xor1(u, cp[0]);
-            dpp_layer_xor2(u, cp[1]);
-            dpp_layer_xor7(u, cp[2]);
-            reg_layer<1>(u, cp[3]);
-            reg_layer<2>(u, cp[4]);
-        } else {
-            reg_layer_first<2>(u, cp[4]);
-            reg_layer<1>(u, cp[3]);
-            dpp_layer_xor7(u, cp[2]);
-            dpp_layer_xor2(u, cp[1]);
-            dpp_layer_xor1(u, cp[0]);
-        }
-        lds_write_p(lb, ap, u);
-    };
-    // Layers of phase A after the first one / layers of phase C before the output scale.
-    auto layers_a = [&](float (&u)[8]) {
-        if (!kInverse) {
-            reg_layer<1>(u, cn[1]);
-            reg_layer<2>(u, cn[2]);
-            dpp_layer_xor1(u, cn[3]);
-            dpp_layer_xor2(u, cn[4]);
-            dpp_layer_xor7(u, cn[5]);
-            dpp_layer_xor8(u, cn[6]);
-        }
-    };
-    auto layers_c = [&](float (&u)[8]) {
-        if (kInverse) {
-            dpp_layer_xor8(u, cn[6]);
-            dpp_layer_xor7(u, cn[5]);
-            dpp_layer_xor2(u, cn[4]);
-            dpp_layer_xor1(u, cn[3]);
-            reg_layer<2>(u, cn[2]);
-            reg_layer<1>(u, cn[1]);
-            reg_layer<0>(u, cn[0]);
-        }
-    };
-    auto rotate_buffers = [&]() {
-        const int t = bc;
-        bc = bb;
-        bb = ba;
-        ba = t;
-    };
-
-    if constexpr (sizeof(T) == 2) {
-        // ---- 16-bit rows: input staged through an LDS ring filled by direct global->LDS loads -------
-        // Two rows per workgroup have to be in flight from HBM to cover its latency, and there are
-        // no registers left to hold them.  global_load_lds_dwordx4 moves 16 bytes per lane straight
-        // into LDS (wave w, lane l -> bytes [1024 w + 16 l, +16) of the ring slot, row order), the
-        // thread later reads its own chunk back with ds_read_b128.  A wave only reads what it loaded
-        // itself, so s_waitcnt vmcnt is the only synchronisation.  These loads and waits are inline
-        // assembly: the compiler would otherwise wait for ALL outstanding loads before any LDS read.
-        // Memory operations of a wave complete in issue order, and per iteration a wave issues one
-        // ring load (in A) and at least kStores stores (in C); row `it` was requested two iterations
-        // earlier, followed by stores, the load of row it+1 and stores again, so at most
-        // 2 kStores + 1 younger operations may still be pending when row `it` is consumed.  The
-        // first four iterations (pipeline fill, fewer stores issued) wait for everything.
-        constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : 1;
-        constexpr uint32_t kSlotBytes = kN * 2;
-        float d[8];
-        {
-            const float *fd = A.fd + (size_t)head * kN;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[(idx_n & tmask) + r];
-        }
-        const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
-        const uint32_t slice = ring0 + (uint32_t)wave * 1024u;                    // this wave's 1 KB of a slot
-        const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * 16u;        // this thread's chunk
-        const uint32_t voff = elem_off<kVirt>(A, head, (wave * 64 + lane) * 8, A.sub_ld_in) * 2u;  // lane's bytes in a row
-        const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
-        auto ring_load = [&](int64_t j, int slot) {
-            const int64_t jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
-            const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
-            const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
-                         :
-                         : "v"(voff), "s"(m0v), "s"(rowp)
-                         : "memory");
-        };
-        ring_load(0, 0);
-        ring_load(1, 1);
-        // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
-        // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
-        // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
-        auto step = [&](auto BA, auto BB, auto BC, int64_t it) {
-            constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
-            float *la = lds + ba * kLdsRow, *lb = lds + bb * kLdsRow, *lc = lds + bc * kLdsRow;
-            if (it < n_my) {  // A(it)
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                u32x4 v;
-                constexpr int ro = ba * (int)kSlotBytes;
-                if (it >= 4) {
-                    if (kStores == 2)
-                        asm volatile("s_waitcnt vmcnt(5)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                    else if (kStores == 1)
-                        asm volatile("s_waitcnt vmcnt(3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                    else
-                        asm volatile("s_waitcnt vmcnt(1)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                } else {
-                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                 : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                }
-                ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
-                Raw8 raw;
-                raw.lo = make_uint4(v.x, v.y, v.z, v.w);
-                float u[8];
-                unpack8(raw, u, (const T *)nullptr);
-                if (!kInverse) reg_layer_first<0>(u, cn[0]);
-                layers_a(u);
-                lds_write_n(la, an, u);
-            }
-            if (it >= 2) {  // C(it-2)
-                float u[8];
-                lds_read_n(lc, an, u);
-                layers_c(u);
-#pragma unroll
-                for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
-            }
-            if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
-            __syncthreads();
-        };
-        typedef std::integral_constant<int, 0> I0;
-        typedef std::integral_constant<int, 1> I1;
-        typedef std::integral_constant<int, 2> I2;
-        const int64_t end = n_my + 2;
-        for (int64_t it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
-            step(I0{}, I2{}, I1{}, it);
-            if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
-            if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
-        }
-    } else {
-        // ---- 32-bit rows: two rows prefetched in registers, output scales kept in LDS ---------------
-        float *dtab = lds_raw;
-        {
-            const float *fd = A.fd + (size_t)head * kN;
-            float d[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[(idx_n & tmask) + r];
-            lds_write_n(dtab, an, d);
-        }
-        __syncthreads();
-        // `raw` holds row `it` on entry and is refilled with row it + 2 (unconditionally: the last two
-        // iterations re-read the last row).
-        auto iteration = [&](int64_t it, Raw8 &raw) {
-            float *la = lds + ba * kLdsRow, *lb = lds + bb * kLdsRow, *lc = lds + bc * kLdsRow;
-            if (it < n_my) {  // A(it)
-                float u[8];
-                unpack8(raw, u, (const T *)nullptr);
-                if (!kInverse) reg_layer_first<0>(u, cn[0]);
-                {
-                    __builtin_amdgcn_sched_barrier(0);
-                    uint32_t off = off_n * (uint32_t)sizeof(T);
-                    asm volatile("" : "+v"(off));
-                    const int64_t nxt = (it + 2 < n_my) ? it + 2 : n_my - 1;
-                    const char *rowp = (const char *)(in + (row_first + nxt * row_step) * A.ld_in);
-                    raw = load8((const T *)(rowp + off));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                layers_a(u);
-                lds_write_n(la, an, u);
-            }
-            if (it >= 2) {  // C(it-2)
-                float u[8];
-                lds_read_n(lc, an, u);
-                layers_c(u);
-                {
-                    float d[8];
-                    lds_read_n(dtab, an, d);
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt>(A, u, row_first + (it - 2) * row_step, head, chunk, bins, wg_bins);
-            }
-            if (it >= 1 && it <= n_my) phase_b(lb);  // B(it-1)
-            __syncthreads();
-            rotate_buffers();
-        };
-        Raw8 raw_even = load8(in + row_first * A.ld_in + off_n);
-        Raw8 raw_odd = raw_even;
-        if (n_my > 1) raw_odd = load8(in + (row_first + row_step) * A.ld_in + off_n);
-        for (int64_t it = 0; it < n_my + 2; it += 2) {
-            iteration(it, raw_even);
-            if (it + 1 < n_my + 2) iteration(it + 1, raw_odd);
-        }
-    }
-    flush_bins();
-}
-
-template <typename T, bool kVirt>
-static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned grid, hipStream_t stream)
-{
-    void (*kern)(K12Args) = nullptr;
-    if (mode == kFwd)
-        kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, kVirt>;
-    else if (mode == kInv)
-        kern = k12_kernel<T, kInv, 4, 0, 0, true, false, kVirt>;
-    else if (mode == kFwdFake) {
-        if (A.out && A.hist)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true, kVirt>;
-        else if (A.out)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false, kVirt>;
-        else
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true, kVirt> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true, kVirt>;
-    } else if (!kVirt && A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1> : k12_kernel<T, kFwdQuant, 4, 16, 1>;
-    else
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, kVirt> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, kVirt>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, A);
-    return hipGetLastError();
-}
-
-// n = 4096 with any number of heads, or one head of n = 256 .. 2048, where 4096 / n consecutive rows form one
-// block of the kernel (k12_block_rows; the caller passes whole blocks only).
+// n = 4096 or 8192 with any number of heads, or one head of n = 256 .. 2048, where 4096 / n consecutive rows
+// form one block of the kernel (k12_block_rows; the caller passes whole blocks only).
 bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q)
 {
-    if (s.n > kN || s.n < 256) return false;
+    if (s.n > 2 * kN || s.n < 256) return false;
     if (s.n < kN && (s.heads != 1 || s.rows < kN / s.n)) return false;
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;  // elements per 16 bytes
@@ -520,7 +22,7 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
     return true;
 }
 
-int k12_block_rows(const Shape &s) { return kN / s.n; }
+int k12_block_rows(const Shape &s) { return s.n < kN ? kN / s.n : 1; }
 
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream)
@@ -532,8 +34,8 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.fd = mode == kInv ? pv.fd_inv : pv.fd_fwd;
     A.cs = pv.cs;
     A.fast_bad = mode == kInv ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
-    const bool virt = s.n < kN;
-    const int block_rows = kN / s.n;  // rows of the caller per kernel row
+    const bool virt = s.n < kN, wide = s.n > kN;
+    const int block_rows = k12_block_rows(s);  // rows of the caller per kernel row
     A.rows = s.rows / block_rows;     // whole blocks only (the caller handles the remainder)
     A.ld_in = s.ld_x * block_rows;
     A.ld_out = s.ld_y * block_rows;
@@ -554,22 +56,14 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  On
     // large batches the fused kernel (VALU-bound) measured fastest with 1024 workgroups, the plain
     // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
-    const int target = (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
+    // n = 8192: one workgroup of 1024 threads per compute unit at a time.
+    const int target = wide ? 512 : (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
     int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * s.heads);
-    if (virt) {
-        switch (s.dtype) {
-            case BQ_F32: return launch_k12_t<float, true>(mode, A, bits, grid, stream);
-            case BQ_F16: return launch_k12_t<__half, true>(mode, A, bits, grid, stream);
-            default: return launch_k12_t<bf16_t, true>(mode, A, bits, grid, stream);
-        }
-    }
-    switch (s.dtype) {
-        case BQ_F32: return launch_k12_t<float, false>(mode, A, bits, grid, stream);
-        case BQ_F16: return launch_k12_t<__half, false>(mode, A, bits, grid, stream);
-        default: return launch_k12_t<bf16_t, false>(mode, A, bits, grid, stream);
-    }
+    if (wide) return launch_k13_dtype(mode, A, bits, grid, s.dtype, stream);
+    if (virt) return launch_k12_dtype<true, false>(mode, A, bits, grid, s.dtype, stream);
+    return launch_k12_dtype<false, false>(mode, A, bits, grid, s.dtype, stream);
 }
 
 }  // namespace bq

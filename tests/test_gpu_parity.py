@@ -330,3 +330,53 @@ def test_mid_sizes_backward_flagged_plan(n):
     rdx, rdth, ab = oracle.backward(synth.to_f64(x, "f16"), synth.to_f64(dy, "f16"), th, n)
     gu.check_rotated(dx, rdx, "f16", "mid flagged dx")
     gu.check_dtheta(dth, rdth, ab, what="mid flagged")
+
+
+# ---- n = 8192: 1024-thread workgroups, both halves of a row side by side, layer 13 across them -----------
+WIDE = [(1, 1, "f16"), (1, 23, "bf16"), (1, 1300, "f16"), (2, 9, "f16"), (1, 11, "f32"), (3, 700, "bf16")]
+
+
+@pytest.mark.parametrize("heads,rows,dtype", WIDE)
+def test_n8192_forward_inverse_padded_inplace(heads, rows, dtype):
+    n = 8192
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=80 + rows)
+    ref = _ref_fwd(x, th, n, heads, dtype)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype), ref, dtype, f"wide fwd H={heads} T={rows}")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, pad=40), ref, dtype, "wide fwd padded")
+    a = gu.run_transform(x, th, n, heads, dtype)
+    b = gu.run_transform(x, th, n, heads, dtype, inplace=True)
+    np.testing.assert_array_equal(a.view(np.uint8), b.view(np.uint8))
+    xi = gu.run_transform(x, th, n, heads, dtype, inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"wide inv H={heads} T={rows}")
+    xi2 = gu.run_transform(x, th, n, heads, dtype, inverse=True, inplace=True)
+    np.testing.assert_array_equal(xi.view(np.uint8), xi2.view(np.uint8))
+
+
+@pytest.mark.parametrize("heads,rows,dtype", [(1, 5, "f16"), (1, 900, "bf16"), (2, 33, "f32")])
+@pytest.mark.parametrize("bits,group,sd", [(4, 128, "f16"), (2, 128, "f16"), (2, 32, "f32"), (4, 64, "f32")])
+def test_n8192_fused_quant_and_fakequant(heads, rows, dtype, bits, group, sd):
+    n = 8192
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=81 + rows)
+    y_ref = _ref_fwd(x, th, n, heads, dtype)
+    codes, scales = gu.run_fwd_quant(x, th, n, heads, dtype, bits, group, sd)
+    gu.check_fused_codes(codes, scales, y_ref, bits, group, sd, dtype, f"wide quant H={heads} T={rows}")
+    yq, hist = gu.run_fwd_fakequant(x, th, n, heads, dtype, bits, group, sd)
+    c = oracle.unpack_codes(codes, bits)
+    want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+    u = np.uint16 if dtype != "f32" else np.uint32
+    np.testing.assert_array_equal(yq.view(u), want.view(u))
+    np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits))
+
+
+def test_n8192_flagged_plan():
+    n, k = 8192, 13
+    rng = np.random.default_rng(8192)
+    th = rng.uniform(-math.pi, math.pi, size=(1, k, n // 2)).astype(np.float32)
+    th[0, 0, ::2] = np.float32(math.pi / 2)
+    th[0, k - 1, :] = np.float32(-math.pi / 2)
+    x, _, _ = synth.small_case(n, 7, "f16", seed=5)
+    gu.check_rotated(gu.run_transform(x, th, n, 1, "f16"), _ref_fwd(x, th, n, 1, "f16"), "f16", "wide flagged fwd")
+    gu.check_rotated(gu.run_transform(x, th, n, 1, "f16", inverse=True),
+                     oracle.inverse(synth.to_f64(x, "f16"), th, n, 1), "f16", "wide flagged inv")
+    codes, scales = gu.run_fwd_quant(x, th, n, 1, "f16", 4, 128, "f16")
+    gu.check_fused_codes(codes, scales, _ref_fwd(x, th, n, 1, "f16"), 4, 128, "f16", "f16", "wide flagged quant")
