@@ -292,6 +292,20 @@ def extra_figures(B, synth, torch, dev):
                         "hbm_frac": round(bpr * T5 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                         "alg_TFLOPps": round(fpr * T5 / (avg * 1e-3) / 1e12, 2),
                         "valu_frac": round(fpr * T5 / (avg * 1e-3) / 1e12 / VALU_PEAK_TFLOPS, 4)}
+    # forward kernels at n=8192 on the same rows (1024-thread workgroups, layer 13 across the halves in LDS)
+    y5 = dx5
+    c5, s5 = B.alloc_quant_outputs(T5, 8192, 1, 2, 128, "f16", dev)
+    q5 = B.make_quant(2, 128, "f16")
+    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x5, y5, plan5, rows5), 10, 3)
+    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(x5, y5, plan5, rows5), 10, 3)
+    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(x5, plan5, c5, s5, q5, rows5), 10, 3)
+    b_f = alg_bytes_per_row("fwd", 8192, 1, 2)
+    b_q = alg_bytes_per_row("fwd_quant", 8192, 1, 2, 2, 128, 2)
+    res["fwd_n8192"] = {"workload": "n=8192, T=65536, bf16: forward, inverse, fused forward + INT2 g128",
+                        "fwd_ms": round(a_f, 4), "fwd_GBps": round(b_f * T5 / (a_f * 1e-3) / 1e9, 1),
+                        "inv_ms": round(a_i, 4), "inv_GBps": round(b_f * T5 / (a_i * 1e-3) / 1e9, 1),
+                        "fwd_quant_ms": round(a_q, 4), "fwd_quant_GBps": round(b_q * T5 / (a_q * 1e-3) / 1e9, 1)}
+    del x5, dy5, dx5, y5, ws5, c5, s5
     # fake-quantised forward (Dequant(Quant(Bx)) + code-bin histogram) on the calibration batch, INT2 g128
     T3 = 262144
     x3, th3, _ = synth.device_rows(3, T3, dev)

@@ -57,7 +57,7 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // large batches the fused kernel (VALU-bound) measured fastest with 1024 workgroups, the plain
     // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
-    const int target = wide ? 512 : (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
+    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
     int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * s.heads);

@@ -123,7 +123,7 @@ __device__ __forceinline__ void lds_read_p(const float *buf, int ap, float (&u)[
 }
 
 // Layer 13 of an 8192-point transform: u[r] += c[r] * (the other half's element at the same position), read
-// from the other half's row buffer two at a time so that few registers are live at once.
+// from the other half's row buffer.
 template <bool kLayoutP>
 __device__ __forceinline__ void cross_layer(const float *other, int addr, const float (&c)[8], float (&u)[8])
 {
@@ -133,7 +133,6 @@ __device__ __forceinline__ void cross_layer(const float *other, int addr, const 
         const float2 v = *(const float2 *)&other[a];
         u[2 * j] = __builtin_fmaf(c[2 * j], v.x, u[2 * j]);
         u[2 * j + 1] = __builtin_fmaf(c[2 * j + 1], v.y, u[2 * j + 1]);
-        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
