@@ -283,23 +283,11 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     const T *in = (const T *)A.in;
     if (row_first >= A.rows) return;
 
-    if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
-        const float2 *cs = A.cs + (size_t)head * kLayers * (kPoints / 2);  // kVirt: one head
-        for (int64_t row = row_first; row < A.rows; row += row_step) {
-            float u[8];
-            unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
-            slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide>(A, u, row, head, chunk_row, bins, wg_bins);
-        }
-        flush_bins();
-        return;
-    }
-
     // coefficients: cn[j][r] for layer j+1 (layout N), cp[j][r'] for layer 8+j (layout P), d[r] (layout N)
     const int idx_p = base_p(wave, lane);
     float cn[7][8], cp[5][8];
     float cw[8];  // kWide: layer 13, in layout N (forward, phase C) or layout P (inverse, phase B)
-    {
+    auto load_coefficients = [&]() {
         const float *fg = A.fg + (size_t)head * kLayers * kPoints;  // kVirt: one head
 #pragma unroll
         for (int j = 0; j < 7; ++j)
@@ -313,7 +301,36 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
 #pragma unroll
         for (int r = 0; r < 8; ++r)
             cw[r] = !kWide ? 0.0f : kInverse ? fg[kK * tn + col0 + idx_p + p_reg_idx(r)] : fg[kK * tn + col0 + idx_n + r];
+    };
+    // Transforms and the fused quantiser are also called with a handful of rows (decoding), where the call's
+    // latency is a chain of memory round trips: there the coefficient loads are issued in front of the branch
+    // on the plan's flag (the empty statements consume their results, which pins them there), so that the two
+    // round trips overlap.
+    constexpr bool kEarlyLoads = (kMode != kFwdFake) && !kWide;  // (not where registers are short anyway)
+    if (kEarlyLoads) {
+        load_coefficients();
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+#pragma unroll
+            for (int j = 0; j < 7; ++j) asm volatile("" ::"v"(cn[j][r]));
+#pragma unroll
+            for (int j = 0; j < 5; ++j) asm volatile("" ::"v"(cp[j][r]));
+            if (kWide) asm volatile("" ::"v"(cw[r]));
+        }
     }
+    if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
+        const float2 *cs = A.cs + (size_t)head * kLayers * (kPoints / 2);  // kVirt: one head
+        for (int64_t row = row_first; row < A.rows; row += row_step) {
+            float u[8];
+            unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
+            slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide>(A, u, row, head, chunk_row, bins, wg_bins);
+        }
+        flush_bins();
+        return;
+    }
+    if (!kEarlyLoads) load_coefficients();
+
     const int an = lds_addr(idx_n);
     const int ap = lds_addr(idx_p);
     const int64_t n_my = (A.rows - row_first + row_step - 1) / row_step;  // rows of this workgroup
