@@ -274,7 +274,17 @@ def extra_figures(B, synth, torch, dev):
                        "avg_ms": round(avg, 4), "rows_per_s": 8192 / (avg * 1e-3),
                        "GBps": round(bpr * 8192 / (avg * 1e-3) / 1e9, 1),
                        "hbm_frac": round(bpr * 8192 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    del bufs, x4
+    # the backward pass on the same shape (everything in registers, no LDS)
+    dy4 = bufs[1]
+    dx4 = torch.empty_like(x4)
+    dth4 = torch.empty_like(theta4)
+    ws4 = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows4)), dtype=torch.uint8, device=dev)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x4, dy4, plan4, dx4, dth4, ws4, rows4), 30, 6)
+    bprb = alg_bytes_per_row("bwd", 128, 32, 2)
+    res["per_head_bwd"] = {"workload": "32 heads x n=128, T=8192, bf16: dx and dtheta", "avg_ms": round(avg, 4),
+                           "rows_per_s": 8192 / (avg * 1e-3), "GBps": round(bprb * 8192 / (avg * 1e-3) / 1e9, 1),
+                           "hbm_frac": round(bprb * 8192 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del bufs, x4, dy4, dx4, ws4
     # backward at n=8192, T=65536, bf16
     T5 = 65536
     x5, th5, dy5 = synth.device_rows(5, T5, dev, want_dy=True)

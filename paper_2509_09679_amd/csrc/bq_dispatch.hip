@@ -35,6 +35,10 @@ size_t bwd_workspace_bytes(const Shape &s)
         const size_t fast = bwd_fast_workspace_bytes(s);
         if (fast > need) need = fast;
     }
+    if (s.k >= 3 && s.k <= 7 && s.rows > 0) {
+        const size_t small = small_bwd_workspace_bytes(s);
+        if (small > need) need = small;
+    }
     return need;
 }
 
@@ -47,6 +51,11 @@ hipError_t launch_bwd(const void *x, const void *dy, const PlanView &pv, void *d
     }
     if (bwd_fast_supported(x, dy, dx, dtheta, s)) {
         hipError_t e = launch_bwd_fast(x, dy, pv, dx, dtheta, ws, s, stream);
+        if (e != hipSuccess) return e;
+        return launch_generic_bwd(x, dy, pv, dx, dtheta, ws, s, stream, /*only_if_bad=*/true);
+    }
+    if (small_bwd_supported(x, dy, dx, dtheta, s)) {
+        hipError_t e = launch_small_bwd(x, dy, pv, dx, dtheta, ws, s, stream);
         if (e != hipSuccess) return e;
         return launch_generic_bwd(x, dy, pv, dx, dtheta, ws, s, stream, /*only_if_bad=*/true);
     }

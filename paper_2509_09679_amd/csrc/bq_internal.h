@@ -130,7 +130,12 @@ size_t bwd_workspace_bytes_generic(const Shape &s);
 hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
                               void *ws, const Shape &s, hipStream_t stream, bool only_if_bad = false);
 
-// n = 4096 / 8192 backward: bq_bwd.hip
+// backward for n = 8 .. 128 (bq_bwd_small.hip)
+bool small_bwd_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s);
+size_t small_bwd_workspace_bytes(const Shape &s);
+hipError_t launch_small_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,
+                            const Shape &s, hipStream_t stream);
+// n = 256 .. 8192 backward: bq_bwd.hip
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s);
 size_t bwd_fast_workspace_bytes(const Shape &s);
 hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta, void *ws,

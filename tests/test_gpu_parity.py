@@ -380,3 +380,34 @@ def test_n8192_flagged_plan():
                      oracle.inverse(synth.to_f64(x, "f16"), th, n, 1), "f16", "wide flagged inv")
     codes, scales = gu.run_fwd_quant(x, th, n, 1, "f16", 4, 128, "f16")
     gu.check_fused_codes(codes, scales, _ref_fwd(x, th, n, 1, "f16"), 4, 128, "f16", "f16", "wide flagged quant")
+
+
+# ---- backward for n = 8 .. 128: everything in registers, one slot of partial sums per row position ----------
+SMALL_BWD = [(8, 1, 1000, "f32"), (8, 256, 19, "f16"), (16, 4, 301, "bf16"), (32, 64, 77, "f16"), (64, 2, 513, "f32"),
+             (64, 32, 40, "bf16"), (128, 1, 1, "f16"), (128, 16, 33, "f32"), (128, 32, 300, "bf16"), (128, 64, 21, "f16")]
+
+
+@pytest.mark.parametrize("n,heads,rows,dtype", SMALL_BWD)
+def test_small_transforms_backward(n, heads, rows, dtype):
+    x, th, dy = synth.small_case(n, rows, dtype, heads=heads, seed=90 + n + heads, with_dy=True, outliers=0)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n, heads)
+    dx, dth = gu.run_bwd(x, dy, th, n, heads, dtype)
+    gu.check_rotated(dx, rdx, dtype, f"small dx n={n} H={heads}")
+    gu.check_dtheta(dth, rdth, ab, what=f"small n={n} H={heads} T={rows} {dtype}")
+    dx_p, dth_p = gu.run_bwd(x, dy, th, n, heads, dtype, pad=16)  # padded rows: same arithmetic, same bits
+    np.testing.assert_array_equal(dth, dth_p)
+    np.testing.assert_array_equal(dx.view(np.uint8), dx_p.view(np.uint8))
+    _, dth_only = gu.run_bwd(x, dy, th, n, heads, dtype, want_dx=False)
+    np.testing.assert_array_equal(dth, dth_only)
+
+
+def test_small_transforms_backward_flagged_plan():
+    n, heads, k = 128, 4, 7
+    rng = np.random.default_rng(77)
+    th = rng.uniform(-math.pi, math.pi, size=(heads, k, n // 2)).astype(np.float32)
+    th[2, 3, ::4] = np.float32(math.pi / 2)
+    x, _, dy = synth.small_case(n, 45, "f16", heads=heads, seed=8, with_dy=True, outliers=0)
+    dx, dth = gu.run_bwd(x, dy, th, n, heads, "f16")
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, "f16"), synth.to_f64(dy, "f16"), th, n, heads)
+    gu.check_rotated(dx, rdx, "f16", "small flagged dx")
+    gu.check_dtheta(dth, rdth, ab, what="small flagged")
