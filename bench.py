@@ -331,6 +331,16 @@ def extra_figures(B, synth, torch, dev):
                         "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
                         "GBps": round(bpr * T3 / (avg * 1e-3) / 1e9, 1),
                         "hbm_frac": round(bpr * T3 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    # the fused kernel with INT4 codes on the same batch
+    c34, s34 = B.alloc_quant_outputs(T3, 4096, 1, 4, 128, "f16", dev)
+    q34 = B.make_quant(4, 128, "f16")
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x3, plan3, c34, s34, q34, rows3), 10, 3)
+    bpr4 = alg_bytes_per_row("fwd_quant", 4096, 1, 2, 4, 128, 2)
+    res["fwd_quant_int4"] = {"workload": "n=4096, T=262144, fp16: fused forward + INT4 g128, fp16 scales",
+                             "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
+                             "GBps": round(bpr4 * T3 / (avg * 1e-3) / 1e9, 1),
+                             "hbm_frac": round(bpr4 * T3 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del c34, s34
     # the same forward kernel with every angle at pi/4 (a signed Hadamard transform): in the scale-deferred
     # form a butterfly layer and a Hadamard layer both cost one FMA-class instruction per element
     import math

@@ -138,3 +138,57 @@ def test_weight_side_rotation_quant_and_gradient(m):
                          dtype, f"weight side m={m}")
     _, ref, ab = oracle.backward(W64, synth.to_f64(dW, dtype), theta, n)
     gu.check_dtheta(dth.cpu().numpy(), ref, ab, what=f"weight side m={m} dtheta")
+
+
+def test_n8192_full_size_forward_inverse_quant():
+    # the rows of the n = 8192 workload (T = 65536, bf16) through forward, inverse and the fused quantiser
+    cfg, T = 5, 65536
+    x, th, _ = synth.device_rows(cfg, T, DEV)
+    wl = synth.make_workload(cfg, rows=1)
+    n, dtype = wl.n, wl.dtype
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, 1)
+    rows = B.make_rows(x, n, 1)
+    pick = torch.as_tensor(_sample_rows(T, 48, 3), device=DEV)
+    xs = synth.torch_to_storage(x[pick], dtype)
+    y_ref = oracle.forward(synth.to_f64(xs, dtype), th, n)
+    y = torch.empty_like(x)
+    B.bq_butterfly_fwd(x, y, plan, rows)
+    torch.cuda.synchronize()
+    ys = synth.torch_to_storage(y[pick], dtype)
+    gu.check_rotated(ys, y_ref, dtype, "n8192 full fwd")
+    xi = torch.empty_like(x)
+    B.bq_butterfly_inv(y, xi, plan, rows)
+    torch.cuda.synchronize()
+    gu.check_rotated(synth.torch_to_storage(xi[pick], dtype), oracle.inverse(synth.to_f64(ys, dtype), th, n), dtype,
+                     "n8192 full inv")
+    nx = torch.linalg.vector_norm(x.float(), dim=1)
+    ny = torch.linalg.vector_norm(y.float(), dim=1)
+    assert torch.all((nx - ny).abs() <= 4e-3 * nx)  # bf16 output rounding
+    del xi, y
+    codes, scales = B.alloc_quant_outputs(T, n, 1, 2, 128, "f16", DEV)
+    B.bq_butterfly_fwd_quant(x, plan, codes, scales, B.make_quant(2, 128, "f16"), rows)
+    torch.cuda.synchronize()
+    gu.check_fused_codes(codes[pick].cpu().numpy(), scales[pick].float().cpu().numpy(), y_ref, 2, 128, "f16", dtype,
+                         "n8192 full int2")
+
+
+def test_workload4_full_size_per_head_backward():
+    # 32 heads x n = 128, T = 8192, bf16: dx and dtheta on the whole batch
+    cfg, T = 4, 8192
+    x, th, dy = synth.device_rows(cfg, T, DEV, want_dy=True)
+    wl = synth.make_workload(cfg, rows=1)
+    n, H, dtype = wl.n, wl.heads, wl.dtype
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, H)
+    rows = B.make_rows(x, n, H)
+    dx = torch.empty_like(x)
+    dth = torch.empty_like(theta)
+    ws = torch.empty(B.bq_butterfly_bwd_workspace_bytes(rows), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
+    torch.cuda.synchronize()
+    xs = synth.to_f64(synth.torch_to_storage(x, dtype), dtype)
+    gs = synth.to_f64(synth.torch_to_storage(dy, dtype), dtype)
+    rdx, rdth, ab = oracle.backward(xs, gs, th, n, H)
+    gu.check_rotated(synth.torch_to_storage(dx, dtype), rdx, dtype, "c4 full dx")
+    gu.check_dtheta(dth.cpu().numpy(), rdth, ab, what="c4 full dtheta")
