@@ -204,7 +204,11 @@ def main() -> int:
             traffic = None
     roofline = {"kernel": "fused forward + INT2 quantisation, n=4096 fp16, group 128", "bound": "hbm",
                 "achieved": fq["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fq["hbm_frac"],
-                "traffic": traffic, "launch_ms": fq["avg_ms"], "alg_bytes_per_launch": fq["alg_bytes_per_row"] * T}
+                "traffic": traffic, "launch_ms": fq["avg_ms"], "alg_bytes_per_launch": fq["alg_bytes_per_row"] * T,
+                # the same launch against the vector-ALU roof (3 n log2 n flop per row; the published fp32 peak
+                # counts packed instructions, which this build does not use)
+                "alu": {"achieved": fq["alg_TFLOPps"], "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": fq["valu_frac"]}}
 
     if args.copy_ref:
         y.copy_(x)
