@@ -115,7 +115,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (rows are independent, so more "
-              "GPUs would each take a slice of the rows; see DESIGN.md)", file=sys.stderr)
+              "GPUs would each take a slice of the rows and add their dtheta once per call)", file=sys.stderr)
         return 2
 
     import torch
