@@ -190,15 +190,21 @@ __device__ __forceinline__ float rcp_f16_valued(float s)
 // 2^(BITS-1) to every field makes all fields non-negative (no borrows between fields); the final
 // XOR takes the bias out again, field by field.
 // Scale, its reciprocal and the products y * inv (clipped where the clip can act) of the thread's 8 channels.
-template <int BITS>
-__device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool scale_f16, float (&t)[8], float *scale_out,
-                                        bool *ordinary_out)
+// max |y| over the thread's 8 channels
+__device__ __forceinline__ float amax8(const float (&y)[8])
 {
     float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fabsf(y[2]));
     m = fmaxf(fmaxf(m, fabsf(y[3])), fabsf(y[4]));
     m = fmaxf(fmaxf(m, fabsf(y[5])), fabsf(y[6]));
-    m = fmaxf(m, fabsf(y[7]));
-    m = lanes_max(m, lanes);
+    return fmaxf(m, fabsf(y[7]));
+}
+
+// kMaxGiven: group_max is the group's max |y|, formed by the caller (groups that reach beyond a 16-lane row)
+template <int BITS, bool kMaxGiven = false>
+__device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool scale_f16, float (&t)[8], float *scale_out,
+                                        bool *ordinary_out, float group_max = -1.0f)
+{
+    const float m = kMaxGiven ? group_max : lanes_max(amax8(y), lanes);
     constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
     constexpr float qmin = -(float)(1 << (BITS - 1));
     float s, inv;
@@ -239,12 +245,13 @@ __device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool sca
 
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
 
-template <int BITS>
-__device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out)
+template <int BITS, bool kMaxGiven = false>
+__device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out,
+                                           float group_max = -1.0f)
 {
     float t[8];
     bool ordinary;
-    scaled8<BITS>(y, lanes, scale_f16, t, scale_out, &ordinary);
+    scaled8<BITS, kMaxGiven>(y, lanes, scale_f16, t, scale_out, &ordinary, group_max);
     uint32_t acc = 0;
 #pragma unroll
     for (int r = 7; r >= 0; --r) acc = (acc << BITS) + __float_as_uint(t[r] + kRoundMagic);
@@ -362,12 +369,12 @@ struct BinCount<4> {
 // the output (fewer values alive at once): rounded8 gives f = t + 1.5 * 2^23 (the code q is f - 1.5 * 2^23,
 // and the low bits of f's pattern hold q in two's complement); Dequant is s * q, one float32 rounding, with
 // the same scale and codes as quant8.
-template <int BITS>
+template <int BITS, bool kMaxGiven = false>
 __device__ __forceinline__ void rounded8(const float (&y)[8], int lanes, bool scale_f16, float (&f)[8], float *s,
-                                         bool *ordinary)
+                                         bool *ordinary, float group_max = -1.0f)
 {
     float t[8];
-    scaled8<BITS>(y, lanes, scale_f16, t, s, ordinary);
+    scaled8<BITS, kMaxGiven>(y, lanes, scale_f16, t, s, ordinary, group_max);
 #pragma unroll
     for (int r = 0; r < 8; ++r) f[r] = t[r] + kRoundMagic;
 }

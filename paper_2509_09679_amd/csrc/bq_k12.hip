@@ -16,7 +16,6 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
     if (s.n < kN && ((int64_t)(kN / s.n) * (s.ld_x > s.ld_y ? s.ld_x : s.ld_y) * isz >= ((int64_t)1 << 31))) return false;
     if (s.heads > 512) return false;
     if (mode == kFwdQuant || mode == kFwdFake) {
-        if (q->group > 128) return false;
         if (mode == kFwdQuant && ((uintptr_t)q->codes & 3)) return false;
     }
     return true;
@@ -61,6 +60,8 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * s.heads);
+    if ((mode == kFwdQuant || mode == kFwdFake) && q->group > 128)
+        return launch_k12_big_dtype(mode, A, bits, grid, s.dtype, virt, wide, stream);
     if (wide) return launch_k13_dtype(mode, A, bits, grid, s.dtype, stream);
     if (virt) return launch_k12_dtype<true, false>(mode, A, bits, grid, s.dtype, stream);
     return launch_k12_dtype<false, false>(mode, A, bits, grid, s.dtype, stream);

@@ -171,6 +171,26 @@ __device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const fl
     __syncthreads();
 }
 
+// max |y| over a group of 256 .. 8192 consecutive channels (up to the whole row): 16-lane rows by DPP, the
+// wave by two lane shuffles, several waves through `wg_max` (one float per wave) and one workgroup barrier.
+// Every thread of the workgroup must call it; successive calls must be separated by a barrier of their own
+// (the row loop's is).
+__device__ __forceinline__ float big_group_max(const float (&y)[8], int group, int wave_row, float *wg_max)
+{
+    float m = row16_max(amax8(y));
+    m = fmaxf(m, __shfl_xor(m, 16));
+    if (group >= 512) m = fmaxf(m, __shfl_xor(m, 32));
+    if (group > 512) {
+        if ((threadIdx.x & 63) == 0) wg_max[wave_row] = m;
+        __syncthreads();
+        const int waves = group >> 9, first = wave_row & ~(waves - 1);
+        float g = wg_max[first];
+        for (int w = 1; w < waves; ++w) g = fmaxf(g, wg_max[first + w]);
+        m = g;
+    }
+    return m;
+}
+
 // Epilogue shared by the fast and the slow loop: y[] holds the rotated values in layout N.
 // kLanes > 0 fixes the group size (8 * kLanes) and kScale fixes the scale type (0 = float32,
 // 1 = binary16) at compile time; kLanes == 0 reads both from the arguments.
@@ -187,15 +207,21 @@ struct CountOf<kFwdFake, kBits> {
 
 // kFwdFake only: kYq = the dequantised row is stored, kHist = the bins are counted.
 // chunk: the thread's group of 8 elements, counted inside the whole row.
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt, bool kWide>
+// kBig: quantiser groups of more than 128 channels (the maximum then comes from big_group_max()).
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt, bool kWide, bool kBig>
 __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
-                                           typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins)
+                                           typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins,
+                                           float *wg_max)
 {
+    constexpr bool big = kBig;
     if (kMode == kFwdFake) {
-        const int lanes = A.group >> 3;  // 1..16 lanes per group
+        const int lanes = A.group >> 3;  // lanes per group
         float f[8], s;
         bool ordinary;
-        rounded8<kBits>(y, lanes, A.scale_f16 != 0, f, &s, &ordinary);
+        if (big)
+            rounded8<kBits, true>(y, lanes, A.scale_f16 != 0, f, &s, &ordinary, big_group_max(y, A.group, chunk >> 6, wg_max));
+        else
+            rounded8<kBits>(y, lanes, A.scale_f16 != 0, f, &s, &ordinary);
         if (kHist) {
             auto &bc = (BinCount<kBits> &)bins;
             count8<kBits>(bc, f, ordinary);
@@ -215,10 +241,14 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
         asm volatile("" : "+v"(off));
         store8((T *)((char *)out_row + off), y);
     } else {
-        const int lanes = kLanes > 0 ? kLanes : (A.group >> 3);  // 1..16 lanes per group
+        const int lanes = kLanes > 0 ? kLanes : (A.group >> 3);  // lanes per group
         const bool f16 = kLanes > 0 ? (kScale != 0) : (A.scale_f16 != 0);
         float s;
-        const uint32_t packed = quant8<kBits>(y, lanes, f16, &s);
+        uint32_t packed;
+        if (big)
+            packed = quant8<kBits, true>(y, lanes, f16, &s, big_group_max(y, A.group, chunk >> 6, wg_max));
+        else
+            packed = quant8<kBits>(y, lanes, f16, &s);
         const int64_t unit = row * A.heads + head;
         uint8_t *codes_row = A.codes + unit * ((kWide ? 2 * kN : kN) * kBits / 8);
         uint32_t coff = (uint32_t)(chunk * kBits);
@@ -239,14 +269,16 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
 }
 
 template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false, bool kVirt = false,
-          bool kWide = false>
+          bool kWide = false, bool kBig = false>
 __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel(K12Args A)
 {
     static_assert(!(kWide && kVirt), "blocks of small transforms are a 4096-point scheme");
+    static_assert(!kBig || ((kMode == kFwdQuant || kMode == kFwdFake) && kLanes == 0), "large groups: general quantiser variants");
     constexpr int kHalves = kWide ? 2 : 1;
     constexpr int kPoints = kHalves * kN;  // n
     constexpr int kLayers = kWide ? kK + 1 : kK;
     __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
+    __shared__ float wg_max[16];                // quantiser groups that span several waves: one maximum per wave
     typename CountOf<kMode, kBits>::type bins;
     if (kMode == kFwdFake && kHist) {
         ((BinCount<kBits> &)bins).clear();
@@ -324,7 +356,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
             slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide>(A, u, row, head, chunk_row, bins, wg_bins);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row, head, chunk_row, bins, wg_bins, wg_max);
         }
         flush_bins();
         return;
@@ -474,7 +506,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                 layers_c(u);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
             }
             if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
             __syncthreads();
@@ -533,7 +565,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
 #pragma unroll
                     for (int r = 0; r < 8; ++r) u[r] *= d[r];
                 }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins);
+                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
             }
             if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
             __syncthreads();
@@ -550,26 +582,29 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     flush_bins();
 }
 
-template <typename T, bool kVirt, bool kWide>
+template <typename T, bool kVirt, bool kWide, bool kBig>
 static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned grid, hipStream_t stream)
 {
-    constexpr bool V = kVirt, W = kWide;
+    constexpr bool V = kVirt, W = kWide, G = kBig;
     void (*kern)(K12Args) = nullptr;
-    if (mode == kFwd)
-        kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
-    else if (mode == kInv)
-        kern = k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
-    else if (mode == kFwdFake) {
+    if (mode == kFwdFake) {
         if (A.out && A.hist)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true, V, W> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true, V, W>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, true, V, W, G> : k12_kernel<T, kFwdFake, 4, 0, 0, true, true, V, W, G>;
         else if (A.out)
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false, V, W> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false, V, W>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, true, false, V, W, G> : k12_kernel<T, kFwdFake, 4, 0, 0, true, false, V, W, G>;
         else
-            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true, V, W> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true, V, W>;
-    } else if (!kVirt && A.group == 128 && A.scale_f16)  // the common activation format: group 128, binary16 scales
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1, true, false, false, W> : k12_kernel<T, kFwdQuant, 4, 16, 1, true, false, false, W>;
-    else
-        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, V, W> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, V, W>;
+            kern = bits == 2 ? k12_kernel<T, kFwdFake, 2, 0, 0, false, true, V, W, G> : k12_kernel<T, kFwdFake, 4, 0, 0, false, true, V, W, G>;
+    } else if (mode == kFwdQuant && (kBig || kVirt || A.group != 128 || !A.scale_f16)) {
+        kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, V, W, G> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, V, W, G>;
+    } else if constexpr (!kBig) {
+        if (mode == kFwd)
+            kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
+        else if (mode == kInv)
+            kern = k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
+        else  // the common activation format: group 128, binary16 scales
+            kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1, true, false, false, W> : k12_kernel<T, kFwdQuant, 4, 16, 1, true, false, false, W>;
+    }
+    if (!kern) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (kWide ? 2 : 1) * kLdsBytes;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
@@ -577,17 +612,20 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     return hipGetLastError();
 }
 
-template <bool kVirt, bool kWide>
+template <bool kVirt, bool kWide, bool kBig = false>
 static hipError_t launch_k12_dtype(Mode mode, const K12Args &A, int bits, unsigned grid, int dtype, hipStream_t stream)
 {
     switch (dtype) {
-        case BQ_F32: return launch_k12_t<float, kVirt, kWide>(mode, A, bits, grid, stream);
-        case BQ_F16: return launch_k12_t<__half, kVirt, kWide>(mode, A, bits, grid, stream);
-        default: return launch_k12_t<bf16_t, kVirt, kWide>(mode, A, bits, grid, stream);
+        case BQ_F32: return launch_k12_t<float, kVirt, kWide, kBig>(mode, A, bits, grid, stream);
+        case BQ_F16: return launch_k12_t<__half, kVirt, kWide, kBig>(mode, A, bits, grid, stream);
+        default: return launch_k12_t<bf16_t, kVirt, kWide, kBig>(mode, A, bits, grid, stream);
     }
 }
 
 // the n = 8192 instantiations live in a translation unit of their own
 hipError_t launch_k13_dtype(Mode mode, const K12Args &A, int bits, unsigned grid, int dtype, hipStream_t stream);
+// ... and so do those for quantiser groups of more than 128 channels (virt: n < 4096, wide: n = 8192)
+hipError_t launch_k12_big_dtype(Mode mode, const K12Args &A, int bits, unsigned grid, int dtype, bool virt, bool wide,
+                                hipStream_t stream);
 
 }  // namespace bq

@@ -411,3 +411,33 @@ def test_small_transforms_backward_flagged_plan():
     rdx, rdth, ab = oracle.backward(synth.to_f64(x, "f16"), synth.to_f64(dy, "f16"), th, n, heads)
     gu.check_rotated(dx, rdx, "f16", "small flagged dx")
     gu.check_dtheta(dth, rdth, ab, what="small flagged")
+
+
+# ---- quantiser groups of more than 128 channels, up to one scale per row (per-token), n = 256 .. 8192 --------
+BIG_GROUPS = [(4096, 256, 19, "f16"), (4096, 512, 5, "bf16"), (4096, 1024, 33, "f32"), (4096, 4096, 300, "f16"),
+              (8192, 512, 7, "bf16"), (8192, 2048, 3, "f16"), (8192, 8192, 130, "f16"), (512, 256, 8 * 5 + 3, "f16"),
+              (512, 512, 8 * 40, "bf16"), (2048, 2048, 2 * 9 + 1, "f32"), (1024, 512, 4 * 7, "f16")]
+
+
+@pytest.mark.parametrize("n,group,rows,dtype", BIG_GROUPS)
+@pytest.mark.parametrize("bits,sd", [(4, "f16"), (2, "f32")])
+def test_large_quantiser_groups(n, group, rows, dtype, bits, sd):
+    x, th, _ = synth.small_case(n, rows, dtype, seed=100 + n + group)
+    y_ref = _ref_fwd(x, th, n, 1, dtype)
+    codes, scales = gu.run_fwd_quant(x, th, n, 1, dtype, bits, group, sd)
+    gu.check_fused_codes(codes, scales, y_ref, bits, group, sd, dtype, f"big group n={n} g={group}")
+    yq, hist = gu.run_fwd_fakequant(x, th, n, 1, dtype, bits, group, sd)
+    c = oracle.unpack_codes(codes, bits)
+    want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+    u = np.uint16 if dtype != "f32" else np.uint32
+    np.testing.assert_array_equal(yq.view(u), want.view(u))
+    np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits))
+
+
+def test_large_quantiser_groups_flagged_plan():
+    n, k = 4096, 12
+    th = np.random.default_rng(3).uniform(-math.pi, math.pi, size=(1, k, n // 2)).astype(np.float32)
+    th[0, 5, ::7] = np.float32(math.pi / 2)
+    x, _, _ = synth.small_case(n, 9, "f16", seed=12)
+    codes, scales = gu.run_fwd_quant(x, th, n, 1, "f16", 4, n, "f16")
+    gu.check_fused_codes(codes, scales, _ref_fwd(x, th, n, 1, "f16"), 4, n, "f16", "f16", "per-token flagged")
