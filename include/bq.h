@@ -57,7 +57,8 @@ typedef enum { BQ_F32 = 0, BQ_F16 = 1, BQ_BF16 = 2 } bq_dtype;
 typedef struct {
     int64_t rows;  /* T >= 0                                                                  */
     int32_t n;     /* transform size, power of two, 2 <= n <= 16384                           */
-    int32_t heads; /* H >= 1 transforms side by side; logical row width = H * n               */
+    int32_t heads; /* H >= 1 transforms side by side; logical row width = H * n <= 2^24,
+                      and rows * H * n <= 2^40 (else BQ_ERR_SHAPE)                            */
     int64_t ld_x;  /* row stride, in elements, of the input operand(s)  (>= H * n)            */
     int64_t ld_y;  /* row stride, in elements, of the output operand    (>= H * n)            */
     int32_t dtype; /* bq_dtype of the row operands (inputs and outputs share it)              */

@@ -1,5 +1,5 @@
-// Backward pass for small transforms, n = 8 .. 128 (k = 3 .. 7), any number of heads whose row width tiles
-// 2048 elements: dx = B^T dy and dtheta (paper, "Gradient Flow Through Butterfly Layers").
+// Backward pass for small transforms, n = 8 .. 128 (k = 3 .. 7), for the row widths the small forward kernels
+// take: dx = B^T dy and dtheta (paper, "Gradient Flow Through Butterfly Layers").
 //
 // Geometry of the small forward kernels (bq_small.hip): a transform occupies n/8 consecutive lanes, 8
 // consecutive elements per lane, no LDS and no barrier; a workgroup of 256 threads covers 2048 consecutive
@@ -32,8 +32,10 @@ struct SmallBwdArgs {
     const int *bad_fwd, *bad_inv;
     int64_t rows, ld_in, ld_out;
     int heads, width;    // width = heads * n
-    int rows_per_block;  // kSbSpan / width if width < kSbSpan, else 1
-    int slices;          // width / kSbSpan if width >= kSbSpan, else 1
+    int span;            // elements covered by a workgroup: kSbSpan, or the largest power of two below it that
+                         // divides a wider row (the workgroup then has span / 8 threads)
+    int rows_per_block;  // span / width if width < span, else 1
+    int slices;          // width / span if width >= span, else 1
     int64_t n_groups;    // row groups = ceil(rows / rows_per_block)
     int64_t n_angles;    // heads * k * n / 2
 };
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(kSbThreads) void small_bwd_kernel(SmallBwdArgs A)
     int64_t grp_first, grp_step, slot;
     if (A.slices > 1) {
         row_in_block = 0;
-        col = (int)(blockIdx.x % A.slices) * kSbSpan + e0;
+        col = (int)(blockIdx.x % A.slices) * A.span + e0;
         grp_first = blockIdx.x / A.slices;
         grp_step = gridDim.x / A.slices;
         slot = grp_first;
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(256) void small_bwd_reduce_kernel(const float *__re
 
 // ---- host side -----------------------------------------------------------------------------------
 struct SmallBwdGrid {
-    int rows_per_block, slices;
+    int span, rows_per_block, slices;
     int64_t n_groups, slots;
     unsigned grid;
 };
@@ -188,8 +190,9 @@ static SmallBwdGrid small_bwd_grid(const Shape &s)
 {
     SmallBwdGrid g;
     const int64_t width = (int64_t)s.n * s.heads;
-    g.rows_per_block = width < kSbSpan ? (int)(kSbSpan / width) : 1;
-    g.slices = width >= kSbSpan ? (int)(width / kSbSpan) : 1;
+    g.span = small_span(width);
+    g.rows_per_block = width < g.span ? (int)(g.span / width) : 1;
+    g.slices = width >= g.span ? (int)(width / g.span) : 1;
     g.n_groups = (s.rows + g.rows_per_block - 1) / g.rows_per_block;
     // about two workgroups per compute unit; the slot count (partial sums to write and to add) stays bounded
     int64_t per_slice = 512 / g.slices > 0 ? 512 / g.slices : 1;
@@ -204,8 +207,7 @@ bool small_bwd_supported(const void *x, const void *dy, const void *dx, const fl
 {
     if (s.k < 3 || s.k > 7 || dtheta == nullptr || s.rows == 0) return false;
     const int64_t width = (int64_t)s.n * s.heads;
-    if (!((width < kSbSpan && kSbSpan % width == 0) || (width >= kSbSpan && width % kSbSpan == 0))) return false;
-    if (width / kSbSpan > 512) return false;
+    if (small_span(width) == 0 || width / small_span(width) > 512) return false;
     const int vec = s.dtype == BQ_F32 ? 4 : 8;
     if (((uintptr_t)x & 15) || ((uintptr_t)dy & 15) || (dx && ((uintptr_t)dx & 15))) return false;
     if ((s.ld_x % vec) || (s.ld_y % vec)) return false;
@@ -214,6 +216,7 @@ bool small_bwd_supported(const void *x, const void *dy, const void *dx, const fl
 
 size_t small_bwd_workspace_bytes(const Shape &s)
 {
+    if (small_span((int64_t)s.n * s.heads) == 0) return 0;  // not a shape of these kernels
     const SmallBwdGrid g = small_bwd_grid(s);
     return align256((size_t)g.slots * s.heads * s.k * (s.n / 2) * sizeof(float));
 }
@@ -222,9 +225,9 @@ template <typename T, int K>
 static void launch_small_bwd_k(const SmallBwdArgs &A, unsigned grid, hipStream_t stream)
 {
     if (A.dx)
-        hipLaunchKernelGGL((small_bwd_kernel<T, K, true>), dim3(grid), dim3(kSbThreads), 0, stream, A);
+        hipLaunchKernelGGL((small_bwd_kernel<T, K, true>), dim3(grid), dim3(A.span / 8), 0, stream, A);
     else
-        hipLaunchKernelGGL((small_bwd_kernel<T, K, false>), dim3(grid), dim3(kSbThreads), 0, stream, A);
+        hipLaunchKernelGGL((small_bwd_kernel<T, K, false>), dim3(grid), dim3(A.span / 8), 0, stream, A);
 }
 
 template <typename T>
@@ -260,6 +263,7 @@ hipError_t launch_small_bwd(const void *x, const void *dy, const PlanView &pv, v
     A.ld_out = s.ld_y;
     A.heads = s.heads;
     A.width = s.n * s.heads;
+    A.span = g.span;
     A.rows_per_block = g.rows_per_block;
     A.slices = g.slices;
     A.n_groups = g.n_groups;

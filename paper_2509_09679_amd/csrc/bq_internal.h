@@ -130,6 +130,7 @@ size_t bwd_workspace_bytes_generic(const Shape &s);
 hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv, void *dx, float *dtheta,
                               void *ws, const Shape &s, hipStream_t stream, bool only_if_bad = false);
 
+int small_span(int64_t width);  // bq_small.hip: elements per workgroup of the small-transform kernels, 0 = unsupported
 // backward for n = 8 .. 128 (bq_bwd_small.hip)
 bool small_bwd_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s);
 size_t small_bwd_workspace_bytes(const Shape &s);

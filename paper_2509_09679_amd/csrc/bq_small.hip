@@ -1,5 +1,7 @@
-// Specialised kernels for small transforms, n = 8 .. 128 (k = 3 .. 7), any number of heads whose row
-// width tiles 2048 elements: forward, inverse and fused forward + quantisation.
+// Specialised kernels for small transforms, n = 8 .. 128 (k = 3 .. 7): forward, inverse and fused forward +
+// quantisation, for any number of heads whose row width divides 2048 or is a multiple of 512 (rows that are
+// not a multiple of 2048 elements wide are covered by narrower workgroups: 1024 or 512 elements, 128 or 64
+// threads).
 //
 // A transform of n elements occupies n/8 consecutive lanes (at most one 16-lane row), 8 consecutive
 // elements per lane, and never touches LDS: layers 1-3 pair registers, layers 4..k pair lanes through
@@ -26,8 +28,10 @@ struct SmallArgs {
     const int *fast_bad;
     int64_t rows, ld_in, ld_out;
     int heads, width;    // width = heads * n
-    int rows_per_block;  // kSmallSpan / width if width < kSmallSpan, else 1
-    int slices;          // width / kSmallSpan if width >= kSmallSpan, else 1
+    int span;            // elements covered by a workgroup: kSmallSpan, or the largest power of two below it that
+                         // divides a wider row (the workgroup then has span / 8 threads)
+    int rows_per_block;  // span / width if width < span, else 1
+    int slices;          // width / span if width >= span, else 1
     int64_t n_groups;    // row groups = ceil(rows / rows_per_block)
     uint8_t *codes;
     void *scales;
@@ -61,7 +65,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
     int64_t grp_first, grp_step;
     if (A.slices > 1) {
         row_in_block = 0;
-        col = (int)(blockIdx.x % A.slices) * kSmallSpan + e0;
+        col = (int)(blockIdx.x % A.slices) * A.span + e0;
         grp_first = blockIdx.x / A.slices;
         grp_step = gridDim.x / A.slices;
     } else {
@@ -190,12 +194,21 @@ static void (*pick_small_k(int k, Mode mode, int bits))(SmallArgs)
     }
 }
 
+// Elements per workgroup for rows of `width` elements: 2048 where rows tile it or it tiles rows, else the
+// largest power of two that divides the row, down to one wave (512); 0 if there is none.
+int small_span(int64_t width)
+{
+    if (width < kSmallSpan) return kSmallSpan % width == 0 ? kSmallSpan : 0;
+    const int64_t low = width & -width;
+    const int span = (int)(low < kSmallSpan ? low : kSmallSpan);
+    return span >= 512 ? span : 0;
+}
+
 bool small_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q)
 {
     if (s.k < 3 || s.k > 7) return false;
     const int64_t width = (int64_t)s.n * s.heads;
-    if (!((width < kSmallSpan && kSmallSpan % width == 0) || (width >= kSmallSpan && width % kSmallSpan == 0)))
-        return false;
+    if (small_span(width) == 0) return false;
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;
     if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
@@ -222,8 +235,9 @@ hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv
     A.ld_out = s.ld_y;
     A.heads = s.heads;
     A.width = s.n * s.heads;
-    A.rows_per_block = A.width < kSmallSpan ? kSmallSpan / A.width : 1;
-    A.slices = A.width >= kSmallSpan ? A.width / kSmallSpan : 1;
+    A.span = small_span(A.width);
+    A.rows_per_block = A.width < A.span ? A.span / A.width : 1;
+    A.slices = A.width >= A.span ? A.width / A.span : 1;
     A.n_groups = (s.rows + A.rows_per_block - 1) / A.rows_per_block;
     int bits = 4;
     if (q) {
@@ -241,7 +255,7 @@ hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv
     void (*kern)(SmallArgs) = s.dtype == BQ_F32   ? pick_small_k<float>(s.k, mode, bits)
                               : s.dtype == BQ_F16 ? pick_small_k<__half>(s.k, mode, bits)
                                                   : pick_small_k<bf16_t>(s.k, mode, bits);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kSmallThreads), 0, stream, A);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(A.span / 8), 0, stream, A);
     return hipGetLastError();
 }
 

@@ -124,6 +124,19 @@ def test_bwd_validation_and_workspace_query():
     assert call(rr=_rows(n=7)) == 2
 
 
+def test_workspace_query_over_many_shapes():
+    # host arithmetic only: every valid shape gets a size (a positive multiple of 256), whichever kernel family
+    # the shape belongs to
+    for n in (2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384):
+        for heads in (1, 2, 3, 5, 7, 12, 24, 40, 64, 86, 513):
+            for rows in (0, 1, 7, 1000, 300000):
+                for dtype in (B.BQ_F32, B.BQ_F16):
+                    need = B.bq_butterfly_bwd_workspace_bytes(_rows(rows=rows, n=n, heads=heads, dtype=dtype))
+                    assert need % 256 == 0, (n, heads, rows)
+                    valid = n * heads <= 1 << 24 and rows * n * heads <= 1 << 40  # the documented limits
+                    assert (need > 0) == valid, (n, heads, rows)
+
+
 def test_plan_build_validation():
     L = B.lib()
     need = B.bq_plan_bytes(256, 2)

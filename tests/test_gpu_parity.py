@@ -441,3 +441,21 @@ def test_large_quantiser_groups_flagged_plan():
     x, _, _ = synth.small_case(n, 9, "f16", seed=12)
     codes, scales = gu.run_fwd_quant(x, th, n, 1, "f16", 4, n, "f16")
     gu.check_fused_codes(codes, scales, _ref_fwd(x, th, n, 1, "f16"), 4, n, "f16", "f16", "per-token flagged")
+
+
+# row widths that are a multiple of 512 but not of 2048 elements (e.g. 5120 = 40 x 128): narrower workgroups
+@pytest.mark.parametrize("n,heads,rows,dtype", [(128, 40, 37, "f16"), (64, 24, 50, "bf16"), (128, 12, 9, "f32")])
+def test_small_transforms_odd_row_widths(n, heads, rows, dtype):
+    x, th, dy = synth.small_case(n, rows, dtype, heads=heads, seed=110 + heads, with_dy=True, outliers=0)
+    y_ref = _ref_fwd(x, th, n, heads, dtype)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype), y_ref, dtype, f"odd width fwd H={heads}")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, inverse=True),
+                     oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"odd width inv H={heads}")
+    codes, scales = gu.run_fwd_quant(x, th, n, heads, dtype, 4, n, "f32")
+    gu.check_fused_codes(codes, scales, y_ref, 4, n, "f32", dtype, f"odd width quant H={heads}")
+    yq, hist = gu.run_fwd_fakequant(x, th, n, heads, dtype, 4, n, "f32")
+    np.testing.assert_array_equal(hist, oracle.bin_histogram(oracle.unpack_codes(codes, 4), 4))
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n, heads)
+    dx, dth = gu.run_bwd(x, dy, th, n, heads, dtype)
+    gu.check_rotated(dx, rdx, dtype, f"odd width dx H={heads}")
+    gu.check_dtheta(dth, rdth, ab, what=f"odd width H={heads}")
