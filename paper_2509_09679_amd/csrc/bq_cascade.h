@@ -398,10 +398,16 @@ __device__ __forceinline__ void count8<4>(BinCount<4> &bc, const float (&f)[8], 
     bc.add(fbits);
 }
 
+// The product is pinned as a float32 value: left alone, the compiler merges the multiplication with a later
+// conversion to binary16 into one v_fma_mixlo_f16, which rounds the exact product once and so differs from
+// "float32 product, then one rounding" where the float32 product is a binary16 tie (float32 scales, INT4).
 __device__ __forceinline__ void dequant8(const float (&f)[8], float s, float (&yq)[8])
 {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) yq[r] = (f[r] - kRoundMagic) * s;
+    for (int r = 0; r < 8; ++r) {
+        yq[r] = (f[r] - kRoundMagic) * s;
+        asm volatile("" : "+v"(yq[r]));
+    }
 }
 
 // ---- transforms of n = 8 .. 128 inside 16 lanes (8 consecutive elements per lane, no LDS) -----------

@@ -143,7 +143,9 @@ __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
                     if (out) {
                         const int64_t row = unit / heads;
                         const int head = (int)(unit - row * heads);
-                        out[row * A.ld_out + (int64_t)head * n + (e & (n - 1))] = from_float<T>(s_lds[g] * (float)q);
+                        float p = s_lds[g] * (float)q;
+                        asm volatile("" : "+v"(p));  // a float32 product: not merged with the conversion below
+                        out[row * A.ld_out + (int64_t)head * n + (e & (n - 1))] = from_float<T>(p);
                     }
                     if (A.hist) atomicAdd(&hist_lds[q + off], 1u);
                 }

@@ -152,3 +152,33 @@ def test_fakequant_many_rows_per_workgroup(n, heads, rows, dtype, bits, group, s
     oh = oracle.bin_histogram(oc, bits).astype(np.int64)
     gh = oracle.bin_histogram(c[:2048], bits).astype(np.int64)
     assert np.abs(oh - gh).sum() <= 1e-3 * oh.sum()
+
+
+@pytest.mark.parametrize("n,heads,rows", [(4096, 1, 1024), (128, 32, 1024), (8192, 1, 512), (1024, 1, 4096)])
+def test_fakequant_float32_scales_binary16_rows_is_product_then_rounding(n, heads, rows):
+    # With float32 scales the product s * q needs up to 27 bits: it is rounded to float32 first and then to
+    # binary16.  Rounding the exact product once would differ where the float32 product is a binary16 tie
+    # (a few elements per 10^5), so this compares every element of several million.
+    import torch
+    from paper_2509_09679_amd import binding as B
+
+    x, th, _ = synth.small_case(n, rows, "f16", heads=heads, seed=5 + n)
+    theta = torch.from_numpy(th).to("cuda:0")
+    plan = B.alloc_plan(theta, n, heads)
+    xd = synth.storage_to_torch(x, "f16", "cuda:0")
+    r = B.make_rows(xd, n, heads)
+    q = B.make_quant(4, min(n, 128), "f32")
+    yq = torch.empty_like(xd)
+    B.bq_butterfly_fwd_fakequant(xd, plan, yq, None, q, r)
+    codes, scales = B.alloc_quant_outputs(rows, n, heads, 4, min(n, 128), "f32", "cuda:0")
+    B.bq_butterfly_fwd_quant(xd, plan, codes, scales, q, r)
+    torch.cuda.synchronize()
+    c = oracle.unpack_codes(codes.cpu().numpy(), 4)
+    deq = oracle.dequantize(c, scales.cpu().numpy(), min(n, 128))
+    want = synth.cast_storage(deq.astype(np.float64), "f16")
+    got = synth.torch_to_storage(yq, "f16")
+    np.testing.assert_array_equal(got.view(np.uint16), want.view(np.uint16))
+    # the case must contain such ties, or it would not tell the two roundings apart
+    exact = scales.cpu().numpy().astype(np.float64).repeat(min(n, 128), axis=1) * c.astype(np.float64)
+    once = synth.cast_storage(exact, "f16")
+    assert (once.view(np.uint16) != want.view(np.uint16)).sum() > 0
