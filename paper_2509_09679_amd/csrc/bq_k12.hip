@@ -3,25 +3,35 @@
 
 namespace bq {
 
-// n = 4096 or 8192 with any number of heads, or one head of n = 256 .. 2048, where 4096 / n consecutive rows
-// form one block of the kernel (k12_block_rows; the caller passes whole blocks only).
+// n = 4096 or 8192 with any number of heads, or n = 256 .. 2048 where 4096 consecutive elements of the
+// [rows][heads * n] array form one block of the kernel: several whole rows (k12_block_rows of them; rows that do
+// not fill a block are the caller's to handle) or a 4096-element piece of a wider row.
 bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q)
 {
     if (s.n > 2 * kN || s.n < 256) return false;
-    if (s.n < kN && (s.heads != 1 || s.rows < kN / s.n)) return false;
+    const int64_t width = (int64_t)s.n * s.heads;
+    if (s.n < kN) {
+        const bool rows_per_block = width <= kN && kN % width == 0 && s.rows >= kN / width;
+        const bool blocks_per_row = width % kN == 0 && width / kN <= 512;
+        if (!rows_per_block && !blocks_per_row) return false;
+    }
     const int isz = s.dtype == BQ_F32 ? 4 : 2;
     const int vec = 16 / isz;  // elements per 16 bytes
     if (((uintptr_t)in & 15) || (s.ld_x % vec)) return false;
     if (mode != kFwdQuant && out && (((uintptr_t)out & 15) || (s.ld_y % vec))) return false;
-    if (s.n < kN && ((int64_t)(kN / s.n) * (s.ld_x > s.ld_y ? s.ld_x : s.ld_y) * isz >= ((int64_t)1 << 31))) return false;
-    if (s.heads > 512) return false;
+    if (s.n < kN && ((int64_t)k12_block_rows(s) * (s.ld_x > s.ld_y ? s.ld_x : s.ld_y) * isz >= ((int64_t)1 << 31))) return false;
+    if (s.n >= kN && s.heads > 512) return false;
     if (mode == kFwdQuant || mode == kFwdFake) {
         if (mode == kFwdQuant && ((uintptr_t)q->codes & 3)) return false;
     }
     return true;
 }
 
-int k12_block_rows(const Shape &s) { return s.n < kN ? kN / s.n : 1; }
+int k12_block_rows(const Shape &s)
+{
+    const int64_t width = (int64_t)s.n * s.heads;
+    return s.n < kN && width < kN ? (int)(kN / width) : 1;
+}
 
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream)
@@ -42,7 +52,9 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.sub_ld_out = s.ld_y;
     A.n = s.n;
     A.n_log = s.k;
-    A.heads = s.heads;
+    const int64_t width = (int64_t)s.n * s.heads;
+    A.heads = virt ? (width > kN ? (int)(width / kN) : 1) : s.heads;  // virt: 4096-element blocks per row
+    A.row_log = virt ? (width >= kN ? kK : ilog2_exact((int)width)) : 0;
     int bits = 4;
     if (q) {
         A.codes = q->codes;
@@ -57,9 +69,9 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
     const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
-    int64_t per_head = target / s.heads > 0 ? target / s.heads : 1;
+    int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
-    unsigned grid = (unsigned)(per_head * s.heads);
+    unsigned grid = (unsigned)(per_head * A.heads);
     if ((mode == kFwdQuant || mode == kFwdFake) && q->group > 128)
         return launch_k12_big_dtype(mode, A, bits, grid, s.dtype, virt, wide, stream);
     if (wide) return launch_k13_dtype(mode, A, bits, grid, s.dtype, stream);

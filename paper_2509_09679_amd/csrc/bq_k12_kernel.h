@@ -66,9 +66,11 @@ struct K12Args {
     void *scales;
     unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
     int group, scale_f16;
-    // transforms of n = 2^n_log < 4096 points (kVirt): a "row" of the kernel is a block of 4096 / n consecutive
-    // rows of the caller; ld_in / ld_out are then the strides between blocks, sub_ld_* the caller's strides
-    int n, n_log;
+    // transforms of n = 2^n_log < 4096 points (kVirt): a "row" of the kernel is a block of 4096 consecutive
+    // elements of the caller's [rows][heads * n] array.  Rows of up to 4096 elements: 2^(12 - row_log) whole rows
+    // (row_log = log2 of the row width; ld_in / ld_out are the strides between blocks, sub_ld_* the caller's
+    // strides, heads = 1).  Wider rows: block `head` of the heads = width / 4096 blocks of a row (row_log = 12).
+    int n, n_log, row_log;
     int64_t sub_ld_in, sub_ld_out;
 };
 
@@ -77,7 +79,12 @@ template <bool kVirt, bool kWide = false>
 __device__ __forceinline__ uint32_t elem_off(const K12Args &A, int head, int e, int64_t sub_ld)
 {
     if (!kVirt) return (uint32_t)(head * (kWide ? 2 * kN : kN) + e);
-    return (uint32_t)((e >> A.n_log) * (int)sub_ld + (e & (A.n - 1)));
+    return (uint32_t)((e >> A.row_log) * (int)sub_ld + head * kN + (e & ((1 << A.row_log) - 1)));
+}
+// kVirt: the transform (head of the caller's row) that element e of block `head` belongs to
+__device__ __forceinline__ int virt_head(const K12Args &A, int head, int e)
+{
+    return (head * kN + (e & ((1 << A.row_log) - 1))) >> A.n_log;
 }
 
 __device__ __forceinline__ int lds_addr(int idx) { return idx + 2 * (idx >> 5) + 2 * (idx >> 9); }
@@ -139,9 +146,11 @@ __device__ __forceinline__ void cross_layer(const float *other, int addr, const 
 // slow cascade through LDS with (cos, sin); in: u[] in layout N, out: y[] in layout N (true values)
 // n_log < 12: the block holds 4096 >> n_log independent transforms of 2^n_log points (same angles).
 // kWide: 1024 threads on one 8192-point transform (idx_n counts inside the whole row).
+// row_mask, head0: several transforms with their own angles side by side in the block (see K12Args): element a
+// belongs to transform (head0 + (a & row_mask)) >> n_log.
 template <bool kInverse, bool kWide = false>
 __device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const float2 *__restrict__ cs, int idx_n,
-                                             int n_log = kWide ? kK + 1 : kK)
+                                             int n_log = kWide ? kK + 1 : kK, int row_mask = 0, int head0 = 0)
 {
     constexpr int kPoints = kWide ? 2 * kN : kN, kWorkers = kWide ? 2 * kThreads : kThreads;
     __syncthreads();
@@ -153,8 +162,9 @@ __device__ __forceinline__ void slow_cascade(float (&u)[8], float *buf, const fl
         const int i = kInverse ? (n_log - step) : (step + 1);
         const int h = 1 << (i - 1);
         for (int p = threadIdx.x; p < kPoints / 2; p += kWorkers) {
-            const float2 w = cs[(size_t)(i - 1) * half_n + (p & (half_n - 1))];
             const int a = ((p >> (i - 1)) << i) | (p & (h - 1));
+            const int hd = (head0 + (a & row_mask)) >> n_log;
+            const float2 w = cs[((size_t)hd * n_log + (i - 1)) * half_n + (p & (half_n - 1))];
             const float xa = buf[a], xb = buf[a + h];
             if (!kInverse) {
                 buf[a] = __builtin_fmaf(w.x, xa, -(w.y * xb));
@@ -320,16 +330,21 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     float cn[7][8], cp[5][8];
     float cw[8];  // kWide: layer 13, in layout N (forward, phase C) or layout P (inverse, phase B)
     auto load_coefficients = [&]() {
-        const float *fg = A.fg + (size_t)head * kLayers * kPoints;  // kVirt: one head
+        // tables are [head][layer][n]; kVirt: the head is the element's own (virt_head)
+        const float *fg = A.fg + (kVirt ? 0 : (size_t)head * kLayers * kPoints);
+        const float *fg_n = fg + (kVirt ? (size_t)virt_head(A, head, idx_n) * nk * tn : 0);
 #pragma unroll
         for (int j = 0; j < 7; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * tn + ((col0 + idx_n) & tmask) + r];
+            for (int r = 0; r < 8; ++r) cn[j][r] = fg_n[j * tn + ((col0 + idx_n) & tmask) + r];
 #pragma unroll
         for (int j = 0; j < 5; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
-                cp[j][r] = (!kVirt || 8 + j <= nk) ? fg[(7 + j) * tn + ((col0 + idx_p + p_reg_idx(r)) & tmask)] : 0.0f;
+            for (int r = 0; r < 8; ++r) {  // layers above log2 n do not exist: weight zero leaves the element as it is
+                const int e = col0 + idx_p + p_reg_idx(r);
+                const float *fg_p = fg + (kVirt ? (size_t)virt_head(A, head, e) * nk * tn : 0);
+                cp[j][r] = (!kVirt || 8 + j <= nk) ? fg_p[(7 + j) * tn + (e & tmask)] : 0.0f;
+            }
 #pragma unroll
         for (int r = 0; r < 8; ++r)
             cw[r] = !kWide ? 0.0f : kInverse ? fg[kK * tn + col0 + idx_p + p_reg_idx(r)] : fg[kK * tn + col0 + idx_n + r];
@@ -351,11 +366,11 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         }
     }
     if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
-        const float2 *cs = A.cs + (size_t)head * kLayers * (kPoints / 2);  // kVirt: one head
+        const float2 *cs = A.cs + (kVirt ? 0 : (size_t)head * kLayers * (kPoints / 2));
         for (int64_t row = row_first; row < A.rows; row += row_step) {
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
-            slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk);
+            slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk, kVirt ? (1 << A.row_log) - 1 : 0, kVirt ? head * kN : 0);
             finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row, head, chunk_row, bins, wg_bins, wg_max);
         }
         flush_bins();
@@ -442,7 +457,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         constexpr uint32_t kSlotBytes = kPoints * 2;
         float d[8];
         {
-            const float *fd = A.fd + (size_t)head * kPoints;
+            const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
         }
@@ -524,7 +539,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         // ---- 32-bit rows: two rows prefetched in registers, output scales kept in LDS ---------------
         float *dtab = lds_raw + half * kLdsRow;
         {
-            const float *fd = A.fd + (size_t)head * kPoints;
+            const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
             float d[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];

@@ -459,3 +459,43 @@ def test_small_transforms_odd_row_widths(n, heads, rows, dtype):
     dx, dth = gu.run_bwd(x, dy, th, n, heads, dtype)
     gu.check_rotated(dx, rdx, dtype, f"odd width dx H={heads}")
     gu.check_dtheta(dth, rdth, ab, what=f"odd width H={heads}")
+
+
+# n = 256 .. 2048 with several heads: 4096 consecutive elements of the [rows][heads * n] array form a block, either
+# several whole rows (width <= 4096) or a piece of a wider row; every 2^k-element piece has its own angles
+MID_HEADS = [(256, 4, 4 * 9 + 3, "f16"), (256, 16, 21, "bf16"), (512, 8, 13, "f32"), (1024, 2, 2 * 17 + 1, "f16"),
+             (1024, 8, 11, "bf16"), (2048, 2, 7, "f16"), (2048, 6, 5, "f32"), (512, 2, 4 * 5, "bf16")]
+
+
+@pytest.mark.parametrize("n,heads,rows,dtype", MID_HEADS)
+def test_mid_sizes_several_heads(n, heads, rows, dtype):
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=120 + n + heads)
+    ref = _ref_fwd(x, th, n, heads, dtype)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype), ref, dtype, f"mid heads fwd n={n} H={heads}")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, pad=16), ref, dtype, "mid heads fwd padded")
+    a = gu.run_transform(x, th, n, heads, dtype)
+    b = gu.run_transform(x, th, n, heads, dtype, inplace=True)
+    np.testing.assert_array_equal(a.view(np.uint8), b.view(np.uint8))
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, inverse=True),
+                     oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"mid heads inv n={n} H={heads}")
+    for bits, group, sd in ((4, 128, "f16"), (2, n, "f32")):
+        codes, scales = gu.run_fwd_quant(x, th, n, heads, dtype, bits, group, sd)
+        gu.check_fused_codes(codes, scales, ref, bits, group, sd, dtype, f"mid heads quant n={n} H={heads} g={group}")
+        yq, hist = gu.run_fwd_fakequant(x, th, n, heads, dtype, bits, group, sd)
+        c = oracle.unpack_codes(codes, bits)
+        want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+        u = np.uint16 if dtype != "f32" else np.uint32
+        np.testing.assert_array_equal(yq.view(u), want.view(u))
+        np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits))
+
+
+def test_mid_sizes_several_heads_flagged_plan():
+    n, heads, k = 512, 4, 9
+    rng = np.random.default_rng(55)
+    th = rng.uniform(-math.pi, math.pi, size=(heads, k, n // 2)).astype(np.float32)
+    th[1, 2, ::3] = np.float32(math.pi / 2)
+    th[3, k - 1, :] = np.float32(-math.pi / 2)
+    x, _, _ = synth.small_case(n, 2 * 3 + 1, "f16", heads=heads, seed=9)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, "f16"), _ref_fwd(x, th, n, heads, "f16"), "f16", "mid heads flagged fwd")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, "f16", inverse=True),
+                     oracle.inverse(synth.to_f64(x, "f16"), th, n, heads), "f16", "mid heads flagged inv")
