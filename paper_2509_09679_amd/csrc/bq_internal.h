@@ -25,7 +25,6 @@ namespace bq {
 //   [fw_inv  : float  [heads][k][n]]   scale D of every element just BEFORE transposed layer i is applied
 //                                      (row i-1); the backward kernels turn sums accumulated in deferred
 //                                      units into dtheta with the factor D[a] * D[b] of the pair
-//   [dwork   : double [heads][n]]      scratch of the plan build
 //
 // Scale-deferred form.  A rotation  ya = c xa - s xb, yb = s xa + c xb  with t = s / c is
 //   ya = c (xa - t xb),  yb = c (xb + t xa).
@@ -49,7 +48,7 @@ struct PlanHeader {
 static_assert(sizeof(PlanHeader) == 256, "header is 256 bytes");
 
 struct PlanLayout {
-    size_t cs, fg_fwd, fd_fwd, fm_fwd, fg_inv, fd_inv, fw_inv, dwork, total;
+    size_t cs, fg_fwd, fd_fwd, fm_fwd, fg_inv, fd_inv, fw_inv, total;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -66,7 +65,6 @@ inline PlanLayout plan_layout(int n, int heads, int k)
     L.fg_inv = off;  off = align256(off + H * K * N * sizeof(float));
     L.fd_inv = off;  off = align256(off + H * N * sizeof(float));
     L.fw_inv = off;  off = align256(off + H * K * N * sizeof(float));
-    L.dwork = off;   off = align256(off + H * N * sizeof(double));
     L.total = off;
     return L;
 }

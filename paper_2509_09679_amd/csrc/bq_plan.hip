@@ -23,22 +23,29 @@ __global__ void plan_cs_kernel(const float *__restrict__ theta, float2 *__restri
     }
 }
 
-// One workgroup per head.  D (double, one per element) lives in dwork; layers are processed in
-// cascade order with workgroup barriers between them.
+// Layers are processed in cascade order with workgroup barriers between them.
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanMaxPerThread = 16;  // n <= 16384
 
-__global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(const float *__restrict__ theta, int n, int k,
-                                                                  int inverse, float *__restrict__ fg,
-                                                                  float *__restrict__ fd, float *__restrict__ fw,
-                                                                  float *__restrict__ fm, double *__restrict__ dwork,
-                                                                  int *bad_flag)
+// One workgroup per (head, direction): blockIdx.y = 0 builds the forward tables, 1 those of the transposed
+// cascade.  The running scales D (double) live in LDS.
+struct PlanFastArgs {
+    const float *theta;
+    int n, k;
+    float *fg[2], *fd[2];
+    float *fw;  // transposed cascade only
+    float *fm;  // forward cascade only
+    int *bad[2];
+};
+
+__global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(PlanFastArgs A)
 {
-    const int head = blockIdx.x;
-    const int tid = threadIdx.x;
-    double *D = dwork + (size_t)head * n;
-    const float *th = theta + (size_t)head * k * (n / 2);
-    float *fgh = fg + (size_t)head * k * n;
+    extern __shared__ double D[];  // [n]
+    const int head = blockIdx.x, inverse = blockIdx.y;
+    const int tid = threadIdx.x, n = A.n, k = A.k;
+    const float *th = A.theta + (size_t)head * k * (n / 2);
+    float *fgh = A.fg[inverse] + (size_t)head * k * n;
+    float *fw = inverse ? A.fw : nullptr, *fm = inverse ? nullptr : A.fm;
     for (int e = tid; e < n; e += kPlanThreads) D[e] = 1.0;
     __syncthreads();
     int bad = 0;
@@ -77,8 +84,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fast_kernel(const float *__
         for (int e = tid; e < n; e += kPlanThreads, ++j) D[e] = newD[j];
         __syncthreads();
     }
-    for (int e = tid; e < n; e += kPlanThreads) fd[(size_t)head * n + e] = (float)D[e];
-    if (bad) atomicOr(bad_flag, 1);
+    for (int e = tid; e < n; e += kPlanThreads) A.fd[inverse][(size_t)head * n + e] = (float)D[e];
+    if (bad) atomicOr(A.bad[inverse], 1);
 }
 
 hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *plan, hipStream_t stream)
@@ -90,12 +97,24 @@ hipError_t launch_plan_build(const float *theta, int n, int heads, int k, void *
     unsigned blocks = (unsigned)((count + 255) / 256);
     hipLaunchKernelGGL(plan_cs_kernel, dim3(blocks), dim3(256), 0, stream, theta, (float2 *)(p + L.cs), count,
                        hdr, n, heads, k);
-    hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 0,
-                       (float *)(p + L.fg_fwd), (float *)(p + L.fd_fwd), (float *)nullptr, (float *)(p + L.fm_fwd),
-                       (double *)(p + L.dwork), &hdr->fast_bad_fwd);
-    hipLaunchKernelGGL(plan_fast_kernel, dim3(heads), dim3(kPlanThreads), 0, stream, theta, n, k, 1,
-                       (float *)(p + L.fg_inv), (float *)(p + L.fd_inv), (float *)(p + L.fw_inv), (float *)nullptr,
-                       (double *)(p + L.dwork), &hdr->fast_bad_inv);
+    PlanFastArgs F{};
+    F.theta = theta;
+    F.n = n;
+    F.k = k;
+    F.fg[0] = (float *)(p + L.fg_fwd);
+    F.fg[1] = (float *)(p + L.fg_inv);
+    F.fd[0] = (float *)(p + L.fd_fwd);
+    F.fd[1] = (float *)(p + L.fd_inv);
+    F.fw = (float *)(p + L.fw_inv);
+    F.fm = (float *)(p + L.fm_fwd);
+    F.bad[0] = &hdr->fast_bad_fwd;
+    F.bad[1] = &hdr->fast_bad_inv;
+    const size_t lds = (size_t)n * sizeof(double);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)plan_fast_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(plan_fast_kernel, dim3(heads, 2), dim3(kPlanThreads), lds, stream, F);
     return hipGetLastError();
 }
 
