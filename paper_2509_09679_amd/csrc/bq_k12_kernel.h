@@ -380,7 +380,9 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
 
     const int an = lds_addr(idx_n);
     const int ap = lds_addr(idx_p);
-    const int64_t n_my = (A.rows - row_first + row_step - 1) / row_step;  // rows of this workgroup
+    // rows of this workgroup: below 2^28 for every batch the library accepts, so the loop counters are 32-bit
+    // (64-bit comparisons of uniform values would be done on the vector unit)
+    const int n_my = (int)((A.rows - row_first + row_step - 1) / row_step);
     int ba = 0, bb = 2, bc = 1;  // buffer (and ring slot) of A(it), B(it-1), C(it-2)
 
     // Phase B of one row: layers 8..12 (or 12..8) on layout P, in place in its LDS buffer.
@@ -467,8 +469,8 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * 16u;        // this thread's chunk
         const uint32_t voff = elem_off<kVirt, kWide>(A, head, (wave_row * 64 + lane) * 8, A.sub_ld_in) * 2u;  // lane's bytes in a row
         const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
-        auto ring_load = [&](int64_t j, int slot) {
-            const int64_t jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
+        auto ring_load = [&](int j, int slot) {
+            const int jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
             const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
             const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
@@ -481,7 +483,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
         // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
         // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
-        auto step = [&](auto BA, auto BB, auto BC, int64_t it) {
+        auto step = [&](auto BA, auto BB, auto BC, int it) {
             constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
             float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
             float *lc = lds + (bc * kHalves + half) * kLdsRow;
@@ -529,8 +531,8 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         typedef std::integral_constant<int, 0> I0;
         typedef std::integral_constant<int, 1> I1;
         typedef std::integral_constant<int, 2> I2;
-        const int64_t end = n_my + 2;
-        for (int64_t it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
+        const int end = n_my + 2;
+        for (int it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
             step(I0{}, I2{}, I1{}, it);
             if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
             if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         __syncthreads();
         // `raw` holds row `it` on entry and is refilled with row it + 2 (unconditionally: the last two
         // iterations re-read the last row).
-        auto iteration = [&](int64_t it, Raw8 &raw) {
+        auto iteration = [&](int it, Raw8 &raw) {
             float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
             float *lc = lds + (bc * kHalves + half) * kLdsRow;
             const float *lb_other = lds + (bb * kHalves + (half ^ 1)) * kLdsRow;  // kWide only
@@ -561,7 +563,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                     __builtin_amdgcn_sched_barrier(0);
                     uint32_t off = off_n * (uint32_t)sizeof(T);
                     asm volatile("" : "+v"(off));
-                    const int64_t nxt = (it + 2 < n_my) ? it + 2 : n_my - 1;
+                    const int nxt = (it + 2 < n_my) ? it + 2 : n_my - 1;
                     const char *rowp = (const char *)(in + (row_first + nxt * row_step) * A.ld_in);
                     raw = load8((const T *)(rowp + off));
                     __builtin_amdgcn_sched_barrier(0);
@@ -589,7 +591,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         Raw8 raw_even = load8(in + row_first * A.ld_in + off_n);
         Raw8 raw_odd = raw_even;
         if (n_my > 1) raw_odd = load8(in + (row_first + row_step) * A.ld_in + off_n);
-        for (int64_t it = 0; it < n_my + 2; it += 2) {
+        for (int it = 0; it < n_my + 2; it += 2) {
             iteration(it, raw_even);
             if (it + 1 < n_my + 2) iteration(it + 1, raw_odd);
         }
