@@ -129,7 +129,9 @@ struct Part {
     int ts;     // row length of the plan's tables (n)
     int tmask;  // an element e of the 4096-point block uses table column (c0 + e) & tmask
     int n_log;
-    int64_t tail_row;  // kVirt: the kernel row (counted from this launch's first) that is the short last block
+    // Row counters are 32-bit: a launch covers at most 2^18 kernel rows, and 64-bit comparisons of uniform values
+    // would run on the vector unit.
+    int tail_row;  // kVirt: the kernel row (counted from this launch's first) that is the short last block, or -1
     int tail;          // ... and the number of rows it has
     static constexpr int xs = kHalf ? 2 * G::n : G::n;  // row length of x_k; a slice holds xs / 2 sums per layer
     __device__ __forceinline__ Part(const BwdFastArgs &A)
@@ -141,7 +143,8 @@ struct Part {
         ts = kVirt ? A.n : xs;
         tmask = ts - 1;
         n_log = kVirt ? A.n_log : (kHalf ? K + 1 : K);
-        tail_row = kVirt ? (A.total_rows >> (K - A.n_log)) - A.row0 : -1;
+        const int64_t tr = kVirt ? (A.total_rows >> (K - A.n_log)) - A.row0 : -1;
+        tail_row = (tr >= 0 && tr < A.rows) ? (int)tr : -1;
         tail = kVirt ? (int)(A.total_rows & ((G::n >> A.n_log) - 1)) : 0;
     }
     __device__ __forceinline__ int col(int e) const { return (c0 + e) & tmask; }
@@ -190,16 +193,17 @@ __global__ __launch_bounds__(G::threads) __attribute__((amdgpu_waves_per_eu(4)))
     // kVirt: a sub-row missing from the last block reads the block's first row instead (its dy will be zero)
     const uint32_t off_x = part.off(idx_n, A.sub_ld_in), off_x0 = part.off(idx_n & part.tmask, A.sub_ld_in);
     const bool gap = part.in_tail_gap(idx_n);
-    auto load_row = [&](int64_t r) { return load8(x + r * A.ld_in + ((gap && r == part.tail_row) ? off_x0 : off_x)); };
+    auto load_row = [&](int r) { return load8(x + r * A.ld_in + ((gap && r == part.tail_row) ? off_x0 : off_x)); };
     float *xk = A.xk + part.c0 + idx_n;
-    int64_t row = part.slot;
-    if (row >= A.rows) return;
+    const int n_rows = (int)A.rows;
+    int row = part.slot;
+    if (row >= n_rows) return;
     Raw8 raw = load_row(row);
-    for (; row < A.rows; row += part.nslots) {
+    for (; row < n_rows; row += part.nslots) {
         float u[8];
         unpack8(raw, u, (const T *)nullptr);
-        const int64_t next = row + part.nslots;
-        if (next < A.rows) raw = load_row(next);
+        const int next = row + part.nslots;
+        if (next < n_rows) raw = load_row(next);
         reg_layer_first<0>(u, cn[0]);
         reg_layer<1>(u, cn[1]);
         reg_layer<2>(u, cn[2]);
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(G::threads) __attribute__((amdgpu_waves_per_eu(4)))
         lds_read_n2(dtab, an, d);
 #pragma unroll
         for (int r = 0; r < 8; ++r) u[r] *= d[r];
-        store8(xk + row * xs, u);
+        store8(xk + (size_t)row * xs, u);
     }
 }
 
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
     const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
     const int an = lds_addr2(idx_n);
     float *hand = lds + 2 * G::kRowFloats;
-    const int64_t mine = A.rows > (int64_t)pt.slot ? (A.rows - pt.slot + pt.nslots - 1) / pt.nslots : 0;
+    const int mine = A.rows > (int64_t)pt.slot ? (int)((A.rows - pt.slot + pt.nslots - 1) / pt.nslots) : 0;
     float *part = A.partial + (size_t)pt.slot * A.slice_floats;
     const float *fg = A.fg_inv, *fw = A.fw_inv;
     if (role == 0) {
@@ -469,18 +473,18 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         const uint32_t off_g = pt.off(idx_n, A.sub_ld_in) * (uint32_t)sizeof(T);
         const uint32_t off_g0 = pt.off(idx_n & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
         const bool gap = pt.in_tail_gap(idx_n);
-        auto fetch = [&](int64_t r, float(&ox)[8], Raw8 &og, Raw8 &ogo) {
+        auto fetch = [&](int r, float(&ox)[8], Raw8 &og, Raw8 &ogo) {
             uint32_t offx = (uint32_t)idx_n * 4u, offg = (gap && r == pt.tail_row) ? off_g0 : off_g;
             asm volatile("" : "+v"(offx), "+v"(offg));
-            load8_f32((const float *)((const char *)(xk + r * xs) + offx), ox);
+            load8_f32((const float *)((const char *)(xk + (size_t)r * xs) + offx), ox);
             og = load8((const T *)((const char *)(dy + r * A.ld_in) + offg));
             if (kHalf) ogo = load8((const T *)((const char *)(dyo + r * A.ld_in) + offg));
         };
         float nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         Raw8 ng = {}, ngo = {};
-        int64_t row = pt.slot;
+        int row = pt.slot;
         if (mine > 0) fetch(row, nx, ng, ngo);
-        for (int64_t it = 0; it < mine; ++it, row += pt.nslots) {
+        for (int it = 0; it < mine; ++it, row += pt.nslots) {
             float vx[8], vg[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) vx[r] = nx[r];
@@ -501,7 +505,7 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
                     vg[r] = __builtin_fmaf(c13[r], go[r], vg[r]);
                 }
             }
-            const int64_t next = it + 1 < mine ? row + pt.nslots : row;  // the last one reads its own row again
+            const int next = it + 1 < mine ? row + pt.nslots : row;  // the last one reads its own row again
             fetch(next, nx, ng, ngo);
             lds_write_n2(lds, an, vx);
             lds_write_n2(lds + G::kRowFloats, an, vg);
@@ -541,8 +545,8 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.ts) * (uint32_t)sizeof(T) : 0u;
         __syncthreads();  // the other group's first row
         __syncthreads();
-        int64_t row = pt.slot;
-        for (int64_t it = 0; it < mine; ++it, row += pt.nslots) {
+        int row = pt.slot;
+        for (int it = 0; it < mine; ++it, row += pt.nslots) {
             float vx[8], vg[8];
             lds_read_n2(hand, an, vx);
             lds_read_n2(hand + G::kRowFloats, an, vg);
