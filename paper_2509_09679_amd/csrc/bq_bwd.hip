@@ -110,7 +110,9 @@ struct BwdFastArgs {
     // n = 2^n_log < 4096 (kVirt): a row of the kernels is a block of 4096 / n consecutive rows of the caller;
     // row0, rows, ld_in, ld_out then count and stride blocks, sub_ld_* are the caller's strides and total_rows
     // its row count (the last block may be short: its missing rows are given dy = 0 and are not stored)
-    int n, n_log;
+    // Several heads (row width heads * n <= 4096): a block is 4096 / width whole rows, row_log = log2 of the width,
+    // and every 2^n_log-element piece of a row has its own tables.
+    int n, n_log, row_log, heads;
     int64_t sub_ld_in, sub_ld_out, total_rows;
 };
 
@@ -129,6 +131,7 @@ struct Part {
     int ts;     // row length of the plan's tables (n)
     int tmask;  // an element e of the 4096-point block uses table column (c0 + e) & tmask
     int n_log;
+    int row_log, rmask;  // kVirt: log2 of the caller's row width and width - 1 (else 0, 0)
     // Row counters are 32-bit: a launch covers at most 2^18 kernel rows, and 64-bit comparisons of uniform values
     // would run on the vector unit.
     int tail_row;  // kVirt: the kernel row (counted from this launch's first) that is the short last block, or -1
@@ -143,18 +146,24 @@ struct Part {
         ts = kVirt ? A.n : xs;
         tmask = ts - 1;
         n_log = kVirt ? A.n_log : (kHalf ? K + 1 : K);
-        const int64_t tr = kVirt ? (A.total_rows >> (K - A.n_log)) - A.row0 : -1;
+        row_log = kVirt ? A.row_log : 0;
+        rmask = kVirt ? (1 << A.row_log) - 1 : 0;
+        const int64_t tr = kVirt ? (A.total_rows >> (K - A.row_log)) - A.row0 : -1;
         tail_row = (tr >= 0 && tr < A.rows) ? (int)tr : -1;
-        tail = kVirt ? (int)(A.total_rows & ((G::n >> A.n_log) - 1)) : 0;
+        tail = kVirt ? (int)(A.total_rows & ((G::n >> A.row_log) - 1)) : 0;
     }
     __device__ __forceinline__ int col(int e) const { return (c0 + e) & tmask; }
+    // the head (transform of the caller's row) of block element e; 0 unless kVirt with several heads
+    __device__ __forceinline__ int head(int e) const { return kVirt ? (e & rmask) >> n_log : 0; }
+    // offset into a [head][layer][n] table of the row of layer `layer` (0-based) for block element e
+    __device__ __forceinline__ size_t trow(int e, int layer) const { return ((size_t)head(e) * n_log + layer) * ts; }
     // element offset of block element e (a multiple of 8) from the start of this workgroup's part of a kernel row
     __device__ __forceinline__ uint32_t off(int e, int64_t sub_ld) const
     {
-        return kVirt ? (uint32_t)((e >> n_log) * (int)sub_ld + (e & tmask)) : (uint32_t)e;
+        return kVirt ? (uint32_t)((e >> row_log) * (int)sub_ld + (e & rmask)) : (uint32_t)e;
     }
-    // kVirt: is the sub-row of element e missing from the short last block?
-    __device__ __forceinline__ bool in_tail_gap(int e) const { return kVirt && (e >> n_log) >= tail; }
+    // kVirt: is the row of element e missing from the short last block?
+    __device__ __forceinline__ bool in_tail_gap(int e) const { return kVirt && (e >> row_log) >= tail; }
 };
 
 // ---- F: forward cascade of layers 1..12 to float32 ------------------------------------------------------
@@ -176,17 +185,19 @@ __global__ __launch_bounds__(G::threads) __attribute__((amdgpu_waves_per_eu(4)))
 #pragma unroll
     for (int j = 0; j < 7; ++j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) cn[j][r] = fg[j * ts + part.col(idx_n) + r];
+        for (int r = 0; r < 8; ++r) cn[j][r] = fg[part.trow(idx_n, j) + part.col(idx_n) + r];
 #pragma unroll
     for (int j = 0; j < K - 7; ++j)
 #pragma unroll
         for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
-            cp[j][r] = (!kVirt || 8 + j <= part.n_log) ? fg[(7 + j) * ts + part.col(idx_p + p_reg_idx2<K>(r))] : 0.0f;
+            cp[j][r] = (!kVirt || 8 + j <= part.n_log)
+                           ? fg[part.trow(idx_p + p_reg_idx2<K>(r), 7 + j) + part.col(idx_p + p_reg_idx2<K>(r))]
+                           : 0.0f;
     {
         const float *scale = kHalf ? A.fm_fwd : A.fd_fwd;
         float d[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) d[r] = scale[part.col(idx_n) + r];
+        for (int r = 0; r < 8; ++r) d[r] = scale[(size_t)part.head(idx_n) * ts + part.col(idx_n) + r];
         lds_write_n2(dtab, an, d);
     }
     const T *x = (const T *)A.x + A.row0 * A.ld_in + part.c0;
@@ -309,23 +320,29 @@ struct CoefSplit {
     }
 };
 
+// fw_inv entry (scale before transposed layer i) of block element e; rmask != 0: the tables of e's own head
+__device__ __forceinline__ float fw_at(const float *fw_inv, int stride, int tmask, int n_log, int rmask, int c0, int e, int i)
+{
+    const int hd = (e & rmask) >> n_log;
+    return fw_inv[((size_t)hd * n_log + (i - 1)) * stride + ((c0 + e) & tmask)];
+}
+
 // Deferred sums -> dtheta partials of this workgroup.  part: its slice, `pairs` sums per layer, indexed by the
 // pair's position in the whole kernel row (c0 + element); fw_inv: the plan table, rows `stride` apart, column
 // (c0 + element) & tmask.
 __device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx_p, const float *fw_inv, int stride, int tmask,
-                                           int pairs, int c0, int n_log, int first)
+                                           int pairs, int c0, int n_log, int rmask, int first)
 {
 #pragma unroll
     for (int J = 1; J <= 2; ++J) {  // register layers
         const int i = (J == 2) ? K : K - 1;
         if (i > n_log) continue;  // a layer the transform does not have: no table row, nothing to write
-        const float *fw = fw_inv + (size_t)(i - 1) * stride;
         int q = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
-                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw[(c0 + a) & tmask] * fw[(c0 + b) & tmask]);
+                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, a, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i));
                 put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), v, first);
                 ++q;
             }
@@ -335,7 +352,6 @@ __device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx
     for (int j = 0; j < 3; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7
         const int i = 8 + j;
         if (i > n_log) continue;
-        const float *fw = fw_inv + (size_t)(i - 1) * stride;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const float mine = acc.d[j][r];
@@ -343,25 +359,24 @@ __device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx
             const int e = idx_p + p_reg_idx2<K>(r);
             if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw[(c0 + e) & tmask] * fw[(c0 + b) & tmask]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, e, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
             }
         }
     }
 }
 
 __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int stride, int tmask,
-                                           int pairs, int c0, int n_log, int first)
+                                           int pairs, int c0, int n_log, int rmask, int first)
 {
 #pragma unroll
     for (int J = 0; J < 3; ++J) {  // layers 1..3
         const int i = J + 1;
-        const float *fw = fw_inv + (size_t)(i - 1) * stride;
         int q = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             if (!(r & (1 << J))) {
                 const int a = idx + r, b = idx + (r | (1 << J));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), acc.r[J][q] * (fw[(c0 + a) & tmask] * fw[(c0 + b) & tmask]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), acc.r[J][q] * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, a, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
                 ++q;
             }
         }
@@ -369,7 +384,6 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
 #pragma unroll
     for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
         const int i = 4 + j;
-        const float *fw = fw_inv + (size_t)(i - 1) * stride;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const float mine = acc.d[j][r];
@@ -377,7 +391,7 @@ __device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx
             const int e = idx + r;
             if (!(e & (1 << (i - 1)))) {
                 const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw[(c0 + e) & tmask] * fw[(c0 + b) & tmask]), first);
+                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, e, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
             }
         }
     }
@@ -455,7 +469,9 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         for (int j = 0; j < 5; ++j)
 #pragma unroll
             for (int r = 0; r < 8; ++r)
-                cp[j][r] = (!kVirt || 8 + j <= pt.n_log) ? fg[(7 + j) * ts + pt.col(idx_p + p_reg_idx2<K>(r))] : 0.0f;
+                cp[j][r] = (!kVirt || 8 + j <= pt.n_log)
+                               ? fg[pt.trow(idx_p + p_reg_idx2<K>(r), 7 + j) + pt.col(idx_p + p_reg_idx2<K>(r))]
+                               : 0.0f;
         float c13[8], acc13[8];  // kHalf only: layer 13 in layout N (it pairs column e with e + 4096)
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -519,7 +535,7 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
         }
         __syncthreads();  // the other group's last row
         __syncthreads();
-        finalize_p(part, acc, idx_p, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, A.first_chunk);
+        finalize_p(part, acc, idx_p, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, kVirt ? pt.rmask : 0, A.first_chunk);
         if (kHalf) {
             // sum of layer 13 = (scale after the layer)^2 * deferred sum; the lower half's share goes to the
             // layer's place in the slice, the upper half's, negated, behind the slice's regular part
@@ -534,15 +550,16 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
     } else {
         float *dtab = lds + 4 * G::kRowFloats;  // tables written and read by the same thread
         CoefSplit<kPnLdsLayers> cn;
-        cn.load(fg, ts, pt.col(idx_n), dtab + G::n, tid);
-        ((float4 *)dtab)[tid] = *(const float4 *)(A.fd_inv + pt.col(idx_n));
-        ((float4 *)dtab)[512 + tid] = *(const float4 *)(A.fd_inv + pt.col(idx_n) + 4);
+        cn.load(fg + pt.trow(idx_n, 0), ts, pt.col(idx_n), dtab + G::n, tid);
+        const float *fdi = A.fd_inv + (size_t)pt.head(idx_n) * ts + pt.col(idx_n);
+        ((float4 *)dtab)[tid] = *(const float4 *)fdi;
+        ((float4 *)dtab)[512 + tid] = *(const float4 *)(fdi + 4);
         NAcc acc;
         acc.clear();
         T *dx = (T *)A.dx + A.row0 * A.ld_out + pt.c0;  // used only if kDx
         const uint32_t off_dx = pt.off(idx_n, A.sub_ld_out) * (uint32_t)sizeof(T);
-        const uint32_t block_bytes = (uint32_t)(((G::n >> pt.n_log) - 1) * A.sub_ld_out + pt.ts) * (uint32_t)sizeof(T);
-        const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.ts) * (uint32_t)sizeof(T) : 0u;
+        const uint32_t block_bytes = (uint32_t)(((G::n >> pt.row_log) - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T);
+        const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T) : 0u;
         __syncthreads();  // the other group's first row
         __syncthreads();
         int row = pt.slot;
@@ -565,7 +582,7 @@ __global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
             }
             __syncthreads();  // B2
         }
-        finalize_n(part, acc, idx_n, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, A.first_chunk);
+        finalize_n(part, acc, idx_n, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, kVirt ? pt.rmask : 0, A.first_chunk);
     }
 }
 
@@ -589,18 +606,20 @@ __global__ void bwd_reduce_kernel(const float *__restrict__ partial, Out *__rest
     out[q] = (Out)acc;
 }
 
-// n < 4096: the sums of a 4096-point block hold, per layer, the 4096 / n rows of the block side by side;
-// dtheta[i][p] = sum over those rows, in row order
-__global__ void bwd_fold_kernel(const double *__restrict__ sums, float *__restrict__ dtheta, int n_log, const int *bad_fwd,
-                                const int *bad_inv)
+// n < 4096: the sums of a 4096-point block hold, per layer, the block's rows side by side, each with its `heads`
+// transforms; dtheta[h][i][p] = sum over the rows, in row order
+__global__ void bwd_fold_kernel(const double *__restrict__ sums, float *__restrict__ dtheta, int n_log, int heads,
+                                const int *bad_fwd, const int *bad_inv)
 {
     if ((*bad_fwd | *bad_inv) != 0) return;
     const int half = 1 << (n_log - 1);
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= n_log * half) return;
-    const int layer = q >> (n_log - 1), p = q & (half - 1);
+    if (q >= heads * n_log * half) return;
+    const int p = q & (half - 1), hl = q >> (n_log - 1);
+    const int layer = hl % n_log, h = hl / n_log;
+    const int block_rows = (G::n >> n_log) / heads;
     double acc = 0.0;
-    for (int sub = 0; sub < (G::n >> n_log); ++sub) acc += sums[layer * (G::n / 2) + sub * half + p];
+    for (int row = 0; row < block_rows; ++row) acc += sums[layer * (G::n / 2) + (row * heads + h) * half + p];
     dtheta[q] = (float)acc;
 }
 
@@ -613,20 +632,23 @@ static constexpr int kBwdFGrid = 512;
 // re-reads the coefficients and rewrites the partial slices, which only amortises over many rows per workgroup.
 static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (k == 13 ? 17 : 18); }
 static size_t bwd_fast_slice_floats(int k) { return k == 13 ? (size_t)13 * 4096 + 4096 : (size_t)K * (G::n / 2); }
+static int64_t bwd_fast_block_rows(const Shape &s) { return s.k < K ? (int64_t)G::n / ((int64_t)s.n * s.heads) : 1; }
 static int64_t bwd_fast_kernel_rows(const Shape &s)
 {
-    const int64_t r = s.k < K ? (int64_t)G::n >> s.k : 1;
+    const int64_t r = bwd_fast_block_rows(s);
     return (s.rows + r - 1) / r;
 }
 
 bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const float *dtheta, const Shape &s)
 {
-    if (s.k < 8 || s.k > 13 || s.heads != 1 || dtheta == nullptr || s.rows == 0) return false;
+    if (s.k < 8 || s.k > 13 || dtheta == nullptr || s.rows == 0) return false;
+    // several heads: n < 4096 with rows of at most 4096 elements that tile a 4096-element block
+    if (s.heads != 1 && (s.k >= K || (int64_t)s.n * s.heads > G::n || G::n % (s.n * s.heads) != 0)) return false;
     const int vec = s.dtype == BQ_F32 ? 4 : 8;
     if (((uintptr_t)x & 15) || ((uintptr_t)dy & 15) || (dx && ((uintptr_t)dx & 15))) return false;
     if ((s.ld_x % vec) || (s.ld_y % vec)) return false;
     if (s.k < K) {  // offsets inside a block of 4096 / n rows are 32-bit byte offsets
-        const int64_t r = (int64_t)G::n >> s.k;
+        const int64_t r = bwd_fast_block_rows(s);
         if (r * s.ld_x * 4 >= ((int64_t)1 << 31) || r * s.ld_y * 4 >= ((int64_t)1 << 31)) return false;
     }
     return true;
@@ -675,9 +697,9 @@ static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta
         const size_t sums = (size_t)s.k * (G::n / 2);  // the layers the transform has
         hipLaunchKernelGGL(bwd_reduce_kernel<double>, dim3((unsigned)((sums + 255) / 256)), dim3(256), 0, stream,
                            (const float *)ws, fold, sums, (size_t)A.slice_floats, sums, slices, A.bad_fwd, A.bad_inv);
-        const unsigned angles = (unsigned)(s.k * (s.n / 2));
+        const unsigned angles = (unsigned)(s.heads * s.k * (s.n / 2));
         hipLaunchKernelGGL(bwd_fold_kernel, dim3((angles + 255) / 256), dim3(256), 0, stream, (const double *)fold, dtheta, s.k,
-                           A.bad_fwd, A.bad_inv);
+                           s.heads, A.bad_fwd, A.bad_inv);
     } else {
         const size_t angles = (size_t)s.k * (s.n / 2);
         hipLaunchKernelGGL(bwd_reduce_kernel<float>, dim3((unsigned)((angles + 255) / 256)), dim3(256), 0, stream,
@@ -714,10 +736,12 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     A.bad_inv = &pv.hdr->fast_bad_inv;
     A.n = s.n;
     A.n_log = s.k;
+    A.heads = s.heads;
+    A.row_log = s.k < K ? ilog2_exact(s.n * s.heads) : 0;
     A.total_rows = s.rows;
     A.sub_ld_in = s.ld_x;
     A.sub_ld_out = s.ld_y;
-    const int64_t block_rows = s.k < K ? (int64_t)G::n >> s.k : 1;
+    const int64_t block_rows = bwd_fast_block_rows(s);
     A.ld_in = s.ld_x * block_rows;
     A.ld_out = s.ld_y * block_rows;
     char *w = (char *)ws;

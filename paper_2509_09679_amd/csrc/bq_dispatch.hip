@@ -31,7 +31,7 @@ hipError_t launch_transform(Mode mode, const void *in, void *out, const PlanView
 size_t bwd_workspace_bytes(const Shape &s)
 {
     size_t need = bwd_workspace_bytes_generic(s);
-    if (s.k >= 8 && s.k <= 13 && s.heads == 1 && s.rows > 0) {
+    if (s.k >= 8 && s.k <= 13 && s.rows > 0 && (s.heads == 1 || (s.k < 12 && (int64_t)s.n * s.heads <= 4096))) {
         const size_t fast = bwd_fast_workspace_bytes(s);
         if (fast > need) need = fast;
     }

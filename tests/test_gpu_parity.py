@@ -499,3 +499,17 @@ def test_mid_sizes_several_heads_flagged_plan():
     gu.check_rotated(gu.run_transform(x, th, n, heads, "f16"), _ref_fwd(x, th, n, heads, "f16"), "f16", "mid heads flagged fwd")
     gu.check_rotated(gu.run_transform(x, th, n, heads, "f16", inverse=True),
                      oracle.inverse(synth.to_f64(x, "f16"), th, n, heads), "f16", "mid heads flagged inv")
+
+
+@pytest.mark.parametrize("n,heads,rows,dtype", MID_HEADS)
+@pytest.mark.parametrize("pad", [0, 16])
+def test_mid_sizes_several_heads_backward(n, heads, rows, dtype, pad):
+    # rows of up to 4096 elements run on the fused backward kernels (blocks of whole rows), wider ones on the general one
+    x, th, dy = synth.small_case(n, rows, dtype, heads=heads, seed=130 + n + heads, with_dy=True, outliers=0)
+    rdx, rdth, ab = oracle.backward(synth.to_f64(x, dtype), synth.to_f64(dy, dtype), th, n, heads)
+    dx, dth = gu.run_bwd(x, dy, th, n, heads, dtype, pad=pad)
+    gu.check_rotated(dx, rdx, dtype, f"mid heads dx n={n} H={heads}")
+    floor = np.median(ab, axis=2, keepdims=True)  # few rows: see tests/test_gpu_sweep.py
+    gu.check_dtheta(dth, rdth, np.maximum(ab, floor), what=f"mid heads n={n} H={heads} T={rows} {dtype}")
+    _, dth_only = gu.run_bwd(x, dy, th, n, heads, dtype, want_dx=False, pad=pad)
+    np.testing.assert_array_equal(dth, dth_only)
