@@ -106,7 +106,8 @@ def check_rotated(y_store, y_ref, dtype, what="", tol=None):
         # half-precision outputs must almost always be THE correct rounding of the oracle value
         ref_r = round_to_storage(y_ref, dtype)
         exact = (y == ref_r).mean()
-        assert exact > 0.99, f"{what}: only {exact:.4f} of outputs are the correctly rounded oracle value"
+        misses = int((y != ref_r).sum())  # (a tiny output may miss the 99 % with two or three legitimate neighbours)
+        assert exact > 0.99 or misses <= 3, f"{what}: only {exact:.4f} of outputs are the correctly rounded oracle value"
         if dtype == "bf16":
             # rounding to bfloat16 alone moves a row by up to ~2.4e-3 of its norm: the row-norm bound
             # is applied to the distance from the correctly rounded oracle row instead

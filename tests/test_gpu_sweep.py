@@ -16,7 +16,7 @@ def _cases():
     rng = np.random.default_rng(20250927)
     sizes = [2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384]
     out = []
-    for i in range(120):
+    for i in range(300):
         n = int(sizes[rng.integers(len(sizes))])
         heads = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 8, 12, 16, 40]))
         while n * heads > 16384:
