@@ -192,3 +192,73 @@ def test_workload4_full_size_per_head_backward():
     rdx, rdth, ab = oracle.backward(xs, gs, th, n, H)
     gu.check_rotated(synth.torch_to_storage(dx, dtype), rdx, dtype, "c4 full dx")
     gu.check_dtheta(dth.cpu().numpy(), rdth, ab, what="c4 full dtheta")
+
+
+@pytest.mark.parametrize("n,heads", [(256, 1), (512, 2)])
+def test_backward_blocks_of_small_transforms_across_two_chunks(n, heads):
+    # n < 4096: the kernels work on 4096-element blocks, 2^18 of them per launch.  A batch just above that runs a
+    # second launch whose last block is short: dx on sampled rows, dtheta on the whole batch (oracle in chunks).
+    dtype = "f16"
+    width = n * heads
+    block_rows = 4096 // width
+    T = (1 << 18) * block_rows + 2 * block_rows + max(1, block_rows // 3)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(9679 + n)
+    x = torch.randn((T, width), generator=g, device=DEV, dtype=torch.float32).to(torch.float16)
+    dy = torch.randn((T, width), generator=g, device=DEV, dtype=torch.float32).to(torch.float16)
+    th = synth.small_case(n, 1, dtype, heads=heads, seed=7)[1]
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, heads)
+    rows = B.make_rows(x, n, heads)
+    dx = torch.empty_like(x)
+    dth = torch.empty_like(theta)
+    ws = torch.empty(B.bq_butterfly_bwd_workspace_bytes(rows), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
+    torch.cuda.synchronize()
+    del ws
+    pick = np.unique(np.concatenate([_sample_rows(T, 64, 4), np.arange(T - 3 * block_rows, T),
+                                     np.arange((1 << 18) * block_rows - 4, (1 << 18) * block_rows + 4)]))
+    pt = torch.as_tensor(pick, device=DEV)
+    gs = synth.torch_to_storage(dy[pt], dtype)
+    gu.check_rotated(synth.torch_to_storage(dx[pt], dtype), oracle.inverse(synth.to_f64(gs, dtype), th, n, heads), dtype,
+                     f"two chunks dx n={n}")
+    acc = ab = None
+    step = 1 << 16
+    for r0 in range(0, T, step):
+        xs = synth.to_f64(synth.torch_to_storage(x[r0:r0 + step], dtype), dtype)
+        g64 = synth.to_f64(synth.torch_to_storage(dy[r0:r0 + step], dtype), dtype)
+        _, d, a = oracle.backward(xs, g64, th, n, heads)
+        acc = d if acc is None else acc + d
+        ab = a if ab is None else ab + a
+    gu.check_dtheta(dth.cpu().numpy(), acc, ab, what=f"two chunks dtheta n={n} H={heads}")
+
+
+def test_backward_small_transforms_many_rows():
+    # n = 128, one head: 16 rows per workgroup pass, 4096 slots of partial sums, about 500 row groups per workgroup
+    n, heads, dtype = 128, 1, "bf16"
+    T = (1 << 21) + 5
+    g = torch.Generator(device=DEV)
+    g.manual_seed(9679)
+    x = torch.randn((T, n), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    dy = torch.randn((T, n), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    th = synth.small_case(n, 1, dtype, seed=11)[1]
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, heads)
+    rows = B.make_rows(x, n, heads)
+    dx = torch.empty_like(x)
+    dth = torch.empty_like(theta)
+    ws = torch.empty(B.bq_butterfly_bwd_workspace_bytes(rows), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
+    torch.cuda.synchronize()
+    pt = torch.as_tensor(_sample_rows(T, 256, 5), device=DEV)
+    gs = synth.torch_to_storage(dy[pt], dtype)
+    gu.check_rotated(synth.torch_to_storage(dx[pt], dtype), oracle.inverse(synth.to_f64(gs, dtype), th, n), dtype, "many rows dx")
+    acc = ab = None
+    step = 1 << 18
+    for r0 in range(0, T, step):
+        xs = synth.to_f64(synth.torch_to_storage(x[r0:r0 + step], dtype), dtype)
+        g64 = synth.to_f64(synth.torch_to_storage(dy[r0:r0 + step], dtype), dtype)
+        _, d, a = oracle.backward(xs, g64, th, n)
+        acc = d if acc is None else acc + d
+        ab = a if ab is None else ab + a
+    gu.check_dtheta(dth.cpu().numpy(), acc, ab, what="many rows dtheta n=128")
