@@ -21,7 +21,6 @@
 namespace bq {
 
 constexpr int kSbThreads = 256;
-constexpr int kSbSpan = kSbThreads * 8;  // elements covered by a workgroup
 constexpr int kSbMaxSlots = 4096;
 
 struct SmallBwdArgs {
@@ -32,7 +31,7 @@ struct SmallBwdArgs {
     const int *bad_fwd, *bad_inv;
     int64_t rows, ld_in, ld_out;
     int heads, width;    // width = heads * n
-    int span;            // elements covered by a workgroup: kSbSpan, or the largest power of two below it that
+    int span;            // elements covered by a workgroup: 2048, or the largest power of two below it that
                          // divides a wider row (the workgroup then has span / 8 threads)
     int rows_per_block;  // span / width if width < span, else 1
     int slices;          // width / span if width >= span, else 1

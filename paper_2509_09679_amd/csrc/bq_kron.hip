@@ -18,7 +18,6 @@ namespace bq {
 // ---- Q1 = (I - A)(I + A)^-1 ------------------------------------------------------------------------------
 // One workgroup, Gauss-Jordan with partial pivoting on [I + A | I - A] in double (I + A is never singular:
 // its eigenvalues are 1 + i*lambda).  d1 <= 64.
-constexpr int kCayleyMax = 64;
 constexpr int kCayleyThreads = 256;
 
 __global__ __launch_bounds__(kCayleyThreads) void cayley_kernel(const float *__restrict__ params, int d1,
