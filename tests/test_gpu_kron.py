@@ -140,3 +140,29 @@ def test_kron_with_a_plan_flagged_singular(d1, d2, dtype):
     _check(_run(x, q1, theta, d1, d2, dtype), kron.kron_forward(x64, q1.astype(np.float64), theta, d2), dtype, "flagged fwd")
     _check(_run(x, q1, theta, d1, d2, dtype, inverse=True), kron.kron_inverse(x64, q1.astype(np.float64), theta, d2), dtype,
            "flagged inv")
+
+
+def _sweep_cases():
+    rng = np.random.default_rng(5120)
+    out = []
+    for i in range(40):
+        d1 = int(rng.integers(2, 65))
+        d2 = int(rng.choice([8, 16, 32, 64, 128, 128, 128, 256, 512, 1024]))
+        rows = int(rng.integers(1, max(2, min(40, 60000 // (d1 * d2)) + 1)))
+        out.append((i, d1, d2, rows, str(rng.choice(["f32", "f16", "bf16"]))))
+    return out
+
+
+@pytest.mark.parametrize("i,d1,d2,rows,dtype", _sweep_cases())
+def test_kron_sweep(i, d1, d2, rows, dtype):
+    # seeded sweep over both code paths (fused for d2 = 128 and d1 <= 40, two passes otherwise) and their borders
+    rng = np.random.default_rng(7000 + i)
+    k = int(math.log2(d2))
+    theta = rng.uniform(-math.pi, math.pi, size=(1, k, d2 // 2)).astype(np.float32)
+    q1 = kron.cayley((0.4 * rng.standard_normal(d1 * (d1 - 1) // 2)).astype(np.float32), d1).astype(np.float32)
+    x = synth.small_case(d2, rows * d1, dtype, seed=200 + i)[0].reshape(rows, d1 * d2)
+    x64, q64 = synth.to_f64(x, dtype), q1.astype(np.float64)
+    fused = d2 == 128 and d1 <= 40
+    _check(_run(x, q1, theta, d1, d2, dtype), kron.kron_forward(x64, q64, theta, d2), dtype, f"kron sweep {i} fwd", fused)
+    _check(_run(x, q1, theta, d1, d2, dtype, inverse=True), kron.kron_inverse(x64, q64, theta, d2), dtype,
+           f"kron sweep {i} inv", fused)
