@@ -483,13 +483,14 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
         // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
         // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
+        constexpr bool kLoadAfterB = kWide && kMode == kFwd;
         auto step = [&](auto BA, auto BB, auto BC, int it) {
             constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
             float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
             float *lc = lds + (bc * kHalves + half) * kLdsRow;
             const float *lb_other = lds + (bb * kHalves + (half ^ 1)) * kLdsRow;  // kWide only
             const float *lc_other = lds + (bc * kHalves + (half ^ 1)) * kLdsRow;
-            if (it < n_my) {  // A(it)
+            auto phase_a = [&]() {  // A(it)
                 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
                 u32x4 v;
                 constexpr int ro = ba * (int)kSlotBytes;
@@ -507,7 +508,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                     asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
                                  : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                 }
-                ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
+                if (!kLoadAfterB) ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
                 Raw8 raw;
                 raw.lo = make_uint4(v.x, v.y, v.z, v.w);
                 float u[8];
@@ -515,8 +516,8 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                 if (!kInverse) reg_layer_first<0>(u, cn[0]);
                 layers_a(u);
                 lds_write_n(la, an, u);
-            }
-            if (it >= 2) {  // C(it-2)
+            };
+            auto phase_c = [&]() {  // C(it-2)
                 float u[8];
                 lds_read_n(lc, an, u);
                 if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
@@ -524,8 +525,24 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
                 finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
+            };
+            if (!kLoadAfterB) {
+                if (it < n_my) phase_a();
+                if (it >= 2) phase_c();
+                if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
+            } else {
+                // The n = 8192 kernels spill a few coefficients, and the compiler waits for their reloads with
+                // vmcnt(0), which also waits for whatever this wave issued before.  In the forward kernel the
+                // reloads sit in phase B, so that phase runs first and the load of a new row and the stores are
+                // issued behind it: they then have most of a step before the next such wait (measured: 0.88 ->
+                // 0.67 ms for 65536 fp16 rows; the other modes, whose reloads sit elsewhere, measured slower in
+                // this order and keep the usual one).  The explicit waits in phase A stay valid: the operations
+                // younger than the awaited load only become more.
+                if (it >= 1 && it <= n_my) phase_b(lb, lb_other);
+                if (it < n_my) ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
+                if (it >= 2) phase_c();
+                if (it < n_my) phase_a();
             }
-            if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
             __syncthreads();
         };
         typedef std::integral_constant<int, 0> I0;
