@@ -64,11 +64,11 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
         A.scale_f16 = q->scale_f16;
         bits = q->bits;
     }
-    // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  On
-    // large batches the fused kernel (VALU-bound) measured fastest with 1024 workgroups, the plain
-    // transforms (HBM-bound) with 768; 512 and 2048 are a few percent slower for both.
+    // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  Swept on
+    // large batches (same box, 512 .. 2048): the fused kernels (VALU-bound) are fastest with 1024 .. 1280
+    // workgroups, the plain transforms (HBM-bound) with 768 or 1280 and 15 % slower with 1024 or 2048.
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
-    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1024 : 768;
+    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : 768;
     int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * A.heads);
