@@ -198,7 +198,7 @@ static void (*pick_small_k(int k, Mode mode, int bits))(SmallArgs)
 // largest power of two that divides the row, down to one wave (512); 0 if there is none.
 int small_span(int64_t width)
 {
-    if (width < kSmallSpan) return kSmallSpan % width == 0 ? kSmallSpan : 0;
+    if (width < kSmallSpan && kSmallSpan % width == 0) return kSmallSpan;  // several whole rows per workgroup
     const int64_t low = width & -width;
     const int span = (int)(low < kSmallSpan ? low : kSmallSpan);
     return span >= 512 ? span : 0;
