@@ -60,7 +60,8 @@ typedef struct {
     int32_t heads; /* H >= 1 transforms side by side; logical row width = H * n <= 2^24,
                       and rows * H * n <= 2^40 (else BQ_ERR_SHAPE)                            */
     int64_t ld_x;  /* row stride, in elements, of the input operand(s)  (>= H * n)            */
-    int64_t ld_y;  /* row stride, in elements, of the output operand    (>= H * n)            */
+    int64_t ld_y;  /* row stride, in elements, of the output operand    (>= H * n);
+                      rows * max(ld_x, ld_y) <= 2^44 (else BQ_ERR_SHAPE)                      */
     int32_t dtype; /* bq_dtype of the row operands (inputs and outputs share it)              */
     int32_t reserved;
 } bq_rows;

@@ -44,6 +44,9 @@ bq_status check_rows(const bq_rows *r, bq::Shape *s, const char *who)
         return fail(BQ_ERR_SHAPE, "%s: leading dimensions (%lld, %lld) smaller than the row width %lld", who,
                     (long long)r->ld_x, (long long)r->ld_y, (long long)w);
     if (r->rows > 0 && r->rows > ((int64_t)1 << 40) / w) return fail(BQ_ERR_SHAPE, "%s: batch too large", who);
+    const int64_t ld_max = r->ld_x > r->ld_y ? r->ld_x : r->ld_y;  // byte offsets of the last row must fit 64 bits
+    if (r->rows > 0 && ld_max > ((int64_t)1 << 44) / r->rows)
+        return fail(BQ_ERR_SHAPE, "%s: rows * leading dimension exceeds 2^44 elements", who);
     s->rows = r->rows;
     s->n = r->n;
     s->heads = r->heads;

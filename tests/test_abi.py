@@ -78,6 +78,13 @@ def test_rejects_other_bad_shapes_and_types():
     assert B.lib().bq_butterfly_inv(FAKE, FAKE, FAKE, ctypes.byref(_rows(n=12)), None) == 2
 
 
+def test_rejects_batches_beyond_the_documented_limits():
+    assert _fwd(_rows(rows=(1 << 33) + 1, n=128)) == 2             # rows * H * n > 2^40
+    assert _fwd(_rows(n=16384, heads=2048)) == 2                   # H * n > 2^24
+    assert _fwd(_rows(rows=1 << 20, n=128, ld=(1 << 24) + 128)) == 2  # rows * ld > 2^44
+    assert b"leading dimension" in B.lib().bq_last_error()
+
+
 def test_zero_rows_is_ok_without_launch():
     assert _fwd(_rows(rows=0)) == 0
     assert B.lib().bq_last_error() == b""
