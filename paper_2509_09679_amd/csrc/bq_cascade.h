@@ -338,28 +338,27 @@ struct BinCount<4> {
     // every lane of the wave must call this together
     __device__ __forceinline__ void drain(unsigned long long *wg)
     {
-        // 16-bit counts (a wave's total is at most 64 * 248), two per word, added across the 64 lanes
-        uint32_t w[8];
+        // 16-bit counts (a wave's total is at most 64 * 248), two per word, added across the 64 lanes; one
+        // word of 8-bit counts at a time, so that this rarely executed path keeps few values alive
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            w[2 * j] = c8[j] & 0x00FF00FFu;             // fields 0 and 2 of c8[j]
-            w[2 * j + 1] = (c8[j] >> 8) & 0x00FF00FFu;  // fields 1 and 3
-        }
+            uint32_t w0 = c8[j] & 0x00FF00FFu;         // fields 0 and 2 of c8[j]
+            uint32_t w1 = (c8[j] >> 8) & 0x00FF00FFu;  // fields 1 and 3
 #pragma unroll
-        for (int m = 1; m < 64; m <<= 1)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) w[j] += (uint32_t)__shfl_xor((int)w[j], m, 64);
-        if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int m = 1; m < 64; m <<= 1) {
+                w0 += (uint32_t)__shfl_xor((int)w0, m, 64);
+                w1 += (uint32_t)__shfl_xor((int)w1, m, 64);
+            }
+            if ((threadIdx.x & 63) == 0) {
 #pragma unroll
                 for (int f = 0; f < 4; ++f) {
                     // field f of c8[j] counts nibble: (j >> 1) * 8 + 2 f + (j & 1); bin = nibble ^ 8
                     const int nibble = (j >> 1) * 8 + 2 * f + (j & 1);
-                    const uint32_t word = w[2 * j + (f & 1)];
+                    const uint32_t word = (f & 1) ? w1 : w0;
                     const uint32_t v = (f >> 1) ? (word >> 16) : (word & 0xFFFFu);
                     if (v) atomicAdd(&wg[nibble ^ 8], (unsigned long long)v);
                 }
+            }
         }
         clear();
     }

@@ -457,11 +457,20 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         // first four iterations (pipeline fill, fewer stores issued) wait for everything.
         constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : 1;
         constexpr uint32_t kSlotBytes = kPoints * 2;
+        // kTwoBuf: two row buffers and two ring slots instead of three.  Phase A of row `it` writes the buffer that
+        // phase C of row it-2 has just read (there each thread reads and writes the same addresses, and C comes
+        // first), and the load of row it+2 refills the slot that A has just read.  The third buffer then holds the
+        // output scales, which leave the registers.  Used where it measured faster: the variant that stores the
+        // fake-quantised row and counts INT4 codes as well, which is short of registers (1.14 -> 1.00 ms for 262144
+        // fp16 rows), and the INT2 variant that only counts (0.82 -> 0.77 ms); the others measured equal or slower.
+        constexpr bool kTwoBuf = kMode == kFwdFake && kHist && !kWide && ((kYq && kBits == 4) || (!kYq && kBits == 2));
         float d[8];
+        float *dtab = lds + 2 * kLdsRow;  // kTwoBuf
         {
             const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
+            if (kTwoBuf) lds_write_n(dtab, an, d);  // read back by the same thread only
         }
         const int wave_row = half * 8 + wave;  // the wave's 1 KB piece of a row
         const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
@@ -508,7 +517,8 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                     asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
                                  : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                 }
-                if (!kLoadAfterB) ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
+                // refills the slot of row it-1, consumed in the previous iteration (kTwoBuf: the slot just read)
+                if (!kLoadAfterB) ring_load(it + 2, kTwoBuf ? ba : bb);
                 Raw8 raw;
                 raw.lo = make_uint4(v.x, v.y, v.z, v.w);
                 float u[8];
@@ -522,8 +532,15 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                 lds_read_n(lc, an, u);
                 if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
                 layers_c(u);
+                if (kTwoBuf) {
+                    float dl[8];
+                    lds_read_n(dtab, an, dl);
 #pragma unroll
-                for (int r = 0; r < 8; ++r) u[r] *= d[r];
+                    for (int r = 0; r < 8; ++r) u[r] *= dl[r];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) u[r] *= d[r];
+                }
                 finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
             };
             if (!kLoadAfterB) {
@@ -551,10 +568,17 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         typedef std::integral_constant<int, 1> I1;
         typedef std::integral_constant<int, 2> I2;
         const int end = n_my + 2;
-        for (int it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
-            step(I0{}, I2{}, I1{}, it);
-            if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
-            if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
+        if (kTwoBuf) {
+            for (int it = 0; it < end; it += 2) {  // (A, B, C) buffers: (0, 1, 0) -> (1, 0, 1) -> ...
+                step(I0{}, I1{}, I0{}, it);
+                if (it + 1 < end) step(I1{}, I0{}, I1{}, it + 1);
+            }
+        } else {
+            for (int it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
+                step(I0{}, I2{}, I1{}, it);
+                if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
+                if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
+            }
         }
     } else {
         // ---- 32-bit rows: two rows prefetched in registers, output scales kept in LDS ---------------

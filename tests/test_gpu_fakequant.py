@@ -182,3 +182,36 @@ def test_fakequant_float32_scales_binary16_rows_is_product_then_rounding(n, head
     exact = scales.cpu().numpy().astype(np.float64).repeat(min(n, 128), axis=1) * c.astype(np.float64)
     once = synth.cast_storage(exact, "f16")
     assert (once.view(np.uint16) != want.view(np.uint16)).sum() > 0
+
+
+@pytest.mark.parametrize("n,rows,group", [(4096, 9000, 128), (1024, 30000, 64), (4096, 7001, 4096)])
+def test_fakequant_every_row_over_many_pipeline_steps(n, rows, group):
+    # Several rows per workgroup, so that the kernels' row buffers and input slots are reused many times;
+    # every element of every row is compared, for both outputs together and for each one alone.
+    import torch
+    from paper_2509_09679_amd import binding as B
+
+    x, th, _ = synth.small_case(n, rows, "f16", heads=1, seed=77 + n + group)
+    theta = torch.from_numpy(th).to("cuda:0")
+    plan = B.alloc_plan(theta, n, 1)
+    xd = synth.storage_to_torch(x, "f16", "cuda:0")
+    r = B.make_rows(xd, n, 1)
+    for bits in (4, 2):
+        q = B.make_quant(bits, group, "f16")
+        codes, scales = B.alloc_quant_outputs(rows, n, 1, bits, group, "f16", "cuda:0")
+        B.bq_butterfly_fwd_quant(xd, plan, codes, scales, q, r)
+        yq_both, yq_only = torch.empty_like(xd), torch.empty_like(xd)
+        h_both = torch.zeros(1 << bits, dtype=torch.int64, device="cuda:0")
+        h_only = torch.zeros_like(h_both)
+        B.bq_butterfly_fwd_fakequant(xd, plan, yq_both, h_both, q, r)
+        B.bq_butterfly_fwd_fakequant(xd, plan, yq_only, None, q, r)
+        B.bq_butterfly_fwd_fakequant(xd, plan, None, h_only, q, r)
+        torch.cuda.synchronize()
+        c = oracle.unpack_codes(codes.cpu().numpy(), bits)
+        want_hist = oracle.bin_histogram(c, bits)
+        np.testing.assert_array_equal(h_both.cpu().numpy().astype(np.uint64), want_hist)
+        np.testing.assert_array_equal(h_only.cpu().numpy().astype(np.uint64), want_hist)
+        deq = oracle.dequantize(c, scales.float().cpu().numpy(), group)
+        want = synth.cast_storage(deq.astype(np.float64), "f16").view(np.uint16)
+        np.testing.assert_array_equal(synth.torch_to_storage(yq_both, "f16").view(np.uint16), want)
+        np.testing.assert_array_equal(synth.torch_to_storage(yq_only, "f16").view(np.uint16), want)
