@@ -20,8 +20,9 @@
 //             output scale, store
 //
 // The three phases of consecutive rows are software-pipelined: iteration `it` of a workgroup runs
-// C(row it-2), B(row it-1), A(row it) and then ONE barrier; LDS1 and LDS2 are double-buffered by row
-// parity, so every read of a buffer is separated from the next write to it by a barrier.
+// C(row it-2), B(row it-1), A(row it) and then ONE barrier; three row buffers rotate through the roles,
+// so every read of a buffer is separated from the next write to it by a barrier.  (Some variants use two
+// buffers: A then overwrites what C has just read, each thread at the very addresses it read itself.)
 //
 // LDS accesses are 64-bit (two adjacent floats per lane), which is what reaches the full LDS rate.
 // LDS float address of idx is idx + 2 (idx >> 5) + 2 (idx >> 9).  For a group of 16 lanes the N-side
@@ -47,7 +48,8 @@ namespace bq {
 
 constexpr int kN = 4096, kK = 12, kThreads = 512;
 constexpr int kLdsRow = 4368;  // floats: 4095 + 2*127 + 2*7 + 1, rounded up to a multiple of 4
-// three row buffers plus either the input ring (3 x 8 KB, 16-bit rows) or the output-scale table (32-bit rows)
+// three row buffers behind the input ring (3 x 8 KB, 16-bit rows) or the output-scale table (32-bit rows of
+// n = 8192); 32-bit rows of n <= 4096: two ring slots of 16 KB and two row buffers inside the same allocation
 constexpr int kFrontFloats = 3 * kN * 2 / 4;  // 6144 floats = 24 KB in front of the row buffers
 static_assert(kFrontFloats >= kLdsRow, "scale table must fit");
 constexpr size_t kLdsBytes = (kFrontFloats + 3 * kLdsRow) * sizeof(float);
@@ -305,7 +307,9 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     };
     // LDS: [input ring 3 x 8 KB | output-scale table] first (low addresses), then the row buffers L[0..2]
     extern __shared__ float lds_raw[];
-    float *lds = lds_raw + kHalves * kFrontFloats;
+    // (32-bit rows of n = 4096: two ring slots of 16 KB in front, two row buffers behind them)
+    constexpr bool kRing32 = sizeof(T) == 4 && !kWide;
+    float *lds = lds_raw + (kRing32 ? 2 * kN : kHalves * kFrontFloats);
     constexpr bool kInverse = (kMode == kInv);
     // kWide: `half` selects the half of the row; tid, wave, chunk and idx_n count inside the half
     const int half = kWide ? (int)(threadIdx.x >> 9) : 0;
@@ -442,11 +446,11 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         ba = t;
     };
 
-    if constexpr (sizeof(T) == 2) {
-        // ---- 16-bit rows: input staged through an LDS ring filled by direct global->LDS loads -------
+    if constexpr (sizeof(T) == 2 || kRing32) {
+        // ---- input staged through an LDS ring filled by direct global->LDS loads -------------------
         // Two rows per workgroup have to be in flight from HBM to cover its latency, and there are
         // no registers left to hold them.  global_load_lds_dwordx4 moves 16 bytes per lane straight
-        // into LDS (wave w, lane l -> bytes [1024 w + 16 l, +16) of the ring slot, row order), the
+        // into LDS (16-bit rows: wave w, lane l -> bytes [1024 w + 16 l, +16) of the ring slot, row order), the
         // thread later reads its own chunk back with ds_read_b128.  A wave only reads what it loaded
         // itself, so s_waitcnt vmcnt is the only synchronisation.  These loads and waits are inline
         // assembly: the compiler would otherwise wait for ALL outstanding loads before any LDS read.
@@ -455,28 +459,37 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         // earlier, followed by stores, the load of row it+1 and stores again, so at most
         // 2 kStores + 1 younger operations may still be pending when row `it` is consumed.  The
         // first four iterations (pipeline fill, fewer stores issued) wait for everything.
-        constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : 1;
-        constexpr uint32_t kSlotBytes = kPoints * 2;
+        // 32-bit rows: two such loads per lane and row (kLoads), two stores per lane for a row of output.
+        constexpr int kLoads = (int)sizeof(T) / 2;
+        constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : kLoads;
+        constexpr int kPending = 2 * kStores + kLoads;  // operations younger than the last load of the awaited row
+        constexpr uint32_t kSlotBytes = kPoints * sizeof(T);
         // kTwoBuf: two row buffers and two ring slots instead of three.  Phase A of row `it` writes the buffer that
         // phase C of row it-2 has just read (there each thread reads and writes the same addresses, and C comes
         // first), and the load of row it+2 refills the slot that A has just read.  The third buffer then holds the
         // output scales, which leave the registers.  Used where it measured faster: the variant that stores the
         // fake-quantised row and counts INT4 codes as well, which is short of registers (1.14 -> 1.00 ms for 262144
         // fp16 rows), and the INT2 variant that only counts (0.82 -> 0.77 ms); the others measured equal or slower.
-        constexpr bool kTwoBuf = kMode == kFwdFake && kHist && !kWide && ((kYq && kBits == 4) || (!kYq && kBits == 2));
+        // 32-bit rows always run this way (their slots are twice as large, and three of them plus three buffers
+        // would not leave room for two workgroups per compute unit), with the output scales in registers.
+        constexpr bool kTwoBuf = kRing32 || (kMode == kFwdFake && kHist && !kWide && ((kYq && kBits == 4) || (!kYq && kBits == 2)));
+        constexpr bool kScaleLds = kTwoBuf && !kRing32;
         float d[8];
-        float *dtab = lds + 2 * kLdsRow;  // kTwoBuf
+        float *dtab = lds + 2 * kLdsRow;  // kScaleLds
         {
             const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
-            if (kTwoBuf) lds_write_n(dtab, an, d);  // read back by the same thread only
+            if (kScaleLds) lds_write_n(dtab, an, d);  // read back by the same thread only
         }
-        const int wave_row = half * 8 + wave;  // the wave's 1 KB piece of a row
+        const int wave_row = half * 8 + wave;  // the wave's piece of a row: 512 elements, 1 KB per load
+        constexpr int kPer = 16 / (int)sizeof(T);  // elements per lane and load
         const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
-        const uint32_t slice = ring0 + (uint32_t)wave_row * 1024u;                // this wave's 1 KB of a slot
-        const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * 16u;        // this thread's chunk
-        const uint32_t voff = elem_off<kVirt, kWide>(A, head, (wave_row * 64 + lane) * 8, A.sub_ld_in) * 2u;  // lane's bytes in a row
+        const uint32_t slice = ring0 + (uint32_t)wave_row * (1024u * kLoads);             // this wave's piece of a slot
+        const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * (16u * kLoads);      // this thread's chunk
+        // lane's bytes in a row, first and (32-bit rows) second load
+        const uint32_t voff = elem_off<kVirt, kWide>(A, head, wave_row * 512 + lane * kPer, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const uint32_t voff1 = kLoads == 2 ? elem_off<kVirt, kWide>(A, head, wave_row * 512 + (64 + lane) * kPer, A.sub_ld_in) * (uint32_t)sizeof(T) : 0u;
         const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
         auto ring_load = [&](int j, int slot) {
             const int jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
@@ -486,6 +499,11 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                          :
                          : "v"(voff), "s"(m0v), "s"(rowp)
                          : "memory");
+            if (kLoads == 2)
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
+                             :
+                             : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
+                             : "memory");
         };
         ring_load(0, 0);
         ring_load(1, 1);
@@ -501,26 +519,28 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             const float *lc_other = lds + (bc * kHalves + (half ^ 1)) * kLdsRow;
             auto phase_a = [&]() {  // A(it)
                 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                u32x4 v;
+                u32x4 v, v1;
                 constexpr int ro = ba * (int)kSlotBytes;
-                if (it >= 4) {
-                    if (kStores == 2)
-                        asm volatile("s_waitcnt vmcnt(5)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                    else if (kStores == 1)
-                        asm volatile("s_waitcnt vmcnt(3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
+                if (kLoads == 1) {
+                    if (it >= 4)
+                        asm volatile("s_waitcnt vmcnt(%3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(rd_addr), "n"(ro), "n"(kPending) : "memory");
                     else
-                        asm volatile("s_waitcnt vmcnt(1)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                        asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
                                      : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
                 } else {
-                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                 : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
+                    if (it >= 4)
+                        asm volatile("s_waitcnt vmcnt(%5)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16), "n"(kPending) : "memory");
+                    else
+                        asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16) : "memory");
                 }
                 // refills the slot of row it-1, consumed in the previous iteration (kTwoBuf: the slot just read)
                 if (!kLoadAfterB) ring_load(it + 2, kTwoBuf ? ba : bb);
                 Raw8 raw;
                 raw.lo = make_uint4(v.x, v.y, v.z, v.w);
+                if (kLoads == 2) raw.hi = make_uint4(v1.x, v1.y, v1.z, v1.w);
                 float u[8];
                 unpack8(raw, u, (const T *)nullptr);
                 if (!kInverse) reg_layer_first<0>(u, cn[0]);
@@ -532,7 +552,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
                 lds_read_n(lc, an, u);
                 if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
                 layers_c(u);
-                if (kTwoBuf) {
+                if (kScaleLds) {
                     float dl[8];
                     lds_read_n(dtab, an, dl);
 #pragma unroll
@@ -581,7 +601,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             }
         }
     } else {
-        // ---- 32-bit rows: two rows prefetched in registers, output scales kept in LDS ---------------
+        // ---- 32-bit rows of n = 8192: two rows prefetched in registers, output scales kept in LDS ----
         float *dtab = lds_raw + half * kLdsRow;
         {
             const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
