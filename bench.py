@@ -361,6 +361,23 @@ def extra_figures(B, synth, torch, dev):
                              "GBps": round(bpr4 * T3 / (avg * 1e-3) / 1e9, 1),
                              "hbm_frac": round(bpr4 * T3 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     del c34, s34
+    # float32 rows (the 1e-5 tolerance class) at the same width: half the rows, the same bytes
+    Tf = T3 // 2
+    xf = x3[:Tf].float()
+    yf = torch.empty_like(xf)
+    rf = B.make_rows(xf, 4096, 1)
+    cf, sf = B.alloc_quant_outputs(Tf, 4096, 1, 2, 128, "f16", dev)
+    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(xf, yf, plan3, rf), 10, 3)
+    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(xf, yf, plan3, rf), 10, 3)
+    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(xf, plan3, cf, sf, q3, rf), 10, 3)
+    b_f = alg_bytes_per_row("fwd", 4096, 1, 4)
+    b_q = alg_bytes_per_row("fwd_quant", 4096, 1, 4, 2, 128, 2)
+    res["f32_rows"] = {"workload": "n=4096, T=131072, float32 rows: forward, inverse, fused forward + INT2 g128",
+                       "fwd_ms": round(a_f, 4), "fwd_GBps": round(b_f * Tf / (a_f * 1e-3) / 1e9, 1),
+                       "inv_ms": round(a_i, 4), "inv_GBps": round(b_f * Tf / (a_i * 1e-3) / 1e9, 1),
+                       "fwd_quant_ms": round(a_q, 4), "fwd_quant_GBps": round(b_q * Tf / (a_q * 1e-3) / 1e9, 1),
+                       "fwd_quant_hbm_frac": round(b_q * Tf / (a_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del xf, yf, cf, sf
     # the same forward kernel with every angle at pi/4 (a signed Hadamard transform): in the scale-deferred
     # form a butterfly layer and a Hadamard layer both cost one FMA-class instruction per element
     import math
