@@ -48,11 +48,11 @@ namespace bq {
 
 constexpr int kN = 4096, kK = 12, kThreads = 512;
 constexpr int kLdsRow = 4368;  // floats: 4095 + 2*127 + 2*7 + 1, rounded up to a multiple of 4
-// three row buffers behind the input ring (3 x 8 KB, 16-bit rows) or the output-scale table (32-bit rows of
-// n = 8192); 32-bit rows of n <= 4096: two ring slots of 16 KB and two row buffers inside the same allocation
+// per half of a row: the input ring (16-bit rows: 3 slots of 8 KB; 32-bit rows: 2 slots of 16 KB) and behind
+// it three row buffers (the variants that use two of them fit the same allocation)
 constexpr int kFrontFloats = 3 * kN * 2 / 4;  // 6144 floats = 24 KB in front of the row buffers
-static_assert(kFrontFloats >= kLdsRow, "scale table must fit");
 constexpr size_t kLdsBytes = (kFrontFloats + 3 * kLdsRow) * sizeof(float);
+static_assert((2 * kN + 2 * kLdsRow) * sizeof(float) <= kLdsBytes, "32-bit rows: two slots and two buffers must fit");
 
 struct K12Args {
     const void *in;
@@ -307,9 +307,9 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     };
     // LDS: [input ring 3 x 8 KB | output-scale table] first (low addresses), then the row buffers L[0..2]
     extern __shared__ float lds_raw[];
-    // (32-bit rows of n = 4096: two ring slots of 16 KB in front, two row buffers behind them)
-    constexpr bool kRing32 = sizeof(T) == 4 && !kWide;
-    float *lds = lds_raw + (kRing32 ? 2 * kN : kHalves * kFrontFloats);
+    // (32-bit rows: two ring slots of 16 KB per half in front, two row buffers behind them)
+    constexpr bool kRing32 = sizeof(T) == 4;
+    float *lds = lds_raw + kHalves * (kRing32 ? 2 * kN : kFrontFloats);
     constexpr bool kInverse = (kMode == kInv);
     // kWide: `half` selects the half of the row; tid, wave, chunk and idx_n count inside the half
     const int half = kWide ? (int)(threadIdx.x >> 9) : 0;
@@ -387,7 +387,6 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     // rows of this workgroup: below 2^28 for every batch the library accepts, so the loop counters are 32-bit
     // (64-bit comparisons of uniform values would be done on the vector unit)
     const int n_my = (int)((A.rows - row_first + row_step - 1) / row_step);
-    int ba = 0, bb = 2, bc = 1;  // buffer (and ring slot) of A(it), B(it-1), C(it-2)
 
     // Phase B of one row: layers 8..12 (or 12..8) on layout P, in place in its LDS buffer.
     // kWide: lb is the buffer of the thread's own half, lo the other half's; the inverse starts with layer 13.
@@ -439,224 +438,160 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             reg_layer<0>(u, cn[0]);
         }
     };
-    auto rotate_buffers = [&]() {
-        const int t = bc;
-        bc = bb;
-        bb = ba;
-        ba = t;
-    };
-
-    if constexpr (sizeof(T) == 2 || kRing32) {
-        // ---- input staged through an LDS ring filled by direct global->LDS loads -------------------
-        // Two rows per workgroup have to be in flight from HBM to cover its latency, and there are
-        // no registers left to hold them.  global_load_lds_dwordx4 moves 16 bytes per lane straight
-        // into LDS (16-bit rows: wave w, lane l -> bytes [1024 w + 16 l, +16) of the ring slot, row order), the
-        // thread later reads its own chunk back with ds_read_b128.  A wave only reads what it loaded
-        // itself, so s_waitcnt vmcnt is the only synchronisation.  These loads and waits are inline
-        // assembly: the compiler would otherwise wait for ALL outstanding loads before any LDS read.
-        // Memory operations of a wave complete in issue order, and per iteration a wave issues one
-        // ring load (in A) and at least kStores stores (in C); row `it` was requested two iterations
-        // earlier, followed by stores, the load of row it+1 and stores again, so at most
-        // 2 kStores + 1 younger operations may still be pending when row `it` is consumed.  The
-        // first four iterations (pipeline fill, fewer stores issued) wait for everything.
-        // 32-bit rows: two such loads per lane and row (kLoads), two stores per lane for a row of output.
-        constexpr int kLoads = (int)sizeof(T) / 2;
-        constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : kLoads;
-        constexpr int kPending = 2 * kStores + kLoads;  // operations younger than the last load of the awaited row
-        constexpr uint32_t kSlotBytes = kPoints * sizeof(T);
-        // kTwoBuf: two row buffers and two ring slots instead of three.  Phase A of row `it` writes the buffer that
-        // phase C of row it-2 has just read (there each thread reads and writes the same addresses, and C comes
-        // first), and the load of row it+2 refills the slot that A has just read.  The third buffer then holds the
-        // output scales, which leave the registers.  Used where it measured faster: the variant that stores the
-        // fake-quantised row and counts INT4 codes as well, which is short of registers (1.14 -> 1.00 ms for 262144
-        // fp16 rows), and the INT2 variant that only counts (0.82 -> 0.77 ms); the others measured equal or slower.
-        // 32-bit rows always run this way (their slots are twice as large, and three of them plus three buffers
-        // would not leave room for two workgroups per compute unit), with the output scales in registers.
-        constexpr bool kTwoBuf = kRing32 || (kMode == kFwdFake && kHist && !kWide && ((kYq && kBits == 4) || (!kYq && kBits == 2)));
-        constexpr bool kScaleLds = kTwoBuf && !kRing32;
-        float d[8];
-        float *dtab = lds + 2 * kLdsRow;  // kScaleLds
-        {
-            const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
+    // ---- input staged through an LDS ring filled by direct global->LDS loads -------------------
+    // Two rows per workgroup have to be in flight from HBM to cover its latency, and there are
+    // no registers left to hold them.  global_load_lds_dwordx4 moves 16 bytes per lane straight
+    // into LDS (16-bit rows: wave w, lane l -> bytes [1024 w + 16 l, +16) of the ring slot, row order), the
+    // thread later reads its own chunk back with ds_read_b128.  A wave only reads what it loaded
+    // itself, so s_waitcnt vmcnt is the only synchronisation.  These loads and waits are inline
+    // assembly: the compiler would otherwise wait for ALL outstanding loads before any LDS read.
+    // Memory operations of a wave complete in issue order, and per iteration a wave issues one
+    // ring load (in A) and at least kStores stores (in C); row `it` was requested two iterations
+    // earlier, followed by stores, the load of row it+1 and stores again, so at most
+    // 2 kStores + 1 younger operations may still be pending when row `it` is consumed.  The
+    // first four iterations (pipeline fill, fewer stores issued) wait for everything.
+    // 32-bit rows: two such loads per lane and row (kLoads), two stores per lane for a row of output.
+    constexpr int kLoads = (int)sizeof(T) / 2;
+    constexpr int kStores = (kMode == kFwdQuant) ? 2 : (kMode == kFwdFake && !kYq) ? 0 : kLoads;
+    constexpr int kPending = 2 * kStores + kLoads;  // operations younger than the last load of the awaited row
+    constexpr uint32_t kSlotBytes = kPoints * sizeof(T);
+    // kTwoBuf: two row buffers and two ring slots instead of three.  Phase A of row `it` writes the buffer that
+    // phase C of row it-2 has just read (there each thread reads and writes the same addresses, and C comes
+    // first), and the load of row it+2 refills the slot that A has just read.  Where the rows are 16-bit the
+    // third buffer then holds the output scales, which leave the registers.  Used
+    //  - for 32-bit rows (slots twice as large: three of them plus three buffers would not leave room for two
+    //    workgroups per compute unit; before, such rows were prefetched in registers, at the price of a dozen
+    //    spilled ones: 131072 rows of n = 4096 went from 1.20 / 0.92 / 0.84 ms to 0.81 / 0.80 / 0.53 ms);
+    //  - for n = 8192, whose kernels are short of registers (65536 fp16 rows: 0.67 / 0.78 / 0.62 ms ->
+    //    0.63 / 0.60 / 0.47 ms forward / inverse / fused quantiser, despite the barrier it adds, see below);
+    //  - for two fake-quantising variants of n <= 4096, where it measured faster: the one that stores the row
+    //    and counts INT4 codes as well (1.14 -> 1.00 ms for 262144 fp16 rows) and the INT2 one that only counts
+    //    (0.82 -> 0.77 ms).  On the other 16-bit variants of n <= 4096 it measured equal or slower.
+    constexpr bool kTwoBuf = kRing32 || kWide || (kMode == kFwdFake && kHist && ((kYq && kBits == 4) || (!kYq && kBits == 2)));
+    constexpr bool kScaleLds = kTwoBuf && !kRing32;
+    float d[8];
+    float *dtab = lds + (2 * kHalves + half) * kLdsRow;  // kScaleLds: the third buffer
+    {
+        const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
 #pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
-            if (kScaleLds) lds_write_n(dtab, an, d);  // read back by the same thread only
-        }
-        const int wave_row = half * 8 + wave;  // the wave's piece of a row: 512 elements, 1 KB per load
-        constexpr int kPer = 16 / (int)sizeof(T);  // elements per lane and load
-        const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
-        const uint32_t slice = ring0 + (uint32_t)wave_row * (1024u * kLoads);             // this wave's piece of a slot
-        const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * (16u * kLoads);      // this thread's chunk
-        // lane's bytes in a row, first and (32-bit rows) second load
-        const uint32_t voff = elem_off<kVirt, kWide>(A, head, wave_row * 512 + lane * kPer, A.sub_ld_in) * (uint32_t)sizeof(T);
-        const uint32_t voff1 = kLoads == 2 ? elem_off<kVirt, kWide>(A, head, wave_row * 512 + (64 + lane) * kPer, A.sub_ld_in) * (uint32_t)sizeof(T) : 0u;
-        const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
-        auto ring_load = [&](int j, int slot) {
-            const int jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
-            const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
-            const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
+        for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
+        if (kScaleLds) lds_write_n(dtab, an, d);  // read back by the same thread only
+    }
+    const int wave_row = half * 8 + wave;  // the wave's piece of a row: 512 elements, 1 KB per load
+    constexpr int kPer = 16 / (int)sizeof(T);  // elements per lane and load
+    const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
+    const uint32_t slice = ring0 + (uint32_t)wave_row * (1024u * kLoads);             // this wave's piece of a slot
+    const uint32_t rd_addr = slice + (uint32_t)lane_chunk(lane) * (16u * kLoads);      // this thread's chunk
+    // lane's bytes in a row, first and (32-bit rows) second load
+    const uint32_t voff = elem_off<kVirt, kWide>(A, head, wave_row * 512 + lane * kPer, A.sub_ld_in) * (uint32_t)sizeof(T);
+    const uint32_t voff1 = kLoads == 2 ? elem_off<kVirt, kWide>(A, head, wave_row * 512 + (64 + lane) * kPer, A.sub_ld_in) * (uint32_t)sizeof(T) : 0u;
+    const uint32_t slice_s = __builtin_amdgcn_readfirstlane(slice);  // uniform over the wave
+    auto ring_load = [&](int j, int slot) {
+        const int jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
+        const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
+        const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
+                     :
+                     : "v"(voff), "s"(m0v), "s"(rowp)
+                     : "memory");
+        if (kLoads == 2)
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
                          :
-                         : "v"(voff), "s"(m0v), "s"(rowp)
+                         : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
                          : "memory");
-            if (kLoads == 2)
-                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
-                             :
-                             : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
-                             : "memory");
-        };
-        ring_load(0, 0);
-        ring_load(1, 1);
-        // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
-        // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
-        // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
-        constexpr bool kLoadAfterB = kWide && kMode == kFwd;
-        auto step = [&](auto BA, auto BB, auto BC, int it) {
-            constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
-            float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
-            float *lc = lds + (bc * kHalves + half) * kLdsRow;
-            const float *lb_other = lds + (bb * kHalves + (half ^ 1)) * kLdsRow;  // kWide only
-            const float *lc_other = lds + (bc * kHalves + (half ^ 1)) * kLdsRow;
-            auto phase_a = [&]() {  // A(it)
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                u32x4 v, v1;
-                constexpr int ro = ba * (int)kSlotBytes;
-                if (kLoads == 1) {
-                    if (it >= 4)
-                        asm volatile("s_waitcnt vmcnt(%3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro), "n"(kPending) : "memory");
-                    else
-                        asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
-                } else {
-                    if (it >= 4)
-                        asm volatile("s_waitcnt vmcnt(%5)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16), "n"(kPending) : "memory");
-                    else
-                        asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
-                                     : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16) : "memory");
-                }
-                // refills the slot of row it-1, consumed in the previous iteration (kTwoBuf: the slot just read)
-                if (!kLoadAfterB) ring_load(it + 2, kTwoBuf ? ba : bb);
-                Raw8 raw;
-                raw.lo = make_uint4(v.x, v.y, v.z, v.w);
-                if (kLoads == 2) raw.hi = make_uint4(v1.x, v1.y, v1.z, v1.w);
-                float u[8];
-                unpack8(raw, u, (const T *)nullptr);
-                if (!kInverse) reg_layer_first<0>(u, cn[0]);
-                layers_a(u);
-                lds_write_n(la, an, u);
-            };
-            auto phase_c = [&]() {  // C(it-2)
-                float u[8];
-                lds_read_n(lc, an, u);
-                if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
-                layers_c(u);
-                if (kScaleLds) {
-                    float dl[8];
-                    lds_read_n(dtab, an, dl);
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) u[r] *= dl[r];
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
-            };
-            if (!kLoadAfterB) {
-                // (the three phases touch different buffers, so any order is correct; this one measured 1-2 %
-                // faster than the others on all four modes)
-                if (it >= 2) phase_c();
-                if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
-                if (it < n_my) phase_a();
+    };
+    ring_load(0, 0);
+    ring_load(1, 1);
+    // One pipeline step with the roles of the three buffers fixed at compile time (BA: phase A of row it,
+    // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
+    // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
+    // n = 8192: whether phase B runs before phase C (see below)
+    constexpr bool kBFirst = kWide && (sizeof(T) == 2 ? (kMode == kFwd || kMode == kInv) : kMode == kFwdFake);
+    auto step = [&](auto BA, auto BB, auto BC, int it) {
+        constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
+        float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
+        float *lc = lds + (bc * kHalves + half) * kLdsRow;
+        const float *lb_other = lds + (bb * kHalves + (half ^ 1)) * kLdsRow;  // kWide only
+        const float *lc_other = lds + (bc * kHalves + (half ^ 1)) * kLdsRow;
+        auto phase_a = [&]() {  // A(it)
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 v, v1;
+            constexpr int ro = ba * (int)kSlotBytes;
+            if (kLoads == 1) {
+                if (it >= 4)
+                    asm volatile("s_waitcnt vmcnt(%3)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(v) : "v"(rd_addr), "n"(ro), "n"(kPending) : "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=v"(v) : "v"(rd_addr), "n"(ro) : "memory");
             } else {
-                // The n = 8192 kernels spill a few coefficients, and the compiler waits for their reloads with
-                // vmcnt(0), which also waits for whatever this wave issued before.  In the forward kernel the
-                // reloads sit in phase B, so that phase runs first and the load of a new row and the stores are
-                // issued behind it: they then have most of a step before the next such wait (measured: 0.88 ->
-                // 0.67 ms for 65536 fp16 rows; the other modes, whose reloads sit elsewhere, measured slower in
-                // this order and keep the usual one).  The explicit waits in phase A stay valid: the operations
-                // younger than the awaited load only become more.
-                if (it >= 1 && it <= n_my) phase_b(lb, lb_other);
-                if (it < n_my) ring_load(it + 2, bb);  // slot of row it-1, consumed in the previous iteration
-                if (it >= 2) phase_c();
-                if (it < n_my) phase_a();
+                if (it >= 4)
+                    asm volatile("s_waitcnt vmcnt(%5)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16), "n"(kPending) : "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(v), "=&v"(v1) : "v"(rd_addr), "n"(ro), "n"(ro + 16) : "memory");
             }
-            __syncthreads();
+            // refills the slot of row it-1, consumed in the previous iteration (kTwoBuf: the slot just read)
+            ring_load(it + 2, kTwoBuf ? ba : bb);
+            Raw8 raw;
+            raw.lo = make_uint4(v.x, v.y, v.z, v.w);
+            if (kLoads == 2) raw.hi = make_uint4(v1.x, v1.y, v1.z, v1.w);
+            float u[8];
+            unpack8(raw, u, (const T *)nullptr);
+            if (!kInverse) reg_layer_first<0>(u, cn[0]);
+            layers_a(u);
+            lds_write_n(la, an, u);
         };
-        typedef std::integral_constant<int, 0> I0;
-        typedef std::integral_constant<int, 1> I1;
-        typedef std::integral_constant<int, 2> I2;
-        const int end = n_my + 2;
-        if (kTwoBuf) {
-            for (int it = 0; it < end; it += 2) {  // (A, B, C) buffers: (0, 1, 0) -> (1, 0, 1) -> ...
-                step(I0{}, I1{}, I0{}, it);
-                if (it + 1 < end) step(I1{}, I0{}, I1{}, it + 1);
+        auto phase_c = [&]() {  // C(it-2)
+            float u[8];
+            lds_read_n(lc, an, u);
+            if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
+            layers_c(u);
+            if (kScaleLds) {
+                float dl[8];
+                lds_read_n(dtab, an, dl);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) u[r] *= dl[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) u[r] *= d[r];
             }
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
+        };
+        // The phases touch different buffers, so any order is correct as long as C precedes A where the two
+        // share a buffer.  n = 4096: C, B, A measured 1-2 % faster than the other orders on all modes.
+        // n = 8192 (always two buffers): layer 13 makes phase C of the forward modes read the other half's
+        // buffer, which that half's phase A is about to overwrite, hence the extra barrier.  These kernels also
+        // spill a few coefficients, and the compiler waits for their reloads with vmcnt(0), which waits for every
+        // load and store the wave issued before; which order keeps those waits away from fresh loads depends on
+        // where the reloads fall, and was measured per mode (65536 rows: fp16 forward 0.66 -> 0.63 ms and
+        // inverse 0.69 -> 0.60 ms with B first, fused quantiser 0.52 -> 0.47 ms with C first).
+        if (!kBFirst) {
+            if (it >= 2) phase_c();
+            if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
         } else {
-            for (int it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
-                step(I0{}, I2{}, I1{}, it);
-                if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
-                if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
-            }
+            if (it >= 1 && it <= n_my) phase_b(lb, lb_other);
+            if (it >= 2) phase_c();
+        }
+        if (kWide && !kInverse) __syncthreads();  // the other half's reads in phase C are complete
+        if (it < n_my) phase_a();
+        __syncthreads();
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    typedef std::integral_constant<int, 2> I2;
+    const int end = n_my + 2;
+    if (kTwoBuf) {
+        for (int it = 0; it < end; it += 2) {  // (A, B, C) buffers: (0, 1, 0) -> (1, 0, 1) -> ...
+            step(I0{}, I1{}, I0{}, it);
+            if (it + 1 < end) step(I1{}, I0{}, I1{}, it + 1);
         }
     } else {
-        // ---- 32-bit rows of n = 8192: two rows prefetched in registers, output scales kept in LDS ----
-        float *dtab = lds_raw + half * kLdsRow;
-        {
-            const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
-            float d[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
-            lds_write_n(dtab, an, d);
-        }
-        __syncthreads();
-        // `raw` holds row `it` on entry and is refilled with row it + 2 (unconditionally: the last two
-        // iterations re-read the last row).
-        auto iteration = [&](int it, Raw8 &raw) {
-            float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
-            float *lc = lds + (bc * kHalves + half) * kLdsRow;
-            const float *lb_other = lds + (bb * kHalves + (half ^ 1)) * kLdsRow;  // kWide only
-            const float *lc_other = lds + (bc * kHalves + (half ^ 1)) * kLdsRow;
-            if (it < n_my) {  // A(it)
-                float u[8];
-                unpack8(raw, u, (const T *)nullptr);
-                if (!kInverse) reg_layer_first<0>(u, cn[0]);
-                {
-                    __builtin_amdgcn_sched_barrier(0);
-                    uint32_t off = off_n * (uint32_t)sizeof(T);
-                    asm volatile("" : "+v"(off));
-                    const int nxt = (it + 2 < n_my) ? it + 2 : n_my - 1;
-                    const char *rowp = (const char *)(in + (row_first + nxt * row_step) * A.ld_in);
-                    raw = load8((const T *)(rowp + off));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                layers_a(u);
-                lds_write_n(la, an, u);
-            }
-            if (it >= 2) {  // C(it-2)
-                float u[8];
-                lds_read_n(lc, an, u);
-                if (kWide && !kInverse) cross_layer<false>(lc_other, an, cw, u);  // layer 13
-                layers_c(u);
-                {
-                    float d[8];
-                    lds_read_n(dtab, an, d);
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) u[r] *= d[r];
-                }
-                finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
-            }
-            if (it >= 1 && it <= n_my) phase_b(lb, lb_other);  // B(it-1)
-            __syncthreads();
-            rotate_buffers();
-        };
-        Raw8 raw_even = load8(in + row_first * A.ld_in + off_n);
-        Raw8 raw_odd = raw_even;
-        if (n_my > 1) raw_odd = load8(in + (row_first + row_step) * A.ld_in + off_n);
-        for (int it = 0; it < n_my + 2; it += 2) {
-            iteration(it, raw_even);
-            if (it + 1 < n_my + 2) iteration(it + 1, raw_odd);
+        for (int it = 0; it < end; it += 3) {  // (A, B, C) buffers: (0, 2, 1) -> (1, 0, 2) -> (2, 1, 0) -> ...
+            step(I0{}, I2{}, I1{}, it);
+            if (it + 1 < end) step(I1{}, I0{}, I2{}, it + 1);
+            if (it + 2 < end) step(I2{}, I1{}, I0{}, it + 2);
         }
     }
     flush_bins();

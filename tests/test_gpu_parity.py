@@ -513,3 +513,23 @@ def test_mid_sizes_several_heads_backward(n, heads, rows, dtype, pad):
     gu.check_dtheta(dth, rdth, np.maximum(ab, floor), what=f"mid heads n={n} H={heads} T={rows} {dtype}")
     _, dth_only = gu.run_bwd(x, dy, th, n, heads, dtype, want_dx=False, pad=pad)
     np.testing.assert_array_equal(dth, dth_only)
+
+
+# ---- float32 rows over many pipeline steps (several rows per workgroup, every element compared) ----------
+@pytest.mark.parametrize("n,heads,rows", [(4096, 1, 5200), (8192, 1, 1500), (1024, 1, 20000 + 3), (2048, 2, 2600)])
+def test_float32_rows_many_steps(n, heads, rows):
+    dtype = "f32"
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=300 + n)
+    ref = _ref_fwd(x, th, n, heads, dtype)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype), ref, dtype, f"f32 fwd n={n} T={rows}")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, pad=12), ref, dtype, f"f32 fwd padded n={n}")
+    xi = gu.run_transform(x, th, n, heads, dtype, inverse=True)
+    gu.check_rotated(xi, oracle.inverse(synth.to_f64(x, dtype), th, n, heads), dtype, f"f32 inv n={n} T={rows}")
+    for bits, group, sd in [(4, 128, "f16"), (2, 64, "f32")]:
+        codes, scales = gu.run_fwd_quant(x, th, n, heads, dtype, bits, group, sd)
+        gu.check_fused_codes(codes, scales, ref, bits, group, sd, dtype, f"f32 quant n={n} T={rows}")
+        yq, hist = gu.run_fwd_fakequant(x, th, n, heads, dtype, bits, group, sd)
+        c = oracle.unpack_codes(codes, bits)
+        want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+        np.testing.assert_array_equal(yq.view(np.uint32), want.view(np.uint32))
+        np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits))
