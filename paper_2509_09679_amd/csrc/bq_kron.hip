@@ -239,7 +239,8 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 //     sub-rows; Q1 (zero-padded) stays in registers as the A operands (lane l: output 16 i + l % 16, input
 //     4 s + l / 16).  Results (lane l, register r: output 16 i + 4 (l / 16) + r, column l % 16) overwrite
 //     the wave's own columns of the tile.
-// Vector and matrix work of different rows overlap on the same SIMDs.  Three tiles rotate.  The two factors
+// Three tiles rotate.  (Measured with timing-only builds: the float32 matrix instructions' time adds to the vector
+// work of the other groups instead of hiding behind it, so a row costs about the sum of the two.)  The two factors
 // act on different indices and commute, so the inverse runs the transposed butterfly first and then mixes
 // with Q1^T: same structure.
 constexpr int kFusedD2 = 128;
@@ -292,18 +293,24 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
 #pragma unroll
         for (int r = 0; r < 8; ++r) d[r] = A.fd[idx + r];
         const T *in = (const T *)A.in + (size_t)sub * kFusedD2 + idx;
-        // Two rows are in flight from memory.  This group only loads; the rows are stored by the mix group:
-        // memory operations of a wave retire in order, so a wave that both stores and prefetches ends up
-        // waiting for its stores to be acknowledged before it may use a prefetched row.
-        Raw8 raw = {}, raw_next = {};
-        if (live && mine > 0) raw = load8(in + (int64_t)blockIdx.x * width);
-        if (live && mine > 1) raw_next = load8(in + ((int64_t)blockIdx.x + gridDim.x) * width);
+        // kAhead rows are in flight from memory: a compute unit runs one workgroup, and a row is only 256 bytes
+        // per sub-row, so it takes several to cover the latency (four instead of two: d1 = 8 and 16 run 20 % and
+        // 16 % faster; d1 = 40, which is bound by arithmetic, is unchanged; six measured slower again).
+        // This group only loads; the rows are stored by the store group: memory operations of a wave retire
+        // in order, so a wave that both stores and prefetches ends up waiting for its stores to be
+        // acknowledged before it may use a prefetched row.
+        constexpr int kAhead = 4;
+        Raw8 raw[kAhead] = {};
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a)
+            if (live && mine > a) raw[a] = load8(in + ((int64_t)blockIdx.x + a * (int64_t)gridDim.x) * width);
         for (int64_t it = 0; it < mine + 2; ++it) {
             if (live && it < mine) {  // transform row it (its tile last held row it-3, stored one step ago)
                 float u[8];
-                unpack8(raw, u, (const T *)nullptr);
-                raw = raw_next;
-                if (it + 2 < mine) raw_next = load8(in + (blockIdx.x + (it + 2) * gridDim.x) * width);
+                unpack8(raw[0], u, (const T *)nullptr);
+#pragma unroll
+                for (int a = 0; a + 1 < kAhead; ++a) raw[a] = raw[a + 1];
+                if (it + kAhead < mine) raw[kAhead - 1] = load8(in + (blockIdx.x + (it + kAhead) * gridDim.x) * width);
                 if (!kSlow)
                     fast_small<7, kInverse>(u, c, d);
                 else
