@@ -416,7 +416,9 @@ def test_small_transforms_backward_flagged_plan():
 # ---- quantiser groups of more than 128 channels, up to one scale per row (per-token), n = 256 .. 8192 --------
 BIG_GROUPS = [(4096, 256, 19, "f16"), (4096, 512, 5, "bf16"), (4096, 1024, 33, "f32"), (4096, 4096, 300, "f16"),
               (8192, 512, 7, "bf16"), (8192, 2048, 3, "f16"), (8192, 8192, 130, "f16"), (512, 256, 8 * 5 + 3, "f16"),
-              (512, 512, 8 * 40, "bf16"), (2048, 2048, 2 * 9 + 1, "f32"), (1024, 512, 4 * 7, "f16")]
+              (512, 512, 8 * 40, "bf16"), (2048, 2048, 2 * 9 + 1, "f32"), (1024, 512, 4 * 7, "f16"),
+              # several rows per workgroup (the row buffers are reused)
+              (8192, 2048, 1500, "f16"), (4096, 4096, 5100, "f32"), (8192, 8192, 1100, "f32"), (1024, 1024, 4 * 5000, "f16")]
 
 
 @pytest.mark.parametrize("n,group,rows,dtype", BIG_GROUPS)
