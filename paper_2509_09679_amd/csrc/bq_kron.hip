@@ -233,14 +233,18 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 //   * the store group (two waves) stores row t-2: 16-byte pieces read back from that row's tile, one rounding
 //     to the row type;
 //   * the mix group (four waves, one per SIMD) takes row t-1: Y = Q1 Z is a dense product, done on the matrix
-//     cores in float32 (v_mfma_f32_16x16x4_f32: no rounding of Z or Q1, float32 accumulation).  A wave owns two
+//     cores.  float32 rows: in float32 (v_mfma_f32_16x16x4_f32: no rounding of Z or Q1, float32 accumulation),
+//     as described next.  16-bit rows: as three bfloat16 products of two-way splits of both factors with
+//     float32 accumulation (v_mfma_f32_16x16x16_bf16; the tile then holds each value of Z as a (hi, lo) pair of
+//     bfloat16 in one word), which keeps the error forty times under the bound for such rows at less than half
+//     the matrix cycles: 65536 rows of 5120 went from 0.49 to 0.36 ms.  A wave owns two
 //     blocks of 16 columns; per step of four input sub-rows it reads one B operand per block from the tile
 //     (lane l: sub-row 4 s + l / 16, column l % 16 of the block) and issues one MFMA per block of 16 output
 //     sub-rows; Q1 (zero-padded) stays in registers as the A operands (lane l: output 16 i + l % 16, input
 //     4 s + l / 16).  Results (lane l, register r: output 16 i + 4 (l / 16) + r, column l % 16) overwrite
 //     the wave's own columns of the tile.
-// Three tiles rotate.  (Measured with timing-only builds: the float32 matrix instructions' time adds to the vector
-// work of the other groups instead of hiding behind it, so a row costs about the sum of the two.)  The two factors
+// Three tiles rotate.  (Measured with timing-only builds: the matrix instructions' time adds to the vector
+// work of the waves on the same SIMD instead of hiding behind it, so a row costs about the sum of the two.)  The two factors
 // act on different indices and commute, so the inverse runs the transposed butterfly first and then mixes
 // with Q1^T: same structure.
 constexpr int kFusedD2 = 128;
@@ -264,6 +268,24 @@ struct FusedArgs {
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+
+// Two-way bfloat16 split of float32 values for the matrix cores: v = hi + lo + e with hi = v rounded to
+// bfloat16 (8 significant bits), lo = (v - hi) rounded to bfloat16 (the difference is exact), |e| <= 2^-16 |v|.
+// bfloat16 has float32's exponent range, so no scaling is needed.  Four values make one operand of
+// v_mfma_f32_16x16x16_bf16 (two registers).
+__device__ __forceinline__ uint32_t bf16_bits_of(float v) { return (__float_as_uint(v) + 0x8000u) & 0xFFFF0000u; }
+__device__ __forceinline__ void split4_bf16(const float (&v)[4], v4s *hi, v4s *lo)
+{
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        h[j] = bf16_bits_of(v[j]);
+        l[j] = bf16_bits_of(v[j] - __uint_as_float(h[j]));
+    }
+    *hi = __builtin_bit_cast(v4s, make_uint2((h[0] >> 16) | h[1], (h[2] >> 16) | h[3]));
+    *lo = __builtin_bit_cast(v4s, make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]));
+}
 
 // KS: steps of four input sub-rows (d1 <= 4 KS; inputs past d1 carry zero weights and re-read the last
 // sub-row), IT = ceil(KS / 4) blocks of 16 output sub-rows.  kSlow: the variant for plans whose scale-deferred tables
@@ -304,36 +326,66 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
 #pragma unroll
         for (int a = 0; a < kAhead; ++a)
             if (live && mine > a) raw[a] = load8(in + ((int64_t)blockIdx.x + a * (int64_t)gridDim.x) * width);
-        for (int64_t it = 0; it < mine + 2; ++it) {
+        // one step: row `it` out of `slot`, which is then refilled with row it + kAhead (the loop below is unrolled
+        // over the slots, so that no row moves between registers)
+        auto row_step = [&](int64_t it, Raw8 &slot) {
             if (live && it < mine) {  // transform row it (its tile last held row it-3, stored one step ago)
                 float u[8];
-                unpack8(raw[0], u, (const T *)nullptr);
-#pragma unroll
-                for (int a = 0; a + 1 < kAhead; ++a) raw[a] = raw[a + 1];
-                if (it + kAhead < mine) raw[kAhead - 1] = load8(in + (blockIdx.x + (it + kAhead) * gridDim.x) * width);
+                unpack8(slot, u, (const T *)nullptr);
+                if (it + kAhead < mine) slot = load8(in + (blockIdx.x + (it + kAhead) * gridDim.x) * width);
                 if (!kSlow)
                     fast_small<7, kInverse>(u, c, d);
                 else
                     slow_small<7, kInverse>(u, A.cs, idx);
+                if (sizeof(T) == 2) {
+                    // 16-bit rows: the tile takes each value as its two-way bfloat16 split, hi (rounded) in the upper
+                    // half of the word and lo (truncated: |v - hi - lo| < 2^-16 |v| either way) in the lower, ready
+                    // to be packed into matrix operands by the mix group
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        const uint32_t h = bf16_bits_of(u[r]);
+                        const float rest = u[r] - __uint_as_float(h);
+                        u[r] = __uint_as_float(__builtin_amdgcn_perm(h, __float_as_uint(rest), 0x07060302u));
+                    }
+                }
                 float4 *dst = (float4 *)&tile[(int)(it % 3) * tile_floats + sub * kTileRow + idx];
                 dst[0] = make_float4(u[0], u[1], u[2], u[3]);
                 dst[1] = make_float4(u[4], u[5], u[6], u[7]);
             }
             __syncthreads();
+        };
+        for (int64_t it = 0; it < mine + 2; it += kAhead) {
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a)
+                if (it + a < mine + 2) row_step(it + a, raw[a]);
         }
     } else if (tid >= A.bfly_threads + kMixWaves * 64) {
         // ---- store group: row it-2, 16-byte pieces of 8 consecutive elements, one rounding to the row type ------
         const int stid = tid - A.bfly_threads - kMixWaves * 64;
+        // pieces per lane (d1 <= 4 KS sub-rows of 16 pieces over the group's lanes): all of a row's tile reads are
+        // issued before the first conversion, so their latency is paid once per row
+        constexpr int kPieces = (4 * KS * 16 + kStoreWaves * 64 - 1) / (kStoreWaves * 64);
         for (int64_t it = 0; it < mine + 2; ++it) {
             if (it >= 2) {
                 const float *y_tile = tile + (int)((it - 2) % 3) * tile_floats;
                 T *out_row = (T *)A.out + (blockIdx.x + (it - 2) * gridDim.x) * width;
-                for (int piece = stid; piece < d1 * 16; piece += kStoreWaves * 64) {
-                    const int sub = piece >> 4, col = (piece & 15) * 8;
-                    const float4 *src = (const float4 *)&y_tile[sub * kTileRow + col];
-                    const float4 a = src[0], b = src[1];
-                    const float y[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-                    store8(out_row + sub * kFusedD2 + col, y);
+                float4 a[kPieces], b[kPieces];
+#pragma unroll
+                for (int p = 0; p < kPieces; ++p) {
+                    const int piece = stid + p * kStoreWaves * 64;
+                    if (piece < d1 * 16) {
+                        const float4 *src = (const float4 *)&y_tile[(piece >> 4) * kTileRow + (piece & 15) * 8];
+                        a[p] = src[0];
+                        b[p] = src[1];
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < kPieces; ++p) {
+                    const int piece = stid + p * kStoreWaves * 64;
+                    if (piece < d1 * 16) {
+                        const float y[8] = {a[p].x, a[p].y, a[p].z, a[p].w, b[p].x, b[p].y, b[p].z, b[p].w};
+                        store8(out_row + (piece >> 4) * kFusedD2 + (piece & 15) * 8, y);
+                    }
                 }
             }
             __syncthreads();
@@ -341,6 +393,86 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
     } else {
         // ---- mix group ---------------------------------------------------------------------------------------
         const int mw = (tid - A.bfly_threads) >> 6;  // 0 .. kMixWaves-1: column blocks 2 mw and 2 mw + 1
+        if constexpr (sizeof(T) == 2) {
+            // 16-bit rows: the product runs on the bfloat16 matrix instruction with two-way splits of both
+            // factors, Y = Q_hi Z_hi + Q_hi Z_lo + Q_lo Z_hi accumulated in float32 (relative error of a term
+            // below 3 * 2^-16 = 4.6e-5, forty times under the bound for such rows), because the float32 matrix
+            // instruction does not overlap the other groups' vector work and costs four times the cycles.
+            // Contraction index of lane l, element j of an operand, step s: k = 16 s + l / 16 + 4 j (the same
+            // map in both operands; consecutive k over the lane groups keeps the tile reads two per bank).
+            v4s qh[IT][IT], ql[IT][IT];
+#pragma unroll
+            for (int t = 0; t < IT; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < IT; ++s2) {
+                    float w[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int i = 16 * t + (lane & 15), k = 16 * s2 + (lane >> 4) + 4 * j;
+                        w[j] = (i < d1 && k < d1) ? (kInverse ? A.q[k * d1 + i] : A.q[i * d1 + k]) : 0.0f;
+                    }
+                    split4_bf16(w, &qh[t][s2], &ql[t][s2]);
+                }
+            for (int64_t it = 0; it < mine + 2; ++it) {
+                if (it >= 1 && it <= mine) {  // mix row it-1 in place
+                    float *t = tile + (int)((it - 1) % 3) * tile_floats + 32 * mw + (lane & 15);
+                    v4f acc[2][IT];
+#pragma unroll
+                    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                        for (int i = 0; i < IT; ++i) acc[jb][i] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+                    uint32_t z[IT][2][4];  // all of the row's operand words (hi | lo) first, so that the reads overlap
+#pragma unroll
+                    for (int s2 = 0; s2 < IT; ++s2)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            int k = 16 * s2 + (lane >> 4) + 4 * j;
+                            k = k < d1 ? k : d1 - 1;  // weight zero
+                            z[s2][0][j] = __float_as_uint(t[k * kTileRow]);
+                            z[s2][1][j] = __float_as_uint(t[k * kTileRow + 16]);
+                        }
+#pragma unroll
+                    for (int s2 = 0; s2 < IT; ++s2) {
+                        v4s zh[2], zl[2];
+#pragma unroll
+                        for (int jb = 0; jb < 2; ++jb) {
+                            const uint32_t *w = z[s2][jb];
+                            zh[jb] = __builtin_bit_cast(v4s, make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u),
+                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x07060302u)));
+                            zl[jb] = __builtin_bit_cast(v4s, make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x05040100u),
+                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x05040100u)));
+                        }
+                        // the small products first; six independent accumulators between two uses of the same one
+#pragma unroll
+                        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                            for (int i = 0; i < IT; ++i)
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ql[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
+#pragma unroll
+                        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                            for (int i = 0; i < IT; ++i)
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qh[i][s2], zl[jb], acc[jb][i], 0, 0, 0);
+#pragma unroll
+                        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                            for (int i = 0; i < IT; ++i)
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qh[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                        for (int i = 0; i < IT; ++i)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const int o = 16 * i + 4 * (lane >> 4) + r;
+                                if (o < d1) t[o * kTileRow + 16 * jb] = acc[jb][i][r];
+                            }
+                }
+                __syncthreads();
+            }
+            return;
+        }
         // A operands: the weight of input sub-row k in output sub-row i is Q1[i][k] (forward) or Q1[k][i]
         float qa[IT][KS];
 #pragma unroll

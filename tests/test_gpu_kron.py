@@ -166,3 +166,35 @@ def test_kron_sweep(i, d1, d2, rows, dtype):
     _check(_run(x, q1, theta, d1, d2, dtype), kron.kron_forward(x64, q64, theta, d2), dtype, f"kron sweep {i} fwd", fused)
     _check(_run(x, q1, theta, d1, d2, dtype, inverse=True), kron.kron_inverse(x64, q64, theta, d2), dtype,
            f"kron sweep {i} inv", fused)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d1", [40, 24, 9])
+def test_kron_16bit_rows_mixing_error_is_far_below_the_output_rounding(d1, dtype):
+    # 16-bit rows mix on the bfloat16 matrix instruction with two-way splits of both factors: every product
+    # Q[i][k] z[k][j] carries a relative error below 3 * 2^-16, so an output is off by at most
+    # 3 * 2^-16 * sum_k |Q[i][k]| |z[k][j]| <= 3 * 2^-16 * ||z[:, j]||_2 = 3 * 2^-16 * ||y[:, j]||_2 (rows of Q1 have
+    # norm one, and Q1 preserves the norm of a column).  Measured against the oracle BEFORE the output rounding:
+    # the distance from the exact value may exceed half a unit in the last place of the row type (what a correctly
+    # rounded result has) by that much, plus the float32 arithmetic's own 1e-5 of the row's rms.  Inputs have
+    # outlier channels (x100), whose products dominate a row; several rows per workgroup.
+    d2, rows = 128, 700
+    rng = np.random.default_rng(55 + d1)
+    theta = rng.uniform(-math.pi, math.pi, size=(1, 7, 64)).astype(np.float32)
+    q1 = kron.cayley((0.4 * rng.standard_normal(d1 * (d1 - 1) // 2)).astype(np.float32), d1).astype(np.float32)
+    x, _, _ = synth.small_case(d2, rows * d1, dtype, seed=9 + d1)
+    x = x.reshape(rows, d1 * d2)
+    x64 = synth.to_f64(x, dtype)
+    bits = 11 if dtype == "f16" else 8
+    for inverse in (False, True):
+        ref = (kron.kron_inverse if inverse else kron.kron_forward)(x64, q1.astype(np.float64), theta, d2)
+        got = synth.to_f64(_run(x, q1, theta, d1, d2, dtype, inverse=inverse), dtype)
+        _, e = np.frexp(gu.round_to_storage(ref, dtype))  # |v| = m * 2^e, m in [0.5, 1): half a unit = 2^(e - 1 - bits)
+        half_ulp = np.ldexp(1.0, e - 1 - bits)
+        col = np.sqrt((ref.reshape(rows, d1, d2) ** 2).sum(axis=1, keepdims=True))  # ||y[:, j]||_2 per row
+        bound = (3 * 2.0 ** -16 * np.broadcast_to(col, (rows, d1, d2))).reshape(rows, d1 * d2)
+        rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        excess = np.abs(got - ref) - half_ulp
+        assert np.all(excess <= bound + 1e-5 * rms), f"d1={d1} {dtype} inv={inverse}: {np.max(excess / (bound + 1e-5 * rms)):.3f}"
+        # and the typical error is far smaller than the bound: all but a few elements in 10^4 within a third of it
+        assert np.mean(excess > bound / 3 + 1e-5 * rms) < 1e-3
