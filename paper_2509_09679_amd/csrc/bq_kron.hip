@@ -235,7 +235,7 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 //   * the mix group (four waves, one per SIMD) takes row t-1: Y = Q1 Z is a dense product, done on the matrix
 //     cores.  float32 rows: in float32 (v_mfma_f32_16x16x4_f32: no rounding of Z or Q1, float32 accumulation),
 //     as described next.  16-bit rows: as three bfloat16 products of two-way splits of both factors with
-//     float32 accumulation (v_mfma_f32_16x16x16_bf16; the tile then holds each value of Z as a (hi, lo) pair of
+//     float32 accumulation (v_mfma_f32_16x16x32_bf16; the tile then holds each value of Z as a (hi, lo) pair of
 //     bfloat16 in one word), which keeps the error forty times under the bound for such rows at less than half
 //     the matrix cycles: 65536 rows of 5120 went from 0.49 to 0.36 ms.  A wave owns two
 //     blocks of 16 columns; per step of four input sub-rows it reads one B operand per block from the tile
@@ -268,23 +268,23 @@ struct FusedArgs {
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __bf16 v8b __attribute__((ext_vector_type(8)));
 
 // Two-way bfloat16 split of float32 values for the matrix cores: v = hi + lo + e with hi = v rounded to
 // bfloat16 (8 significant bits), lo = (v - hi) rounded to bfloat16 (the difference is exact), |e| <= 2^-16 |v|.
-// bfloat16 has float32's exponent range, so no scaling is needed.  Four values make one operand of
-// v_mfma_f32_16x16x16_bf16 (two registers).
+// bfloat16 has float32's exponent range, so no scaling is needed.  Eight values make one operand of
+// v_mfma_f32_16x16x32_bf16 (four registers).
 __device__ __forceinline__ uint32_t bf16_bits_of(float v) { return (__float_as_uint(v) + 0x8000u) & 0xFFFF0000u; }
-__device__ __forceinline__ void split4_bf16(const float (&v)[4], v4s *hi, v4s *lo)
+__device__ __forceinline__ void split8_bf16(const float (&v)[8], v8b *hi, v8b *lo)
 {
-    uint32_t h[4], l[4];
+    uint32_t h[8], l[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {
         h[j] = bf16_bits_of(v[j]);
         l[j] = bf16_bits_of(v[j] - __uint_as_float(h[j]));
     }
-    *hi = __builtin_bit_cast(v4s, make_uint2((h[0] >> 16) | h[1], (h[2] >> 16) | h[3]));
-    *lo = __builtin_bit_cast(v4s, make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]));
+    *hi = __builtin_bit_cast(v8b, make_uint4((h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]));
+    *lo = __builtin_bit_cast(v8b, make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]));
 }
 
 // KS: steps of four input sub-rows (d1 <= 4 KS; inputs past d1 carry zero weights and re-read the last
@@ -398,20 +398,21 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
             // factors, Y = Q_hi Z_hi + Q_hi Z_lo + Q_lo Z_hi accumulated in float32 (relative error of a term
             // below 3 * 2^-16 = 4.6e-5, forty times under the bound for such rows), because the float32 matrix
             // instruction does not overlap the other groups' vector work and costs four times the cycles.
-            // Contraction index of lane l, element j of an operand, step s: k = 16 s + l / 16 + 4 j (the same
+            // Contraction index of lane l, element j of an operand, step s: k = 32 s + l / 16 + 4 j (the same
             // map in both operands; consecutive k over the lane groups keeps the tile reads two per bank).
-            v4s qh[IT][IT], ql[IT][IT];
+            constexpr int SK = (4 * KS + 31) / 32;  // steps of 32 input sub-rows
+            v8b qh[IT][SK], ql[IT][SK];
 #pragma unroll
             for (int t = 0; t < IT; ++t)
 #pragma unroll
-                for (int s2 = 0; s2 < IT; ++s2) {
-                    float w[4];
+                for (int s2 = 0; s2 < SK; ++s2) {
+                    float w[8];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int i = 16 * t + (lane & 15), k = 16 * s2 + (lane >> 4) + 4 * j;
+                    for (int j = 0; j < 8; ++j) {
+                        const int i = 16 * t + (lane & 15), k = 32 * s2 + (lane >> 4) + 4 * j;
                         w[j] = (i < d1 && k < d1) ? (kInverse ? A.q[k * d1 + i] : A.q[i * d1 + k]) : 0.0f;
                     }
-                    split4_bf16(w, &qh[t][s2], &ql[t][s2]);
+                    split8_bf16(w, &qh[t][s2], &ql[t][s2]);
                 }
             for (int64_t it = 0; it < mine + 2; ++it) {
                 if (it >= 1 && it <= mine) {  // mix row it-1 in place
@@ -421,43 +422,45 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
                     for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
                         for (int i = 0; i < IT; ++i) acc[jb][i] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-                    uint32_t z[IT][2][4];  // all of the row's operand words (hi | lo) first, so that the reads overlap
 #pragma unroll
-                    for (int s2 = 0; s2 < IT; ++s2)
+                    for (int s2 = 0; s2 < SK; ++s2) {
+                        uint32_t z[2][8];  // operand words (hi | lo)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            int k = 16 * s2 + (lane >> 4) + 4 * j;
+                        for (int j = 0; j < 8; ++j) {
+                            int k = 32 * s2 + (lane >> 4) + 4 * j;
                             k = k < d1 ? k : d1 - 1;  // weight zero
-                            z[s2][0][j] = __float_as_uint(t[k * kTileRow]);
-                            z[s2][1][j] = __float_as_uint(t[k * kTileRow + 16]);
+                            z[0][j] = __float_as_uint(t[k * kTileRow]);
+                            z[1][j] = __float_as_uint(t[k * kTileRow + 16]);
                         }
-#pragma unroll
-                    for (int s2 = 0; s2 < IT; ++s2) {
-                        v4s zh[2], zl[2];
+                        v8b zh[2], zl[2];
 #pragma unroll
                         for (int jb = 0; jb < 2; ++jb) {
-                            const uint32_t *w = z[s2][jb];
-                            zh[jb] = __builtin_bit_cast(v4s, make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u),
-                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x07060302u)));
-                            zl[jb] = __builtin_bit_cast(v4s, make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x05040100u),
-                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x05040100u)));
+                            const uint32_t *w = z[jb];
+                            zh[jb] = __builtin_bit_cast(v8b, make_uint4(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u),
+                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x07060302u),
+                                                                        __builtin_amdgcn_perm(w[5], w[4], 0x07060302u),
+                                                                        __builtin_amdgcn_perm(w[7], w[6], 0x07060302u)));
+                            zl[jb] = __builtin_bit_cast(v8b, make_uint4(__builtin_amdgcn_perm(w[1], w[0], 0x05040100u),
+                                                                        __builtin_amdgcn_perm(w[3], w[2], 0x05040100u),
+                                                                        __builtin_amdgcn_perm(w[5], w[4], 0x05040100u),
+                                                                        __builtin_amdgcn_perm(w[7], w[6], 0x05040100u)));
                         }
-                        // the small products first; six independent accumulators between two uses of the same one
+                        // the small products first; 2 IT independent accumulators between two uses of the same one
 #pragma unroll
                         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
                             for (int i = 0; i < IT; ++i)
-                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ql[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
 #pragma unroll
                         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
                             for (int i = 0; i < IT; ++i)
-                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qh[i][s2], zl[jb], acc[jb][i], 0, 0, 0);
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[i][s2], zl[jb], acc[jb][i], 0, 0, 0);
 #pragma unroll
                         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
                             for (int i = 0; i < IT; ++i)
-                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qh[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
+                                acc[jb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[i][s2], zh[jb], acc[jb][i], 0, 0, 0);
                     }
 #pragma unroll
                     for (int jb = 0; jb < 2; ++jb)
