@@ -76,6 +76,9 @@ CASES = [
     (64, 128, 9, "bf16"),
     (37, 128, 21, "f16"),
     (2, 128, 1, "f32"),
+    (8, 128, 3000, "f16"),   # d1 <= 8: two workgroups per compute unit, several rows each
+    (4, 128, 5000, "bf16"),
+    (40, 128, 1400, "f32"),  # several rows per workgroup on the float32 matrix path
 ]
 
 
