@@ -11,6 +11,8 @@
 // takes Q1 from LDS, where the workgroup put it transposed and zero-padded: every lane reads the same four
 // coefficients with one 16-byte LDS read (a broadcast), then does eight FMAs.  In place is safe: a thread
 // reads all its inputs before it writes, and no other thread touches its columns.
+#include <type_traits>
+
 #include "bq_cascade.h"
 
 namespace bq {
@@ -234,9 +236,9 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 //     to the row type;
 //   * the mix group (four waves, one per SIMD) takes row t-1: Y = Q1 Z is a dense product, done on the matrix
 //     cores.  float32 rows: in float32 (v_mfma_f32_16x16x4_f32: no rounding of Z or Q1, float32 accumulation),
-//     as described next.  16-bit rows: as three bfloat16 products of two-way splits of both factors with
+//     as described next.  binary16 rows: as three bfloat16 products of two-way splits of both factors with
 //     float32 accumulation (v_mfma_f32_16x16x32_bf16; the tile then holds each value of Z as a (hi, lo) pair of
-//     bfloat16 in one word), which keeps the error forty times under the bound for such rows at less than half
+//     bfloat16 in one word), which keeps the error far under the bound for such rows at less than half
 //     the matrix cycles: 65536 rows of 5120 went from 0.49 to 0.36 ms.  A wave owns two
 //     blocks of 16 columns; per step of four input sub-rows it reads one B operand per block from the tile
 //     (lane l: sub-row 4 s + l / 16, column l % 16 of the block) and issues one MFMA per block of 16 output
@@ -254,6 +256,13 @@ constexpr int kFusedMaxD1 = 40;  // 40 sub-rows x 16 lanes + six more waves = 10
 constexpr int kMixWaves = 4;
 constexpr int kStoreWaves = 2;
 constexpr int kFusedMaxThreads = kFusedMaxD1 * 16 + (kMixWaves + kStoreWaves) * 64;
+
+// Rows of binary16 mix on the bfloat16 matrix instruction (two-way splits, three products): the error this adds, up
+// to 1.5 * 2^-16 of sum_k |Q[i][k] z[k][j]|, is a fifth of such a row's own rounding step.  For bfloat16 rows it
+// would not be small against theirs (2^-9 of the value, which the 2e-3 bound barely covers), and for float32 rows
+// it is far too much: both keep the float32 matrix instruction.
+template <typename T>
+constexpr bool kSplitMix = std::is_same<T, __half>::value;
 
 struct FusedArgs {
     const void *in;
@@ -337,8 +346,8 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
                     fast_small<7, kInverse>(u, c, d);
                 else
                     slow_small<7, kInverse>(u, A.cs, idx);
-                if (sizeof(T) == 2) {
-                    // 16-bit rows: the tile takes each value as its two-way bfloat16 split, hi (rounded) in the upper
+                if (kSplitMix<T>) {
+                    // binary16 rows: the tile takes each value as its two-way bfloat16 split, hi (rounded) in the upper
                     // half of the word and lo (truncated: |v - hi - lo| < 2^-16 |v| either way) in the lower, ready
                     // to be packed into matrix operands by the mix group
 #pragma unroll
@@ -393,10 +402,10 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
     } else {
         // ---- mix group ---------------------------------------------------------------------------------------
         const int mw = (tid - A.bfly_threads) >> 6;  // 0 .. kMixWaves-1: column blocks 2 mw and 2 mw + 1
-        if constexpr (sizeof(T) == 2) {
-            // 16-bit rows: the product runs on the bfloat16 matrix instruction with two-way splits of both
+        if constexpr (kSplitMix<T>) {
+            // binary16 rows: the product runs on the bfloat16 matrix instruction with two-way splits of both
             // factors, Y = Q_hi Z_hi + Q_hi Z_lo + Q_lo Z_hi accumulated in float32 (relative error of a term
-            // below 3 * 2^-16 = 4.6e-5, forty times under the bound for such rows), because the float32 matrix
+            // below 3 * 2^-16 = 4.6e-5, a tenth of such a row's rounding step), because the float32 matrix
             // instruction does not overlap the other groups' vector work and costs four times the cycles.
             // Contraction index of lane l, element j of an operand, step s: k = 32 s + l / 16 + 4 j (the same
             // map in both operands; consecutive k over the lane groups keeps the tile reads two per bank).
