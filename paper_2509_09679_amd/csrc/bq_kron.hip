@@ -258,9 +258,9 @@ constexpr int kStoreWaves = 2;
 constexpr int kFusedMaxThreads = kFusedMaxD1 * 16 + (kMixWaves + kStoreWaves) * 64;
 
 // Rows of binary16 mix on the bfloat16 matrix instruction (two-way splits, three products): the error this adds, up
-// to 1.5 * 2^-16 of sum_k |Q[i][k] z[k][j]|, is a fifth of such a row's own rounding step.  For bfloat16 rows it
-// would not be small against theirs (2^-9 of the value, which the 2e-3 bound barely covers), and for float32 rows
-// it is far too much: both keep the float32 matrix instruction.
+// to 3 * 2^-16 of sum_k |Q[i][k] z[k][j]|, is a tenth of such a row's own rounding step (2^-11 of the value).  For
+// bfloat16 rows, whose rounding step (2^-8 of the value) already uses up their 2e-3 bound, nothing is to spare, and for
+// float32 rows it is far too much: both keep the float32 matrix instruction.
 template <typename T>
 constexpr bool kSplitMix = std::is_same<T, __half>::value;
 
