@@ -228,7 +228,8 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 }
 
 // ---- fused composite transform for d2 = 128 --------------------------------------------------------------
-// One workgroup per row at a time, three groups of waves working on different rows, one barrier per step:
+// One workgroup per pair of rows at a time, three groups of waves working on different pairs, one barrier per step
+// (per pair of rows; the text below says row t for the rows of step t):
 //   * the butterfly group (16 lanes per sub-row, 8 consecutive elements per lane) transforms row t at step t:
 //     the butterfly of every sub-row runs in registers (as in the small-transform kernels) and the float32
 //     results go to an LDS tile Z[d1][128];
@@ -245,7 +246,7 @@ static hipError_t launch_mix_t(const MixArgs &A, hipStream_t stream)
 //     sub-rows; Q1 (zero-padded) stays in registers as the A operands (lane l: output 16 i + l % 16, input
 //     4 s + l / 16).  Results (lane l, register r: output 16 i + 4 (l / 16) + r, column l % 16) overwrite
 //     the wave's own columns of the tile.
-// Three tiles rotate.  (Measured with timing-only builds: the matrix instructions' time adds to the vector
+// Three sets of tiles rotate.  (Measured with timing-only builds: the matrix instructions' time adds to the vector
 // work of the waves on the same SIMD instead of hiding behind it, so a row costs about the sum of the two.)  The two factors
 // act on different indices and commute, so the inverse runs the transposed butterfly first and then mixes
 // with Q1^T: same structure.
@@ -253,6 +254,7 @@ constexpr int kFusedD2 = 128;
 constexpr int kTileRow = kFusedD2 + 16;  // floats: sub-rows 16 banks apart, so a B-operand read (4 sub-rows x 16
                                          // columns) touches every bank twice, the minimum for 256 bytes
 constexpr int kFusedMaxD1 = 40;  // 40 sub-rows x 16 lanes + six more waves = 1024 threads
+constexpr int kStepRows = 2;  // rows between two barriers (per group); 3 * kStepRows tiles rotate
 constexpr int kMixWaves = 4;
 constexpr int kStoreWaves = 2;
 constexpr int kFusedMaxThreads = kFusedMaxD1 * 16 + (kMixWaves + kStoreWaves) * 64;
@@ -304,13 +306,17 @@ template <typename T, bool kInverse, int KS, bool kSlow>
 __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
 {
     constexpr int IT = (KS + 3) / 4;
-    extern __shared__ __align__(16) float tile[];  // 3 x [d1][kTileRow]
+    extern __shared__ __align__(16) float tile[];  // 3 kStepRows x [d1][kTileRow]
     if ((*A.fast_bad != 0) != kSlow) return;
     const int d1 = A.d1;
     const int tile_floats = d1 * kTileRow;
     const int tid = threadIdx.x, lane = tid & 63;
     const int64_t mine = A.rows > (int64_t)blockIdx.x ? (A.rows - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
     const int64_t width = (int64_t)d1 * kFusedD2;
+    // Step s: the butterfly group transforms rows kStepRows * s .. + kStepRows - 1 into the tiles of slot s % 3, the mix
+    // group takes the rows of step s - 1 and the store group those of step s - 2; one barrier per step.
+    const int64_t steps = (mine + kStepRows - 1) / kStepRows + 2;
+    auto tile_of = [&](int64_t step, int r) { return tile + ((int)(step % 3) * kStepRows + r) * tile_floats; };
     if (tid < A.bfly_threads) {
         // ---- butterfly group ---------------------------------------------------------------------------------
         const int sub = tid >> 4, l16 = tid & 15;
@@ -337,8 +343,8 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
             if (live && mine > a) raw[a] = load8(in + ((int64_t)blockIdx.x + a * (int64_t)gridDim.x) * width);
         // one step: row `it` out of `slot`, which is then refilled with row it + kAhead (the loop below is unrolled
         // over the slots, so that no row moves between registers)
-        auto row_step = [&](int64_t it, Raw8 &slot) {
-            if (live && it < mine) {  // transform row it (its tile last held row it-3, stored one step ago)
+        auto row_step = [&](int64_t it, Raw8 &slot, float *z_tile) {
+            if (live && it < mine) {  // transform row it
                 float u[8];
                 unpack8(slot, u, (const T *)nullptr);
                 if (it + kAhead < mine) slot = load8(in + (blockIdx.x + (it + kAhead) * gridDim.x) * width);
@@ -357,16 +363,21 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
                         u[r] = __uint_as_float(__builtin_amdgcn_perm(h, __float_as_uint(rest), 0x07060302u));
                     }
                 }
-                float4 *dst = (float4 *)&tile[(int)(it % 3) * tile_floats + sub * kTileRow + idx];
+                float4 *dst = (float4 *)&z_tile[sub * kTileRow + idx];
                 dst[0] = make_float4(u[0], u[1], u[2], u[3]);
                 dst[1] = make_float4(u[4], u[5], u[6], u[7]);
             }
-            __syncthreads();
         };
-        for (int64_t it = 0; it < mine + 2; it += kAhead) {
+        static_assert(kAhead % kStepRows == 0, "whole steps per turn of the prefetch slots");
+        for (int64_t st = 0; st < steps; st += kAhead / kStepRows) {
 #pragma unroll
-            for (int a = 0; a < kAhead; ++a)
-                if (it + a < mine + 2) row_step(it + a, raw[a]);
+            for (int h = 0; h < kAhead / kStepRows; ++h)
+                if (st + h < steps) {
+#pragma unroll
+                    for (int r = 0; r < kStepRows; ++r)
+                        row_step((st + h) * kStepRows + r, raw[h * kStepRows + r], tile_of(st + h, r));
+                    __syncthreads();
+                }
         }
     } else if (tid >= A.bfly_threads + kMixWaves * 64) {
         // ---- store group: row it-2, 16-byte pieces of 8 consecutive elements, one rounding to the row type ------
@@ -374,10 +385,12 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
         // pieces per lane (d1 <= 4 KS sub-rows of 16 pieces over the group's lanes): all of a row's tile reads are
         // issued before the first conversion, so their latency is paid once per row
         constexpr int kPieces = (4 * KS * 16 + kStoreWaves * 64 - 1) / (kStoreWaves * 64);
-        for (int64_t it = 0; it < mine + 2; ++it) {
-            if (it >= 2) {
-                const float *y_tile = tile + (int)((it - 2) % 3) * tile_floats;
-                T *out_row = (T *)A.out + (blockIdx.x + (it - 2) * gridDim.x) * width;
+        for (int64_t st = 0; st < steps; ++st) {
+            for (int r = 0; r < kStepRows; ++r) {
+                const int64_t row = (st - 2) * kStepRows + r;
+                if (st < 2 || row >= mine) continue;
+                const float *y_tile = tile_of(st - 2, r);
+                T *out_row = (T *)A.out + (blockIdx.x + row * gridDim.x) * width;
                 float4 a[kPieces], b[kPieces];
 #pragma unroll
                 for (int p = 0; p < kPieces; ++p) {
@@ -423,9 +436,10 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
                     }
                     split8_bf16(w, &qh[t][s2], &ql[t][s2]);
                 }
-            for (int64_t it = 0; it < mine + 2; ++it) {
-                if (it >= 1 && it <= mine) {  // mix row it-1 in place
-                    float *t = tile + (int)((it - 1) % 3) * tile_floats + 32 * mw + (lane & 15);
+            for (int64_t st = 0; st < steps; ++st) {
+                for (int r2 = 0; r2 < kStepRows; ++r2) {  // mix the rows of step st-1 in place
+                    if (st < 1 || (st - 1) * kStepRows + r2 >= mine) continue;
+                    float *t = tile_of(st - 1, r2) + 32 * mw + (lane & 15);
                     v4f acc[2][IT];
 #pragma unroll
                     for (int jb = 0; jb < 2; ++jb)
@@ -494,9 +508,10 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
                 const int i = 16 * t + (lane & 15), k = 4 * s + (lane >> 4);
                 qa[t][s] = (i < d1 && k < d1) ? (kInverse ? A.q[k * d1 + i] : A.q[i * d1 + k]) : 0.0f;
             }
-        for (int64_t it = 0; it < mine + 2; ++it) {
-            if (it >= 1 && it <= mine) {  // mix row it-1 in place
-                float *t = tile + (int)((it - 1) % 3) * tile_floats + 32 * mw + (lane & 15);
+        for (int64_t st = 0; st < steps; ++st) {
+            for (int r2 = 0; r2 < kStepRows; ++r2) {  // mix the rows of step st-1 in place
+                if (st < 1 || (st - 1) * kStepRows + r2 >= mine) continue;
+                float *t = tile_of(st - 1, r2) + 32 * mw + (lane & 15);
                 v4f acc[2][IT];
 #pragma unroll
                 for (int jb = 0; jb < 2; ++jb)
@@ -543,7 +558,7 @@ static hipError_t launch_kron_fused_t(FusedArgs &A, hipStream_t stream)
 {
     A.bfly_threads = ((A.d1 * 16 + 63) / 64) * 64;  // 16 lanes per sub-row, whole waves
     const int threads = A.bfly_threads + (kMixWaves + kStoreWaves) * 64;
-    const size_t lds = 3 * (size_t)A.d1 * kTileRow * sizeof(float);
+    const size_t lds = 3 * kStepRows * (size_t)A.d1 * kTileRow * sizeof(float);
     void (*kern)(FusedArgs), (*kern_slow)(FusedArgs);
     if (A.d1 <= 16) {
         kern = kron128_kernel<T, kInverse, 4, false>;
