@@ -98,7 +98,7 @@ def cpu_baseline(sample_rows: int):
         done += rows
     return {"value": done / t_total, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{done} rows of the n=4096 fp16 workload, same step (fwd+INT2 quant, fwd, inv, bwd), "
-                      f"{t_total:.1f} s of CPU work"}
+                      f"{t_total:.1f} s of wall time on these threads"}
 
 
 def main() -> int:
@@ -107,7 +107,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rows", type=int, default=262144, help="rows of the batch (default: the full workload)")
-    ap.add_argument("--cpu-rows", type=int, default=262144, help="rows of the oracle's timed sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=786432, help="rows of the oracle's timed sample (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the decode / per-head / n=8192 backward figures")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also launch one plain device copy of the 2 GiB input (reference for rocprofv3 --pmc "
