@@ -109,14 +109,22 @@ def check_rotated(y_store, y_ref, dtype, what="", tol=None):
         misses = int((y != ref_r).sum())  # (a tiny output may miss the 99 % with two or three legitimate neighbours)
         assert exact > 0.99 or misses <= 3, f"{what}: only {exact:.4f} of outputs are the correctly rounded oracle value"
         if dtype == "bf16":
-            # rounding to bfloat16 alone moves a row by up to ~2.4e-3 of its norm: the row-norm bound
-            # is applied to the distance from the correctly rounded oracle row instead
-            d_norm = np.abs(y - ref_r)
+            # Rounding to bfloat16 alone moves a row by up to 2^-8 of its norm, more than 2e-3, and in a short row
+            # one dominant element that falls on the other side of a rounding boundary moves the row by more than
+            # 2e-3 of its norm away from the correctly rounded row, too.  What is required instead: every output
+            # is a correct rounding of a value within the float32 cascade's error (2e-5 of max(|ref|, row rms)) of
+            # the exact one, i.e. |y - ref| <= half a unit in the last place of bfloat16 at the rounded value + that.
+            _, e = np.frexp(ref_r)  # |v| = m * 2^e, m in [0.5, 1): half a unit = 2^(e - 1 - 8)
+            excess = d - np.ldexp(1.0, e - 9)
+            slack = 2e-5 * np.maximum(np.abs(y_ref), rms)
+            assert (excess <= slack).all(), f"{what}: {np.max(excess / slack):.2f} x the allowed excess over a correct rounding"
+            d_norm = None
     worst = (d / np.maximum(bound, 1e-300)).max()
     assert worst <= 1.0, f"{what}: element error {worst:.3f} x the bound (tol {tol})"
-    rn = np.linalg.norm(d_norm, axis=1)
-    ref_n = np.linalg.norm(y_ref, axis=1)
-    assert (rn <= tol * ref_n + 1e-300).all(), f"{what}: row-norm error {np.max(rn / np.maximum(ref_n, 1e-300)):.3e}"
+    if d_norm is not None:
+        rn = np.linalg.norm(d_norm, axis=1)
+        ref_n = np.linalg.norm(y_ref, axis=1)
+        assert (rn <= tol * ref_n + 1e-300).all(), f"{what}: row-norm error {np.max(rn / np.maximum(ref_n, 1e-300)):.3e}"
     return float(worst)
 
 

@@ -65,3 +65,39 @@ def test_sweep(i, n, heads, rows, dtype, pad, bits, group, sd):
     gu.check_dtheta(dth, rdth, np.maximum(ab, floor) if rows < 32 else ab, what=tag + " dtheta")
     d = np.abs(dth.astype(np.float64) - rdth)
     assert np.linalg.norm(d) <= 1e-5 * np.linalg.norm(ab), tag + " dtheta norm"
+
+
+def _deep_cases():
+    # the same idea with many rows per workgroup, so that the kernels' row buffers and input slots are reused
+    # dozens of times (n >= 256, where a workgroup pipelines its rows through LDS)
+    rng = np.random.default_rng(77)
+    out = []
+    for i in range(16):
+        n = int(rng.choice([256, 512, 1024, 2048, 4096, 4096, 8192, 8192]))
+        heads = int(rng.choice([1, 1, 2])) if n <= 2048 else 1
+        rows = int(rng.integers(2500, 6000)) * 4096 // (n * heads)
+        dtype = str(rng.choice(["f32", "f16", "bf16"]))
+        pad = int(rng.choice([0, 8]))
+        groups = [g for g in (32, 64, 128, 128, 512, n) if g <= n]
+        out.append((i, n, heads, rows, dtype, pad, int(rng.choice([2, 4])), int(groups[rng.integers(len(groups))]),
+                    str(rng.choice(["f16", "f32"]))))
+    return out
+
+
+@pytest.mark.parametrize("i,n,heads,rows,dtype,pad,bits,group,sd", _deep_cases())
+def test_sweep_many_rows(i, n, heads, rows, dtype, pad, bits, group, sd):
+    x, th, _ = synth.small_case(n, rows, dtype, heads=heads, seed=3000 + i)
+    x64 = synth.to_f64(x, dtype)
+    tag = f"deep case {i}: n={n} H={heads} T={rows} {dtype} pad={pad}"
+    y_ref = oracle.forward(x64, th, n, heads)
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, pad=pad), y_ref, dtype, tag + " fwd")
+    gu.check_rotated(gu.run_transform(x, th, n, heads, dtype, inverse=True, pad=pad),
+                     oracle.inverse(x64, th, n, heads), dtype, tag + " inv")
+    codes, scales = gu.run_fwd_quant(x, th, n, heads, dtype, bits, group, sd)
+    gu.check_fused_codes(codes, scales, y_ref, bits, group, sd, dtype, tag + f" int{bits} g={group} {sd}")
+    yq, hist = gu.run_fwd_fakequant(x, th, n, heads, dtype, bits, group, sd)
+    c = oracle.unpack_codes(codes, bits)
+    want = synth.cast_storage(oracle.dequantize(c, scales.astype(np.float32), group).astype(np.float64), dtype)
+    u = np.uint16 if dtype != "f32" else np.uint32
+    np.testing.assert_array_equal(yq.view(u), want.view(u), err_msg=tag + " fake-quantised values")
+    np.testing.assert_array_equal(hist, oracle.bin_histogram(c, bits), err_msg=tag + " histogram")
