@@ -10,9 +10,9 @@ import oracle
 from paper_2509_09679_amd import binding as B
 from paper_2509_09679_amd import synth
 
-# Row-norm tolerance: 1e-5 for float32 I/O, 2e-3 for half-precision I/O.  Element tolerance: the same,
-# except bfloat16 outputs, whose unit roundoff 2^-8 = 3.9e-3 is already above 2e-3: there an element
-# may deviate by one output rounding plus the float32 cascade error.
+# Row-norm tolerance: 1e-5 for float32 I/O, 2e-3 for binary16 I/O.  Element tolerance: the same.
+# bfloat16 outputs, whose unit roundoff 2^-8 = 3.9e-3 is already above 2e-3: an element may deviate by one
+# output rounding plus the float32 cascade error (see check_rotated), and there is no row-norm bound.
 TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
 ELEM_TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2.0 ** -8 + 1e-4}
 
