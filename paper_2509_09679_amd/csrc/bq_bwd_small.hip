@@ -21,7 +21,7 @@
 namespace bq {
 
 constexpr int kSbThreads = 256;
-constexpr int kSbMaxSlots = 4096;
+constexpr int kSbMaxSlots = 4096;  // (8192 measured no faster for narrow rows and slower where the reduction grows)
 
 struct SmallBwdArgs {
     const void *x, *dy;
@@ -193,8 +193,10 @@ static SmallBwdGrid small_bwd_grid(const Shape &s)
     g.rows_per_block = width < g.span ? (int)(g.span / width) : 1;
     g.slices = width >= g.span ? (int)(width / g.span) : 1;
     g.n_groups = (s.rows + g.rows_per_block - 1) / g.rows_per_block;
-    // about two workgroups per compute unit; the slot count (partial sums to write and to add) stays bounded
-    int64_t per_slice = 512 / g.slices > 0 ? 512 / g.slices : 1;
+    // 2048 waves, eight per compute unit (all that fit with these kernels' registers), whatever the workgroup width;
+    // the slot count (partial sums to write and to add) stays bounded
+    const int64_t wgs = 2048 / (g.span / 512);
+    int64_t per_slice = wgs / g.slices > 0 ? wgs / g.slices : 1;
     if (per_slice * g.rows_per_block > kSbMaxSlots) per_slice = kSbMaxSlots / g.rows_per_block;
     if (per_slice > g.n_groups) per_slice = g.n_groups;
     g.grid = (unsigned)(per_slice * g.slices);
