@@ -51,7 +51,8 @@ def alg_flops_per_row(op: str, n: int, heads: int) -> int:
 
 def time_kernel(fn, iters: int, warmup: int = 2):
     """Average duration in ms of `fn` (launches on torch's current stream) measured with events on
-    that stream."""
+    that stream.  The clock needs some tens of milliseconds of work to settle (the first dozens of launches of a
+    sub-millisecond kernel run up to 1.5x slower), hence the generous warm-up counts of the callers."""
     import torch
 
     for _ in range(warmup):
@@ -269,7 +270,7 @@ def extra_figures(B, synth, torch, dev):
                 for _ in range(32):
                     B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows)
         torch.cuda.synchronize()
-        avg_g, med_g, _ = time_kernel(graph.replay, 20, 3)
+        avg_g, med_g, _ = time_kernel(graph.replay, 30, 30)
         dec[f"T{T}"]["in_graph_us"] = round(med_g * 1e3 / 32, 2)
         del graph
     res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream; in_graph_us: "
@@ -288,7 +289,7 @@ def extra_figures(B, synth, torch, dev):
         state["i"] = (state["i"] + 1) % len(bufs)
         B.bq_butterfly_fwd_quant(bufs[state["i"]], plan4, codes4, scales4, q4, rows4)
 
-    avg, med, mx = time_kernel(run4, 30, 6)
+    avg, med, mx = time_kernel(run4, 30, 30)
     bpr = alg_bytes_per_row("fwd_quant", 128, 32, 2, 4, 128, 4)
     res["per_head"] = {"workload": "32 heads x n=128, T=8192, bf16, fused fwd + per-head INT4",
                        "avg_ms": round(avg, 4), "rows_per_s": 8192 / (avg * 1e-3),
@@ -299,7 +300,7 @@ def extra_figures(B, synth, torch, dev):
     dx4 = torch.empty_like(x4)
     dth4 = torch.empty_like(theta4)
     ws4 = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows4)), dtype=torch.uint8, device=dev)
-    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x4, dy4, plan4, dx4, dth4, ws4, rows4), 30, 6)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x4, dy4, plan4, dx4, dth4, ws4, rows4), 30, 30)
     bprb = alg_bytes_per_row("bwd", 128, 32, 2)
     res["per_head_bwd"] = {"workload": "32 heads x n=128, T=8192, bf16: dx and dtheta", "avg_ms": round(avg, 4),
                            "rows_per_s": 8192 / (avg * 1e-3), "GBps": round(bprb * 8192 / (avg * 1e-3) / 1e9, 1),
@@ -314,7 +315,7 @@ def extra_figures(B, synth, torch, dev):
     dth5 = torch.empty_like(theta5)
     rows5 = B.make_rows(x5, 8192, 1)
     ws5 = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows5)), dtype=torch.uint8, device=dev)
-    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x5, dy5, plan5, dx5, dth5, ws5, rows5), 5, 1)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_bwd(x5, dy5, plan5, dx5, dth5, ws5, rows5), 20, 15)
     bpr = alg_bytes_per_row("bwd", 8192, 1, 2)
     fpr = alg_flops_per_row("bwd", 8192, 1)
     res["bwd_n8192"] = {"workload": "n=8192, T=65536, bf16: dx and dtheta", "avg_ms": round(avg, 4),
@@ -326,9 +327,9 @@ def extra_figures(B, synth, torch, dev):
     y5 = dx5
     c5, s5 = B.alloc_quant_outputs(T5, 8192, 1, 2, 128, "f16", dev)
     q5 = B.make_quant(2, 128, "f16")
-    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x5, y5, plan5, rows5), 10, 3)
-    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(x5, y5, plan5, rows5), 10, 3)
-    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(x5, plan5, c5, s5, q5, rows5), 10, 3)
+    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x5, y5, plan5, rows5), 30, 30)
+    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(x5, y5, plan5, rows5), 30, 30)
+    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(x5, plan5, c5, s5, q5, rows5), 30, 30)
     b_f = alg_bytes_per_row("fwd", 8192, 1, 2)
     b_q = alg_bytes_per_row("fwd_quant", 8192, 1, 2, 2, 128, 2)
     res["fwd_n8192"] = {"workload": "n=8192, T=65536, bf16: forward, inverse, fused forward + INT2 g128",
@@ -345,7 +346,7 @@ def extra_figures(B, synth, torch, dev):
     yq3 = torch.empty_like(x3)
     hist3 = torch.zeros(4, dtype=torch.int64, device=dev)
     q3 = B.make_quant(2, 128, "f16")
-    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_fakequant(x3, plan3, yq3, hist3, q3, rows3), 10, 3)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_fakequant(x3, plan3, yq3, hist3, q3, rows3), 30, 30)
     bpr = alg_bytes_per_row("fwd", 4096, 1, 2)
     res["fakequant"] = {"workload": "n=4096, T=262144, fp16: Dequant(Quant(Bx)) INT2 g128 + bin histogram",
                         "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
@@ -354,7 +355,7 @@ def extra_figures(B, synth, torch, dev):
     # the fused kernel with INT4 codes on the same batch
     c34, s34 = B.alloc_quant_outputs(T3, 4096, 1, 4, 128, "f16", dev)
     q34 = B.make_quant(4, 128, "f16")
-    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x3, plan3, c34, s34, q34, rows3), 10, 3)
+    avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x3, plan3, c34, s34, q34, rows3), 30, 30)
     bpr4 = alg_bytes_per_row("fwd_quant", 4096, 1, 2, 4, 128, 2)
     res["fwd_quant_int4"] = {"workload": "n=4096, T=262144, fp16: fused forward + INT4 g128, fp16 scales",
                              "avg_ms": round(avg, 4), "rows_per_s": T3 / (avg * 1e-3),
@@ -367,9 +368,9 @@ def extra_figures(B, synth, torch, dev):
     yf = torch.empty_like(xf)
     rf = B.make_rows(xf, 4096, 1)
     cf, sf = B.alloc_quant_outputs(Tf, 4096, 1, 2, 128, "f16", dev)
-    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(xf, yf, plan3, rf), 10, 3)
-    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(xf, yf, plan3, rf), 10, 3)
-    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(xf, plan3, cf, sf, q3, rf), 10, 3)
+    a_f, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(xf, yf, plan3, rf), 30, 30)
+    a_i, _, _ = time_kernel(lambda: B.bq_butterfly_inv(xf, yf, plan3, rf), 30, 30)
+    a_q, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(xf, plan3, cf, sf, q3, rf), 30, 30)
     b_f = alg_bytes_per_row("fwd", 4096, 1, 4)
     b_q = alg_bytes_per_row("fwd_quant", 4096, 1, 4, 2, 128, 2)
     res["f32_rows"] = {"workload": "n=4096, T=131072, float32 rows: forward, inverse, fused forward + INT2 g128",
@@ -382,9 +383,9 @@ def extra_figures(B, synth, torch, dev):
     # form a butterfly layer and a Hadamard layer both cost one FMA-class instruction per element
     import math
     y3 = yq3
-    a_rand, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan3, rows3), 10, 3)
+    a_rand, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan3, rows3), 30, 30)
     plan_h = B.alloc_plan(torch.full_like(theta3, math.pi / 4), 4096, 1)
-    a_had, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan_h, rows3), 10, 3)
+    a_had, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan_h, rows3), 30, 30)
     res["hadamard_angles"] = {"workload": "n=4096, T=262144, fp16 forward: learned angles vs all angles pi/4",
                               "butterfly_ms": round(a_rand, 4), "hadamard_ms": round(a_had, 4)}
     del yq3, y3
@@ -397,7 +398,7 @@ def extra_figures(B, synth, torch, dev):
     q1 = torch.empty(d1k, d1k, dtype=torch.float32, device=dev)
     B.bq_cayley_build(torch.randn(d1k * (d1k - 1) // 2, device=dev) * 0.3, d1k, q1)
     rk = B.make_kron_rows(xk, d2k)
-    avg, med, mx = time_kernel(lambda: B.bq_kron_fwd(xk, yk, q1, d1k, plank, rk), 10, 3)
+    avg, med, mx = time_kernel(lambda: B.bq_kron_fwd(xk, yk, q1, d1k, plank, rk), 30, 30)
     bprk = 2 * d1k * d2k * 2
     res["kron_5120"] = {"workload": "d = 5120 = 40 x 128, T=65536, fp16: (Cayley 40x40) (x) (butterfly 128)",
                         "avg_ms": round(avg, 4), "rows_per_s": Tk / (avg * 1e-3),
@@ -413,8 +414,8 @@ def extra_figures(B, synth, torch, dev):
     cw, sw = B.alloc_quant_outputs(m, 4096, 1, 2, 128, "f16", dev)
     dthw = torch.empty_like(theta3)
     wsw = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rw)), dtype=torch.uint8, device=dev)
-    a1, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(Wt, plan3, cw, sw, q3, rw), 20, 5)
-    a2, _, _ = time_kernel(lambda: B.bq_butterfly_bwd(Wt, dWt, plan3, None, dthw, wsw, rw), 20, 5)
+    a1, _, _ = time_kernel(lambda: B.bq_butterfly_fwd_quant(Wt, plan3, cw, sw, q3, rw), 30, 30)
+    a2, _, _ = time_kernel(lambda: B.bq_butterfly_bwd(Wt, dWt, plan3, None, dthw, wsw, rw), 30, 30)
     res["weight_side"] = {"workload": "W [11008, 4096] fp16: fused W B^T + INT2 g128; dtheta from (W, dL/dW')",
                           "fwd_quant_ms": round(a1, 4), "bwd_ms": round(a2, 4)}
     return res
