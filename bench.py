@@ -258,6 +258,14 @@ def extra_figures(B, synth, torch, dev):
         q = B.make_quant(4, 128, "f16")
         avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows), 200, 20)
         dec[f"T{T}"] = {"avg_us": round(avg * 1e3, 2), "median_us": round(med * 1e3, 2), "max_us": round(mx * 1e3, 2)}
+        # 2000 calls back to back between two events (the events of the per-call figures cost about 2 us each)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(2000):
+            B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows)
+        e1.record()
+        torch.cuda.synchronize()
+        dec[f"T{T}"]["back_to_back_us"] = round(e0.elapsed_time(e1) / 2000 * 1e3, 2)
         # the same call 32 times in one HIP graph (the library only enqueues kernels, so it can be captured):
         # per-call time without the host's launch cost
         side = torch.cuda.Stream()
@@ -273,8 +281,9 @@ def extra_figures(B, synth, torch, dev):
         avg_g, med_g, _ = time_kernel(graph.replay, 30, 30)
         dec[f"T{T}"]["in_graph_us"] = round(med_g * 1e3 / 32, 2)
         del graph
-    res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream; in_graph_us: "
-                                 "per call inside a captured graph of 32 calls", **dec}
+    res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream; "
+                                 "back_to_back_us: 2000 calls between two events; in_graph_us: per call inside a "
+                                 "captured graph of 32 calls", **dec}
     # per-head: 32 heads x n=128, T=8192, bf16, rotating over 6 buffers (> 256 MB in total)
     x4, th4, _ = synth.device_rows(4, 8192, dev)
     theta4 = torch.from_numpy(th4).to(dev)
