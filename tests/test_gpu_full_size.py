@@ -262,3 +262,45 @@ def test_backward_small_transforms_many_rows():
         acc = d if acc is None else acc + d
         ab = a if ab is None else ab + a
     gu.check_dtheta(dth.cpu().numpy(), acc, ab, what="many rows dtheta n=128")
+
+
+@pytest.mark.parametrize("cfg,T", [(3, 131072), (5, 32768)])
+def test_float32_rows_at_the_sizes_bench_times(cfg, T):
+    # the rows of the n = 4096 / n = 8192 workloads as float32 (the 1e-5 tolerance class): forward, inverse,
+    # fused quantiser and fake quantisation with histogram on the whole batch, sampled rows against the oracle
+    xh, th, _ = synth.device_rows(cfg, T, DEV)
+    x = xh.float()
+    del xh
+    n, dtype = synth.make_workload(cfg, rows=1).n, "f32"
+    plan = B.alloc_plan(torch.from_numpy(th).to(DEV), n, 1)
+    rows = B.make_rows(x, n, 1)
+    pick = torch.as_tensor(_sample_rows(T, 48, 5), device=DEV)
+    xs = synth.torch_to_storage(x[pick], dtype)
+    y_ref = oracle.forward(synth.to_f64(xs, dtype), th, n)
+    y = torch.empty_like(x)
+    B.bq_butterfly_fwd(x, y, plan, rows)
+    torch.cuda.synchronize()
+    ys = synth.torch_to_storage(y[pick], dtype)
+    gu.check_rotated(ys, y_ref, dtype, f"f32 n={n} full fwd")
+    nx, ny = torch.linalg.vector_norm(x.double(), dim=1), torch.linalg.vector_norm(y.double(), dim=1)
+    assert torch.all((nx - ny).abs() <= 1e-5 * nx)  # every row: the transform preserves the norm
+    B.bq_butterfly_inv(y, y, plan, rows)  # in place
+    torch.cuda.synchronize()
+    gu.check_rotated(synth.torch_to_storage(y[pick], dtype), oracle.inverse(synth.to_f64(ys, dtype), th, n), dtype,
+                     f"f32 n={n} full inv")
+    assert torch.all(torch.linalg.vector_norm((y - x).double(), dim=1) <= 2e-5 * nx)  # every row: inverse o forward
+    q = B.make_quant(4, 128, "f16")
+    codes, scales = B.alloc_quant_outputs(T, n, 1, 4, 128, "f16", DEV)
+    B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows)
+    hist = torch.zeros(16, dtype=torch.int64, device=DEV)
+    B.bq_butterfly_fwd_fakequant(x, plan, y, hist, q, rows)
+    torch.cuda.synchronize()
+    gu.check_fused_codes(codes[pick].cpu().numpy(), scales[pick].float().cpu().numpy(), y_ref, 4, 128, "f16", dtype,
+                         f"f32 n={n} full int4")
+    # the fake-quantised rows and the histogram agree with the fused kernel's codes and scales on the whole batch
+    shift = torch.arange(0, 8, 4, device=DEV, dtype=torch.uint8)
+    c = ((codes.unsqueeze(-1) >> shift) & 15).reshape(T, n).to(torch.int64)
+    c = torch.where(c >= 8, c - 16, c)
+    assert torch.equal(torch.bincount((c + 8).reshape(-1), minlength=16), hist)
+    want = c.reshape(T, n // 128, 128).float() * scales.float().unsqueeze(-1)
+    assert torch.equal(want.reshape(T, n), y)
