@@ -65,8 +65,10 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
         bits = q->bits;
     }
     // Persistent workgroups, a multiple of the head count.  Two fit on a compute unit at a time.  Swept on
-    // large batches (same box, 512 .. 2048): the fused kernels (VALU-bound) are fastest with 1024 .. 1280
-    // workgroups, the plain transforms (HBM-bound) with 768 or 1280 and 15 % slower with 1024 or 2048.
+    // large batches (same box, 512 .. 2304, after a long warm-up): the fused kernels (VALU-bound) do not care
+    // (768 .. 2048 within 1 %), the plain transforms (HBM-bound) are fastest with an odd multiple of 256
+    // (768, 1280, 1792, 2304 alike) and 6 .. 18 % slower with anything else tried (512, 640, 896, 1000, 1024,
+    // 1152, 1536, 2048).
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
     const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : 768;
     int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
