@@ -150,8 +150,12 @@ bq_status bq_cayley_build(const float *params, int32_t d1, float *q1, void *stre
 /* y = (Q1 (x) B(theta)) x  (paper, "Kronecker Product Formulation": Q_composite = Q1 (x) Q2 with a
  * butterfly for the power-of-two factor).  A row has d1 * d2 elements, element (i, j) at i * d2 + j:
  * with X the d1 x d2 matrix of a row, the result is Q1 X B^T.  rows->n = d2, rows->heads must be 1,
- * rows->ld_x = rows->ld_y = d1 * d2 (dense rows).  plan: a plan for (n = d2, heads = 1).  The butterfly
- * factor is applied first and its result passes through y in rows->dtype.  y == x is allowed. */
+ * rows->ld_x = rows->ld_y = d1 * d2 (dense rows).  plan: a plan for (n = d2, heads = 1).  y == x is allowed.
+ * Arithmetic: d2 = 128 with d1 <= 40: one pass, the butterflies in float32 and the product with Q1 on the
+ * matrix cores with float32 accumulation, one rounding to rows->dtype; the product's operands are float32 for
+ * float32 and bfloat16 rows, and two-way bfloat16 splits of both factors (three products, relative error of
+ * a term below 3 * 2^-16) for binary16 rows.  Other shapes: two passes, the butterfly factor first, its result
+ * passing through y in rows->dtype (a second rounding), then the product with Q1 in float32. */
 bq_status bq_kron_fwd(const void *x, void *y, const float *q1, int32_t d1, const void *plan,
                       const bq_rows *rows, void *stream);
 
