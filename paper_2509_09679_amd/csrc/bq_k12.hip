@@ -68,9 +68,11 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // large batches (same box, 512 .. 2304, after a long warm-up): the fused kernels (VALU-bound) do not care
     // (768 .. 2048 within 1 %), the plain transforms (HBM-bound) are fastest with an odd multiple of 256
     // (768, 1280, 1792, 2304 alike) and 6 .. 18 % slower with anything else tried (512, 640, 896, 1000, 1024,
-    // 1152, 1536, 2048).
+    // 1152, 1536, 2048).  The forward transform is faster still with ONE workgroup per compute unit (256: 0.84 ->
+    // 0.79 ms for 2^30 16-bit elements at every n from 256 to 4096, float32 rows 0.793 -> 0.776 ms, small
+    // batches too); the inverse is not (0.88 against 0.855 ms).
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
-    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : 768;
+    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : mode == kFwd ? 256 : 768;
     int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * A.heads);
