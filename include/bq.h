@@ -131,10 +131,12 @@ size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows);
  * Given upstream dy = dL/d(Bx):  dx = B^T dy  ([rows][ld_y], rows->dtype) and
  * dtheta[h][i][j] = sum over rows of  g_i[b] * x_i[a] - g_i[a] * x_i[b]   (float32, OVERWRITTEN),
  * where x_i / g_i are the activations / gradients at the output of layer i and (a, b) is the pair of
- * angle (i, j).  x and dy: [rows][ld_x].  Layer activations are recomputed, not stored.  Partial
+ * angle (i, j).  x and dy: [rows][ld_x].  Partial
  * sums are kept per workgroup and combined in a fixed order in a second pass: the result does not
  * depend on scheduling.  workspace: device scratch of at least the queried size, 256-byte aligned;
- * its contents on entry are ignored.  dx may be NULL to skip it; dtheta may be NULL to skip it. */
+ * its contents on entry are ignored.  dx may be NULL to skip it; dtheta may be NULL to skip it.
+ * rows == 0: dtheta (if given) is set to zero, nothing else is read or written, x, dy, plan and workspace may
+ * be NULL. */
 bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
                            void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream);
 

@@ -1,4 +1,4 @@
-// C ABI of libbq: argument validation and dispatch.  No kernels here.
+// C ABI of libbq: argument validation and dispatch.  No transform kernels here (one fill kernel).
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -67,6 +67,12 @@ bq_status check_plan(const void *plan, const char *who)
 bq_status hip_fail(hipError_t e, const char *who)
 {
     return fail(BQ_ERR_HIP, "%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
+}
+
+__global__ void zero_floats_kernel(float *p, size_t count)
+{
+    const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < count) p[q] = 0.0f;
 }
 
 bq_status transform(bq::Mode mode, const void *in, void *out, const void *plan, const bq_rows *rows,
@@ -261,28 +267,45 @@ size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows)
     return bq::bwd_workspace_bytes(s);
 }
 
-bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
-                           void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream)
+static bq_status bwd_common(const void *x, const void *dy, const void *plan, void *dx, float *dtheta, void *workspace,
+                            size_t workspace_bytes, const bq_rows *rows, void *stream, const char *who)
 {
-    const char *who = "bq_butterfly_bwd";
     bq::Shape s;
     bq_status st = check_rows(rows, &s, who);
     if (st != BQ_OK) return st;
-    if (s.rows > 0 && (!x || !dy)) return fail(BQ_ERR_NULL, "%s: x or dy is NULL", who);
     if (!dx && !dtheta) return fail(BQ_ERR_NULL, "%s: both outputs are NULL", who);
+    if (dtheta && misaligned(dtheta, 4)) return fail(BQ_ERR_ALIGN, "%s: dtheta not aligned to 4 bytes", who);
+    if (s.rows == 0) {  // an empty batch may come with NULL data pointers; the sum over no rows is zero
+        if (dtheta) {
+            const size_t count = (size_t)s.heads * s.k * (s.n / 2);
+            hipLaunchKernelGGL(zero_floats_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                               dtheta, count);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e, who);
+        }
+        return ok();
+    }
+    if (!x || !dy) return fail(BQ_ERR_NULL, "%s: x or dy is NULL", who);
     if ((st = check_plan(plan, who)) != BQ_OK) return st;
-    if (misaligned(x, itemsize(s.dtype)) || misaligned(dy, itemsize(s.dtype)) ||
-        (dx && misaligned(dx, itemsize(s.dtype))) || (dtheta && misaligned(dtheta, 4)))
+    if (misaligned(x, itemsize(s.dtype)) || misaligned(dy, itemsize(s.dtype)) || (dx && misaligned(dx, itemsize(s.dtype))))
         return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
-    size_t need = bq::bwd_workspace_bytes(s);
-    if (!workspace) return fail(BQ_ERR_NULL, "%s: workspace is NULL", who);
-    if (misaligned(workspace, 256)) return fail(BQ_ERR_ALIGN, "%s: workspace must be aligned to 256 bytes", who);
-    if (workspace_bytes < need)
-        return fail(BQ_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", who, workspace_bytes, need);
+    const size_t need = bq::bwd_workspace_bytes(s);
+    {
+        if (!workspace) return fail(BQ_ERR_NULL, "%s: workspace is NULL", who);
+        if (misaligned(workspace, 256)) return fail(BQ_ERR_ALIGN, "%s: workspace must be aligned to 256 bytes", who);
+        if (workspace_bytes < need)
+            return fail(BQ_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", who, workspace_bytes, need);
+    }
     bq::PlanView pv = bq::plan_view(plan, s.n, s.heads, s.k);
     hipError_t e = bq::launch_bwd(x, dy, pv, dx, dtheta, workspace, s, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, who);
     return ok();
+}
+
+bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
+                           void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream)
+{
+    return bwd_common(x, dy, plan, dx, dtheta, workspace, workspace_bytes, rows, stream, "bq_butterfly_bwd");
 }
 
 const char *bq_status_string(bq_status s)

@@ -208,3 +208,11 @@ def test_cayley_and_kron_validation():
         assert call(fn, plan=FAKE + 32) == 4
         assert call(fn, r=_rows(rows=3, n=128, ld=40 * 128, dtype=B.BQ_F16), x=FAKE + 2) == 4  # two elements at a time
         assert call(fn, r=_rows(rows=0, n=128, ld=40 * 128), x=None, y=None) == 0
+
+
+def test_bwd_empty_batch_needs_no_plan_or_workspace():
+    # dx alone on an empty batch: nothing to launch, nothing to clear
+    L = B.lib()
+    r = _rows(rows=0, n=1024, dtype=B.BQ_F16)
+    assert L.bq_butterfly_bwd(None, None, None, FAKE, None, None, 0, ctypes.byref(r), None) == 0
+    assert L.bq_butterfly_bwd(None, None, None, None, None, None, 0, ctypes.byref(r), None) == 1  # no output at all
