@@ -140,6 +140,18 @@ size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows);
 bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
                            void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream);
 
+/* The same pass for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch is a fixed array in the
+ * library's device image (bq_butterfly_bwd_static_max_bytes() bytes, 32 MiB, held on every GPU the library
+ * runs on until the process ends); the call allocates and frees nothing.  Same arguments, results and error
+ * codes as bq_butterfly_bwd without the workspace pair; a batch whose bq_butterfly_bwd_workspace_bytes exceeds
+ * the array is refused with BQ_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share the one
+ * array (its previous contents are ignored), so calls that overlap in time on the same GPU, on different
+ * streams, race: serialise them.  The array's address is looked up once per GPU, on the first call there. */
+bq_status bq_butterfly_bwd_static(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
+                                  const bq_rows *rows, void *stream);
+size_t bq_butterfly_bwd_static_max_bytes(void);
+
 /* ---- widths that are not powers of two ------------------------------------------------------ */
 
 /* Orthogonal factor for a width d = d1 * d2 with d1 not a power of two (paper, "Concrete Example for

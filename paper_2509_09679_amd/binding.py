@@ -21,7 +21,8 @@ DTYPE_CODES = {"f32": BQ_F32, "f16": BQ_F16, "bf16": BQ_BF16}
 
 EXPORTS = ["bq_plan_bytes", "bq_plan_build", "bq_butterfly_fwd", "bq_butterfly_inv", "bq_butterfly_fwd_quant",
            "bq_butterfly_fwd_fakequant", "bq_cayley_build", "bq_kron_fwd", "bq_kron_inv",
-           "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_status_string", "bq_last_error",
+           "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_butterfly_bwd_static",
+           "bq_butterfly_bwd_static_max_bytes", "bq_status_string", "bq_last_error",
            "bq_version"]
 
 
@@ -74,6 +75,10 @@ def lib() -> ctypes.CDLL:
         L.bq_butterfly_bwd_workspace_bytes.restype = sz
         L.bq_butterfly_bwd.argtypes = [vp, vp, vp, vp, vp, vp, sz, ctypes.POINTER(bq_rows), vp]
         L.bq_butterfly_bwd.restype = ctypes.c_int
+        L.bq_butterfly_bwd_static.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(bq_rows), vp]
+        L.bq_butterfly_bwd_static.restype = ctypes.c_int
+        L.bq_butterfly_bwd_static_max_bytes.argtypes = []
+        L.bq_butterfly_bwd_static_max_bytes.restype = sz
         L.bq_status_string.argtypes = [ctypes.c_int]
         L.bq_status_string.restype = ctypes.c_char_p
         L.bq_last_error.restype = ctypes.c_char_p
@@ -177,6 +182,15 @@ def bq_butterfly_bwd(x, dy, plan, dx, dtheta, workspace, rows: bq_rows, stream=N
     _check(lib().bq_butterfly_bwd(_ptr(x), _ptr(dy), _ptr(plan), _ptr(dx), _ptr(dtheta), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), ctypes.byref(rows),
                                   _stream_ptr(stream)))
+
+
+def bq_butterfly_bwd_static(x, dy, plan, dx, dtheta, rows: bq_rows, stream=None) -> None:
+    _check(lib().bq_butterfly_bwd_static(_ptr(x), _ptr(dy), _ptr(plan), _ptr(dx), _ptr(dtheta), ctypes.byref(rows),
+                                         _stream_ptr(stream)))
+
+
+def bq_butterfly_bwd_static_max_bytes() -> int:
+    return int(lib().bq_butterfly_bwd_static_max_bytes())
 
 
 def bq_version() -> int:

@@ -1,7 +1,9 @@
-// C ABI of libbq: argument validation and dispatch.  No transform kernels here (one fill kernel).
+// C ABI of libbq: argument validation and dispatch.  No transform kernels here; the only device objects of
+// this file are the fixed scratch array of bq_butterfly_bwd_static and a fill kernel.
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "bq_internal.h"
 
@@ -67,6 +69,34 @@ bq_status check_plan(const void *plan, const char *who)
 bq_status hip_fail(hipError_t e, const char *who)
 {
     return fail(BQ_ERR_HIP, "%s: HIP error %d (%s)", who, (int)e, hipGetErrorString(e));
+}
+
+// ---- fixed device scratch for the entry point that must not allocate ---------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only
+// a stand-in for the symbol: its device address on the current GPU comes from hipGetSymbolAddress, once per
+// device, and that pointer is what kernels and copies receive.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+bq_status static_scratch(void **out, const char *who)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(BQ_ERR_HIP, "%s: hipGetDevice failed: %d (%s)", who, (int)e, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(BQ_ERR_UNSUPPORTED, "%s: device index %d beyond %d", who, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(BQ_ERR_HIP, "%s: hipGetSymbolAddress failed: %d (%s)", who, (int)e, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return BQ_OK;
 }
 
 __global__ void zero_floats_kernel(float *p, size_t count)
@@ -268,7 +298,7 @@ size_t bq_butterfly_bwd_workspace_bytes(const bq_rows *rows)
 }
 
 static bq_status bwd_common(const void *x, const void *dy, const void *plan, void *dx, float *dtheta, void *workspace,
-                            size_t workspace_bytes, const bq_rows *rows, void *stream, const char *who)
+                            size_t workspace_bytes, bool fixed_scratch, const bq_rows *rows, void *stream, const char *who)
 {
     bq::Shape s;
     bq_status st = check_rows(rows, &s, who);
@@ -290,7 +320,12 @@ static bq_status bwd_common(const void *x, const void *dy, const void *plan, voi
     if (misaligned(x, itemsize(s.dtype)) || misaligned(dy, itemsize(s.dtype)) || (dx && misaligned(dx, itemsize(s.dtype))))
         return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
     const size_t need = bq::bwd_workspace_bytes(s);
-    {
+    if (fixed_scratch) {
+        if (need > kStaticScratchBytes)
+            return fail(BQ_ERR_WORKSPACE, "%s: this batch needs %zu bytes of scratch, the fixed scratch array holds %zu; "
+                                          "use bq_butterfly_bwd with a workspace of your own", who, need, kStaticScratchBytes);
+        if ((st = static_scratch(&workspace, who)) != BQ_OK) return st;
+    } else {
         if (!workspace) return fail(BQ_ERR_NULL, "%s: workspace is NULL", who);
         if (misaligned(workspace, 256)) return fail(BQ_ERR_ALIGN, "%s: workspace must be aligned to 256 bytes", who);
         if (workspace_bytes < need)
@@ -305,7 +340,15 @@ static bq_status bwd_common(const void *x, const void *dy, const void *plan, voi
 bq_status bq_butterfly_bwd(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
                            void *workspace, size_t workspace_bytes, const bq_rows *rows, void *stream)
 {
-    return bwd_common(x, dy, plan, dx, dtheta, workspace, workspace_bytes, rows, stream, "bq_butterfly_bwd");
+    return bwd_common(x, dy, plan, dx, dtheta, workspace, workspace_bytes, false, rows, stream, "bq_butterfly_bwd");
+}
+
+size_t bq_butterfly_bwd_static_max_bytes(void) { return kStaticScratchBytes; }
+
+bq_status bq_butterfly_bwd_static(const void *x, const void *dy, const void *plan, void *dx, float *dtheta,
+                                  const bq_rows *rows, void *stream)
+{
+    return bwd_common(x, dy, plan, dx, dtheta, nullptr, 0, true, rows, stream, "bq_butterfly_bwd_static");
 }
 
 const char *bq_status_string(bq_status s)

@@ -215,4 +215,26 @@ def test_bwd_empty_batch_needs_no_plan_or_workspace():
     L = B.lib()
     r = _rows(rows=0, n=1024, dtype=B.BQ_F16)
     assert L.bq_butterfly_bwd(None, None, None, FAKE, None, None, 0, ctypes.byref(r), None) == 0
+    assert L.bq_butterfly_bwd_static(None, None, None, FAKE, None, ctypes.byref(r), None) == 0
     assert L.bq_butterfly_bwd(None, None, None, None, None, None, 0, ctypes.byref(r), None) == 1  # no output at all
+
+
+def test_bwd_static_validation():
+    L = B.lib()
+    cap = B.bq_butterfly_bwd_static_max_bytes()
+    assert cap == 32 << 20
+
+    def call(r, x=FAKE, dy=FAKE, plan=FAKE, dx=FAKE, dth=FAKE):
+        return L.bq_butterfly_bwd_static(x, dy, plan, dx, dth, ctypes.byref(r), None)
+
+    r = _rows(rows=64, n=1024, dtype=B.BQ_BF16)
+    assert call(r, x=None) == 1
+    assert call(r, plan=None) == 1
+    assert call(r, dx=None, dth=None) == 1
+    assert call(r, plan=FAKE + 16) == 4
+    assert call(_rows(rows=64, n=48)) == 2
+    # a batch whose scratch need exceeds the fixed array is refused before anything touches the GPU
+    big = _rows(rows=4096, n=128, heads=4096, dtype=B.BQ_F16)
+    assert B.bq_butterfly_bwd_workspace_bytes(big) > cap
+    assert call(big) == 5
+    assert b"fixed scratch" in L.bq_last_error()
