@@ -1,29 +1,29 @@
-// Backward pass for n = 4096 and n = 8192 (k = 12, 13), one head: dx = B^T dy and
+// Backward pass for n = 256 .. 8192, in blocks of 4096 points (k = 12): dx = B^T dy and
 // dtheta[i][p] = sum over rows of  g_i[b] x_i[a] - g_i[a] x_i[b]   (x_i, g_i at the output of layer i;
 // paper, "Gradient Flow Through Butterfly Layers": d y_a / d theta = -y_b, d y_b / d theta = y_a).
 //
-// Orthogonality makes stored activations unnecessary: x_{i-1} = B_i^T x_i.  The forward state is
-// recomputed once, then the transposed cascade runs on x and g together.  Both start it with scale 1, so
-// they share the scale-deferred coefficients and, before layer i, the scales D_i[e] (plan table fw_inv).
-// Sums are accumulated in deferred units,
-//   acc += v_g[b] v_x[a] - v_g[a] v_x[b],   dtheta = D_i[a] D_i[b] acc,
+// Orthogonality makes stored activations unnecessary: x_{i-1} = B_i^T x_i.  The forward state of a row is
+// recomputed in the workgroup that consumes it, then the transposed cascade runs on x and g together.  Both
+// start it with scale 1, so they share the scale-deferred coefficients c_i and, before layer i, the scales
+// E_i[e] (plan table fw_inv).  Sums are accumulated in deferred units,
+//   acc += v_g[b] v_x[a] - v_g[a] v_x[b],   dtheta = E_i[a] E_i[b] acc,
 // the factor being applied once per workgroup at the end.  For a layer that pairs lanes each lane keeps
 // the partial sum of its own element (one v_fmac_f32 with a DPP operand per element); the two lanes'
 // sums are combined at the end.
 //
-// All kernels work on 4096 points with 8 points per thread.  Registers cannot hold the coefficients of
-// all layers in both directions plus the sums, so the pass is two kernels, and the second one splits
-// its work over two groups of waves:
-//
-//   F:  x -> forward cascade of layers 1..12, float32 result into the workspace
-//   PN: waves 0..7  (phase P): layers 12..8 transposed on (x, g), sums of those layers
-//       waves 8..15 (phase N): layers 7..1 transposed on the row that phase P finished one step
-//                              earlier (handed over through LDS), sums of those layers, dx out
+// One kernel, one pass over x, dy and dx, nothing else in memory.  What makes that fit a compute unit's
+// registers: the forward recomputation uses the SAME coefficient registers as the transposed cascade (see
+// reg_layer_swapped below), so a thread holds one coefficient per element and layer plus the layer's sums,
+// and the 12 layers are split over two groups of eight waves by position, not by direction:
+//   group N (layout N: 8 consecutive elements per thread, layers 1..3 on registers, 4..6 on DPP lanes)
+//   group Q (layout Q: layers 7..10 on DPP lanes, 11 and 12 on registers)
+// A row goes  N: layers 1..6 forward -> LDS -> Q: layers 7..12 forward, then 12..7 transposed on (x, g)
+// with sums -> LDS -> N: layers 6..1 transposed with sums, dx out;  the groups work on different rows at
+// the same time (see bwd_fused_kernel).
 //
 // n = 8192: layers 1..12 act inside each half of a row, only layer 13 couples the halves.  A workgroup
-// takes one half of its rows.  F stops before layer 13 and writes the state in the units the transposed
-// cascade has after its first layer (plan table fm_fwd); phase P reads both halves of dy, forms its own
-// half of g_12 and, for the sum of layer 13, the other half as well:
+// takes one half of its rows; group Q reads both halves of dy, forms its own half of g_12 and, for the sum of
+// layer 13, the other half as well:
 //   dtheta_13[p] = sum over rows of  g_12[b] x_12[a] - g_12[a] x_12[b]
 // (the same expression one layer further down: rotating both vectors of a pair leaves it unchanged),
 // the lower-half workgroup contributing the first term and the upper-half one the second.
@@ -32,8 +32,8 @@
 // of rows add to it in stream order, and a last kernel sums the slices in double in a fixed order: no
 // atomics, the result does not depend on scheduling.
 //
-// All kernels exit at once when the plan flags the scale-deferred tables as unusable; the generic
-// backward kernel, launched behind them with the opposite condition, then does the work.
+// The kernel exits at once when the plan flags the scale-deferred tables as unusable; the generic
+// backward kernel, launched behind it with the opposite condition, then does the work.
 #include "bq_bwd_blocks.h"
 
 namespace bq {
@@ -99,9 +99,8 @@ __device__ __forceinline__ void lds_read_n2(const float *buf, int an, float (&u)
 struct BwdFastArgs {
     const void *x, *dy;
     void *dx;
-    float *xk;       // chunk intermediate, [chunk_rows][n] float32
     float *partial;  // [slices][slice_floats]
-    const float *fg_fwd, *fd_fwd, *fm_fwd, *fg_inv, *fd_inv, *fw_inv;
+    const float *fg_inv, *fd_inv, *fw_inv;  // plan tables of the transposed cascade
     const int *bad_fwd, *bad_inv;
     int64_t row0, rows;  // this chunk: rows [row0, row0 + rows) of the batch
     int64_t ld_in, ld_out;
@@ -136,7 +135,7 @@ struct Part {
     // would run on the vector unit.
     int tail_row;  // kVirt: the kernel row (counted from this launch's first) that is the short last block, or -1
     int tail;          // ... and the number of rows it has
-    static constexpr int xs = kHalf ? 2 * G::n : G::n;  // row length of x_k; a slice holds xs / 2 sums per layer
+    static constexpr int xs = kHalf ? 2 * G::n : G::n;  // kernel row length; a slice holds xs / 2 sums per layer
     __device__ __forceinline__ Part(const BwdFastArgs &A)
     {
         half = kHalf ? (blockIdx.x >> 3) & 1 : 0;
@@ -166,159 +165,154 @@ struct Part {
     __device__ __forceinline__ bool in_tail_gap(int e) const { return kVirt && (e >> row_log) >= tail; }
 };
 
-// ---- F: forward cascade of layers 1..12 to float32 ------------------------------------------------------
-template <typename T, bool kHalf, bool kVirt>
-__global__ __launch_bounds__(G::threads) __attribute__((amdgpu_waves_per_eu(4))) void bwd_f_kernel(BwdFastArgs A)
+// ---- layout Q and the forward recomputation ---------------------------------------------------------------
+// base index of a thread in layout Q: the four bits of its chunk inside the 16-lane row are idx bits 7, 8, 9
+// (DPP masks 1, 2, 7: layers 8, 9, 10) and idx bit 6 (row_ror:8: layer 7); idx bit 0 and idx bits 10, 11 are
+// register bits (layers 11, 12 pair registers); idx bits 1, 2 are lane bits 4, 5 and idx bits 3..5 the wave.
+__device__ __forceinline__ int base_q(int wave, int lane)
 {
-    extern __shared__ float lds[];  // [row buffer][output scales]
-    if (plan_is_bad(A)) return;
-    const Part<kHalf, kVirt> part(A);
-    const int ts = part.ts;
-    constexpr int xs = Part<kHalf, kVirt>::xs;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
-    const int idx_p = base_p2<K>(wave, lane);
-    const int an = lds_addr2(idx_n), ap = lds_addr2(idx_p);
-    float *buf = lds, *dtab = lds + G::kRowFloats;
-    const float *fg = A.fg_fwd;
-    float cn[7][8], cp[K - 7][8];
-#pragma unroll
-    for (int j = 0; j < 7; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) cn[j][r] = fg[part.trow(idx_n, j) + part.col(idx_n) + r];
-#pragma unroll
-    for (int j = 0; j < K - 7; ++j)
-#pragma unroll
-        for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
-            cp[j][r] = (!kVirt || 8 + j <= part.n_log)
-                           ? fg[part.trow(idx_p + p_reg_idx2<K>(r), 7 + j) + part.col(idx_p + p_reg_idx2<K>(r))]
-                           : 0.0f;
-    {
-        const float *scale = kHalf ? A.fm_fwd : A.fd_fwd;
-        float d[8];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) d[r] = scale[(size_t)part.head(idx_n) * ts + part.col(idx_n) + r];
-        lds_write_n2(dtab, an, d);
-    }
-    const T *x = (const T *)A.x + A.row0 * A.ld_in + part.c0;
-    // kVirt: a sub-row missing from the last block reads the block's first row instead (its dy will be zero)
-    const uint32_t off_x = part.off(idx_n, A.sub_ld_in), off_x0 = part.off(idx_n & part.tmask, A.sub_ld_in);
-    const bool gap = part.in_tail_gap(idx_n);
-    auto load_row = [&](int r) { return load8(x + r * A.ld_in + ((gap && r == part.tail_row) ? off_x0 : off_x)); };
-    float *xk = A.xk + part.c0 + idx_n;
-    const int n_rows = (int)A.rows;
-    int row = part.slot;
-    if (row >= n_rows) return;
-    Raw8 raw = load_row(row);
-    for (; row < n_rows; row += part.nslots) {
-        float u[8];
-        unpack8(raw, u, (const T *)nullptr);
-        const int next = row + part.nslots;
-        if (next < n_rows) raw = load_row(next);
-        reg_layer_first<0>(u, cn[0]);
-        reg_layer<1>(u, cn[1]);
-        reg_layer<2>(u, cn[2]);
-        dpp_layer_xor1(u, cn[3]);
-        dpp_layer_xor2(u, cn[4]);
-        dpp_layer_xor7(u, cn[5]);
-        dpp_layer_xor8(u, cn[6]);
-        __syncthreads();  // the previous row's reads of buf are complete
-        lds_write_n2(buf, an, u);
-        __syncthreads();
-        lds_read_p2<K>(buf, ap, u);
-        dpp_layer_xor1(u, cp[0]);
-        dpp_layer_xor2(u, cp[1]);
-        dpp_layer_xor7(u, cp[2]);
-        reg_layer<1>(u, cp[3]);
-        reg_layer<2>(u, cp[4]);
-        lds_write_p2<K>(buf, ap, u);
-        __syncthreads();
-        lds_read_n2(buf, an, u);
-        float d[8];
-        lds_read_n2(dtab, an, d);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) u[r] *= d[r];
-        store8(xk + (size_t)row * xs, u);
-    }
+    const int c4 = lane_chunk(lane & 15);
+    return ((c4 & 7) << 7) | ((c4 >> 3) << 6) | (((lane >> 4) & 1) << 1) | (((lane >> 5) & 1) << 2) | (wave << 3);
 }
 
-// ---- building blocks of PN ------------------------------------------------------------------------------
-struct PAcc {  // deferred sums of phase P: lane layers 8..10, register layers 11 and 12
-    float d[3][8], r1[4], r2[4];
+// Forward layer in the transposed cascade's own coefficients.  With E_i[e] the scale of element e before
+// transposed layer i (plan table fw_inv; E_0 = fd_inv), carry the forward state as w_i = E_i * x_i.  Then
+//   w_i[a] = w_{i-1}[a] + c_i[b] w_{i-1}[b],   w_i[b] = w_{i-1}[b] + c_i[a] w_{i-1}[a]
+// with c_i the transposed cascade's coefficients: an element's forward coefficient is its PARTNER's coefficient
+// of the transposed layer.  (Forward deferred scale F and transposed scale E of a pair satisfy
+// F[b] / F[a] = E[a] / E[b] when F = 1 / E, and E_{i-1} = cos * E_i for both elements of a pair.)  After the
+// last layer w = x, which is also where the transposed cascade starts (E = 1): no rescaling at the turn.
+template <int J>
+__device__ __forceinline__ void reg_layer_swapped(float (&u)[8], const float (&c)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (!(r & (1 << J))) {
+            const int a = r, b = r | (1 << J);
+            const float ua = u[a], ub = u[b];
+            u[a] = __builtin_fmaf(c[b], ub, ua);
+            u[b] = __builtin_fmaf(c[a], ua, ub);
+        }
+    }
+}
+// ... and for a pair in two lanes: both the partner's coefficient and the partner's value sit in the other
+// lane, so the product is formed there and fetched with one DPP add.
+#define BQ_DPP_ADD8(MOD)                                                                               \
+    asm volatile("s_nop 1\n\t"                                                                        \
+                 "v_add_f32_dpp %0, %8, %0 " MOD " row_mask:0xf bank_mask:0xf\n\t"                    \
+                 "v_add_f32_dpp %1, %9, %1 " MOD " row_mask:0xf bank_mask:0xf\n\t"                    \
+                 "v_add_f32_dpp %2, %10, %2 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_add_f32_dpp %3, %11, %3 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_add_f32_dpp %4, %12, %4 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_add_f32_dpp %5, %13, %5 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_add_f32_dpp %6, %14, %6 " MOD " row_mask:0xf bank_mask:0xf\n\t"                   \
+                 "v_add_f32_dpp %7, %15, %7 " MOD " row_mask:0xf bank_mask:0xf"                       \
+                 : "+v"(u[0]), "+v"(u[1]), "+v"(u[2]), "+v"(u[3]), "+v"(u[4]), "+v"(u[5]), "+v"(u[6]),  \
+                   "+v"(u[7])                                                                          \
+                 : "v"(z[0]), "v"(z[1]), "v"(z[2]), "v"(z[3]), "v"(z[4]), "v"(z[5]), "v"(z[6]), "v"(z[7]))
+
+#define BQ_DPP_FWD_LAYER(NAME, MOD)                                                        \
+    __device__ __forceinline__ void NAME(float (&u)[8], const float (&c)[8])               \
+    {                                                                                      \
+        float z[8];                                                                        \
+        _Pragma("unroll") for (int r = 0; r < 8; ++r) z[r] = c[r] * u[r];                  \
+        BQ_DPP_ADD8(MOD);                                                                  \
+    }
+BQ_DPP_FWD_LAYER(dpp_fwd_xor1, "quad_perm:[1,0,3,2]")
+BQ_DPP_FWD_LAYER(dpp_fwd_xor2, "quad_perm:[2,3,0,1]")
+BQ_DPP_FWD_LAYER(dpp_fwd_xor7, "row_half_mirror")
+BQ_DPP_FWD_LAYER(dpp_fwd_xor8, "row_ror:8")
+
+// ---- deferred sums and the transposed layers of the two wave groups -----------------------------------------
+struct QAcc {  // group Q: lane layers 7 (d[0]), 8, 9, 10 (d[1..3]), register layers 11 (r1) and 12 (r2)
+    float d[4][8], r1[4], r2[4];
     __device__ __forceinline__ void clear()
     {
 #pragma unroll
-        for (int j = 0; j < 3; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 8; ++r) d[j][r] = 0.0f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) r1[q] = r2[q] = 0.0f;
     }
 };
-// layers 12..8 transposed on (vx, vg) held in layout P; cp[j] = coefficients of layer 8 + j.  kFirst: layer
-// 12 is the first layer of the transposed cascade (scales still 1).
-template <bool kFirst>
-__device__ __forceinline__ void p_phase(float (&vx)[8], float (&vg)[8], const float (&cp)[5][8], PAcc &acc)
-{
-    reg_acc<2>(acc.r2, vg, vx);  // layer 12 (register bit 2)
-    if (kFirst) {
-        reg_layer_first<2>(vx, cp[4]);
-        reg_layer_first<2>(vg, cp[4]);
-    } else {
-        reg_layer<2>(vx, cp[4]);
-        reg_layer<2>(vg, cp[4]);
-    }
-    reg_acc<1>(acc.r1, vg, vx);  // layer 11 (register bit 1)
-    reg_layer<1>(vx, cp[3]);
-    reg_layer<1>(vg, cp[3]);
-    dpp_acc_xor7(acc.d[2], vg, vx);  // layer 10
-    dpp_layer_xor7(vx, cp[2]);
-    dpp_layer_xor7(vg, cp[2]);
-    dpp_acc_xor2(acc.d[1], vg, vx);  // layer 9
-    dpp_layer_xor2(vx, cp[1]);
-    dpp_layer_xor2(vg, cp[1]);
-    dpp_acc_xor1(acc.d[0], vg, vx);  // layer 8
-    dpp_layer_xor1(vx, cp[0]);
-    dpp_layer_xor1(vg, cp[0]);
-}
-
-// Coefficients of layers 1..7 for the eight points a thread holds in layout N: the first kLds layers in
-// LDS (written and read by the same thread), the others in registers.
-template <int kLds>
-struct CoefSplit {
-    float c[7 - kLds][8];
-    const float4 *tab;  // float4 index (2 j + half) * kSlots + slot: consecutive lanes, consecutive banks
-    int first;
-    static constexpr int kSlots = 512;
-    __device__ __forceinline__ void load(const float *fg, int stride, int idx, float *lds_tab, int slot)
+struct NAcc6 {  // group N: register layers 1..3 (r[0..2]), lane layers 4..6 (d[0..2])
+    float d[3][8], r[3][4];
+    __device__ __forceinline__ void clear()
     {
-        tab = (const float4 *)lds_tab;
-        first = slot;
-        float4 *t = (float4 *)lds_tab + first;
 #pragma unroll
-        for (int j = 0; j < kLds; ++j) {
-            t[(2 * j) * kSlots] = *(const float4 *)(fg + j * stride + idx);
-            t[(2 * j + 1) * kSlots] = *(const float4 *)(fg + j * stride + idx + 4);
-        }
+        for (int j = 0; j < 3; ++j) {
 #pragma unroll
-        for (int j = kLds; j < 7; ++j)
+            for (int q = 0; q < 8; ++q) d[j][q] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 8; ++r) c[j - kLds][r] = fg[j * stride + idx + r];
-    }
-    template <int J>
-    __device__ __forceinline__ void get(float (&o)[8]) const
-    {
-        if (J < kLds) {
-            int f = first;
-            asm volatile("" : "+v"(f));  // keeps the reads inside the row loop (hoisted, they would spill)
-            const float4 a = tab[f + 2 * J * kSlots], b = tab[f + (2 * J + 1) * kSlots];
-            o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-        } else {
-#pragma unroll
-            for (int r = 0; r < 8; ++r) o[r] = c[(J < kLds ? kLds : J) - kLds][r];
+            for (int q = 0; q < 4; ++q) r[j][q] = 0.0f;
         }
     }
 };
+
+// layers 12..7 transposed on (vx, vg) held in layout Q; cq[j] = coefficients of layer 7 + j
+__device__ __forceinline__ void q_phase(float (&vx)[8], float (&vg)[8], const float (&cq)[6][8], QAcc &acc)
+{
+    reg_acc<2>(acc.r2, vg, vx);  // layer 12 (register bit 2)
+    reg_layer<2>(vx, cq[5]);
+    reg_layer<2>(vg, cq[5]);
+    reg_acc<1>(acc.r1, vg, vx);  // layer 11 (register bit 1)
+    reg_layer<1>(vx, cq[4]);
+    reg_layer<1>(vg, cq[4]);
+    dpp_acc_xor7(acc.d[3], vg, vx);  // layer 10
+    dpp_layer_xor7(vx, cq[3]);
+    dpp_layer_xor7(vg, cq[3]);
+    dpp_acc_xor2(acc.d[2], vg, vx);  // layer 9
+    dpp_layer_xor2(vx, cq[2]);
+    dpp_layer_xor2(vg, cq[2]);
+    dpp_acc_xor1(acc.d[1], vg, vx);  // layer 8
+    dpp_layer_xor1(vx, cq[1]);
+    dpp_layer_xor1(vg, cq[1]);
+    dpp_acc_xor8(acc.d[0], vg, vx);  // layer 7
+    dpp_layer_xor8(vx, cq[0]);
+    dpp_layer_xor8(vg, cq[0]);
+}
+// layers 7..12 forward on w held in layout Q
+__device__ __forceinline__ void q_forward(float (&w)[8], const float (&cq)[6][8])
+{
+    dpp_fwd_xor8(w, cq[0]);
+    dpp_fwd_xor1(w, cq[1]);
+    dpp_fwd_xor2(w, cq[2]);
+    dpp_fwd_xor7(w, cq[3]);
+    reg_layer_swapped<1>(w, cq[4]);
+    reg_layer_swapped<2>(w, cq[5]);
+}
+// layers 6..1 transposed on (vx, vg) held in layout N; on return vg holds g_0 in deferred units
+__device__ __forceinline__ void n_phase6(float (&vx)[8], float (&vg)[8], const float (&cn)[6][8], NAcc6 &acc)
+{
+    dpp_acc_xor7(acc.d[2], vg, vx);  // layer 6
+    dpp_layer_xor7(vx, cn[5]);
+    dpp_layer_xor7(vg, cn[5]);
+    dpp_acc_xor2(acc.d[1], vg, vx);  // layer 5
+    dpp_layer_xor2(vx, cn[4]);
+    dpp_layer_xor2(vg, cn[4]);
+    dpp_acc_xor1(acc.d[0], vg, vx);  // layer 4
+    dpp_layer_xor1(vx, cn[3]);
+    dpp_layer_xor1(vg, cn[3]);
+    reg_acc<2>(acc.r[2], vg, vx);  // layer 3
+    reg_layer<2>(vx, cn[2]);
+    reg_layer<2>(vg, cn[2]);
+    reg_acc<1>(acc.r[1], vg, vx);  // layer 2
+    reg_layer<1>(vx, cn[1]);
+    reg_layer<1>(vg, cn[1]);
+    reg_acc<0>(acc.r[0], vg, vx);  // layer 1 (x is not needed below it)
+    reg_layer<0>(vg, cn[0]);
+}
+// layers 1..6 forward on w held in layout N
+__device__ __forceinline__ void n_forward(float (&w)[8], const float (&cn)[6][8])
+{
+    reg_layer_swapped<0>(w, cn[0]);
+    reg_layer_swapped<1>(w, cn[1]);
+    reg_layer_swapped<2>(w, cn[2]);
+    dpp_fwd_xor1(w, cn[3]);
+    dpp_fwd_xor2(w, cn[4]);
+    dpp_fwd_xor7(w, cn[5]);
+}
 
 // fw_inv entry (scale before transposed layer i) of block element e; rmask != 0: the tables of e's own head
 __device__ __forceinline__ float fw_at(const float *fw_inv, int stride, int tmask, int n_log, int rmask, int c0, int e, int i)
@@ -330,69 +324,45 @@ __device__ __forceinline__ float fw_at(const float *fw_inv, int stride, int tmas
 // Deferred sums -> dtheta partials of this workgroup.  part: its slice, `pairs` sums per layer, indexed by the
 // pair's position in the whole kernel row (c0 + element); fw_inv: the plan table, rows `stride` apart, column
 // (c0 + element) & tmask.
-__device__ __forceinline__ void finalize_p(float *part, const PAcc &acc, int idx_p, const float *fw_inv, int stride, int tmask,
-                                           int pairs, int c0, int n_log, int rmask, int first)
-{
-#pragma unroll
-    for (int J = 1; J <= 2; ++J) {  // register layers
-        const int i = (J == 2) ? K : K - 1;
-        if (i > n_log) continue;  // a layer the transform does not have: no table row, nothing to write
-        int q = 0;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            if (!(r & (1 << J))) {
-                const int a = idx_p + p_reg_idx2<K>(r), b = idx_p + p_reg_idx2<K>(r | (1 << J));
-                const float v = (J == 2 ? acc.r2[q] : acc.r1[q]) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, a, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), v, first);
-                ++q;
-            }
-        }
+struct FinArgs {
+    float *part;
+    const float *fw_inv;
+    int stride, tmask, pairs, c0, n_log, rmask, first;
+    __device__ __forceinline__ float scale(int a, int b, int i) const
+    {
+        return fw_at(fw_inv, stride, tmask, n_log, rmask, c0, a, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i);
     }
+    __device__ __forceinline__ float *at(int a, int i) const { return part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i); }
+};
+
+// lane layer i whose pairs sit in lanes `mask_j` apart (0..3: masks 1, 2, 7, 8); e[r]: the thread's elements
+template <class Idx>
+__device__ __forceinline__ void finalize_lane_layer(const FinArgs &F, const float (&acc)[8], int i, int mask_j, Idx elem)
+{
+    if (i > F.n_log) return;  // a layer the transform does not have: no table row, nothing to write
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {  // lane layers: layer 8 + j, lane masks 1, 2, 7
-        const int i = 8 + j;
-        if (i > n_log) continue;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const float mine = acc.d[j][r];
-            const float other = lane_partner(mine, j);
-            const int e = idx_p + p_reg_idx2<K>(r);
-            if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
-                const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, e, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
-            }
+    for (int r = 0; r < 8; ++r) {
+        const float mine = acc[r];
+        const float other = lane_partner(mine, mask_j);
+        const int e = elem(r);
+        if (!(e & (1 << (i - 1)))) {  // the lane holding the lower element writes
+            const int b = e | (1 << (i - 1));
+            put_partial(F.at(e, i), (mine - other) * F.scale(e, b, i), F.first);
         }
     }
 }
-
-__device__ __forceinline__ void finalize_n(float *part, const NAcc &acc, int idx, const float *fw_inv, int stride, int tmask,
-                                           int pairs, int c0, int n_log, int rmask, int first)
+// register layer i pairing register bit J
+template <int J, class Idx>
+__device__ __forceinline__ void finalize_reg_layer(const FinArgs &F, const float (&acc)[4], int i, Idx elem)
 {
+    if (i > F.n_log) return;
+    int q = 0;
 #pragma unroll
-    for (int J = 0; J < 3; ++J) {  // layers 1..3
-        const int i = J + 1;
-        int q = 0;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            if (!(r & (1 << J))) {
-                const int a = idx + r, b = idx + (r | (1 << J));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + a, i), acc.r[J][q] * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, a, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
-                ++q;
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {  // layers 4..7, lane masks 1, 2, 7, 8
-        const int i = 4 + j;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const float mine = acc.d[j][r];
-            const float other = lane_partner(mine, j);
-            const int e = idx + r;
-            if (!(e & (1 << (i - 1)))) {
-                const int b = e | (1 << (i - 1));
-                put_partial(part + (size_t)(i - 1) * pairs + pair_index(c0 + e, i), (mine - other) * (fw_at(fw_inv, stride, tmask, n_log, rmask, c0, e, i) * fw_at(fw_inv, stride, tmask, n_log, rmask, c0, b, i)), first);
-            }
+    for (int r = 0; r < 8; ++r) {
+        if (!(r & (1 << J))) {
+            const int a = elem(r), b = elem(r | (1 << J));
+            put_partial(F.at(a, i), acc[q] * F.scale(a, b, i), F.first);
+            ++q;
         }
     }
 }
@@ -425,164 +395,285 @@ __device__ __forceinline__ void store8_bounded(T *base, uint32_t bytes, uint32_t
     }
 }
 
-__device__ __forceinline__ void load8_f32(const float *p, float (&v)[8])
-{
-    const float4 a = *(const float4 *)p;
-    const float4 b = *((const float4 *)p + 1);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
+// Workgroup barrier that waits for the wave's LDS traffic only.  (__syncthreads() also waits for the wave's
+// outstanding global loads and stores, which would end every row's prefetch at the next barrier.)  Everything
+// the two wave groups exchange goes through LDS.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// ---- PN: the transposed cascade, split over two groups of eight waves -----------------------------------
-// Waves 0..7 run phase P on row t while waves 8..15 run phase N on row t-1; a row changes hands through an
-// LDS area in layout N.  Each group keeps only its own coefficients and sums in registers (the second
-// group also parks the coefficients of its first kPnLdsLayers layers in LDS), which is what lets 1024
-// threads fit the 128-register budget.  Both groups execute the same number of workgroup barriers:
-//   P, row t:   write area A (layout N) | B1 | read A (layout P), layers 12..8, write area H | B2
-//   N, row t-1: read H                  | B1 | layers 7..1, store dx                        | B2
-// A slice of `partial` holds k n / 2 sums in dtheta order; for n = 8192 another 4096 follow, the
-// upper-half workgroup's (negative) share of layer 13.
-constexpr int kPnThreads = 1024;
-constexpr int kPnLdsLayers = 4;
-constexpr size_t kPnLdsFloats = 4 * (size_t)G::kRowFloats + (1 + kPnLdsLayers) * (size_t)G::n;
+// ---- the fused pass ---------------------------------------------------------------------------------------
+// Waves 0..7 (group N, layout N, layers 1..6) and waves 8..15 (group Q, layout Q, layers 7..12) of a workgroup
+// pipeline its rows; per iteration `it` and two barriers M and E:
+//   N: read H (row it-2: x_6, g_6)          | M | layers 6..1 transposed with sums, dx out; row it: x in, scale
+//                                                 E_0, layers 1..6 forward, write XA                           | E
+//   Q: read XA (row it-1: w_6)              | M | layers 7..12 forward; dy (row it-1) from the ring; layers
+//                                                 12..7 transposed with sums; write H                          | E
+// XA and H are read before M and written after it, so one buffer each suffices.  dy reaches group Q through a
+// ring of LDS slots filled by direct global->LDS loads (16 bytes per lane, issued by group Q's waves one
+// iteration or more ahead); the chunk a lane loads is chosen so that the 4-byte reads of layout Q spread over
+// all banks:  position (16-byte units) of chunk q = idx >> 3 in a slot:
+//   pos bits 0..2 = q bits 4..6 (idx 7..9), pos bits 3..5 = q bits 0..2 (idx 3..5), pos bits 6..8 = q bits 3, 7, 8.
+// x reaches group N through registers (one row ahead).
+constexpr int kFusedThreads = 1024;
+
+template <typename T, bool kHalf>
+struct FusedLds {
+    static constexpr int kSlots = (sizeof(T) == 4 && kHalf) ? 2 : 3;
+    static constexpr uint32_t kHalfRowBytes = G::n * sizeof(T);
+    static constexpr uint32_t kSlotBytes = kHalfRowBytes * (kHalf ? 2 : 1);
+    static constexpr int kTabFloats = (kHalf ? 2 : 1) * G::n;  // E_0 (group N) and, n = 8192, the layer-13 coefficients (group Q)
+    // The ring comes first: the LDS address of a direct global->LDS load travels in M0, and the ring's addresses
+    // stay below 64 KB this way whatever the field's width.
+    static constexpr size_t kRingBytes = (size_t)kSlots * kSlotBytes;
+    static_assert(kRingBytes <= 65536, "ring addresses must fit 16 bits");
+    static constexpr size_t kBytes = kRingBytes + (3 * (size_t)G::kRowFloats + kTabFloats) * sizeof(float);
+};
 
 template <typename T, bool kDx, bool kHalf, bool kVirt>
-__global__ __launch_bounds__(kPnThreads) void bwd_pn_kernel(BwdFastArgs A)
+__global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
 {
     extern __shared__ float lds[];
     if (plan_is_bad(A)) return;
+    using L = FusedLds<T, kHalf>;
     const Part<kHalf, kVirt> pt(A);
     const int ts = pt.ts;
     constexpr int xs = Part<kHalf, kVirt>::xs;
     const int role = threadIdx.x >> 9;  // uniform per wave
     const int tid = threadIdx.x & 511, wave = tid >> 6, lane = tid & 63;
-    const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
-    const int an = lds_addr2(idx_n);
-    float *hand = lds + 2 * G::kRowFloats;
+    float *xa = lds + L::kRingBytes / sizeof(float), *hx = xa + G::kRowFloats, *hg = xa + 2 * G::kRowFloats;
+    float4 *tab = (float4 *)(xa + 3 * G::kRowFloats);  // per-thread tables: float4 slots [tid] and [512 + tid]
     const int mine = A.rows > (int64_t)pt.slot ? (int)((A.rows - pt.slot + pt.nslots - 1) / pt.nslots) : 0;
-    float *part = A.partial + (size_t)pt.slot * A.slice_floats;
-    const float *fg = A.fg_inv, *fw = A.fw_inv;
+    const int iters = mine > 0 ? mine + 2 : 0;
+    const float *fg = A.fg_inv;
+    FinArgs F;
+    F.part = A.partial + (size_t)pt.slot * A.slice_floats;
+    F.fw_inv = A.fw_inv;
+    F.stride = ts;
+    F.tmask = pt.tmask;
+    F.pairs = xs / 2;
+    F.c0 = pt.c0;
+    F.n_log = pt.n_log;
+    F.rmask = kVirt ? pt.rmask : 0;
+    F.first = A.first_chunk;
     if (role == 0) {
-        const int idx_p = base_p2<K>(wave, lane);
-        const int ap = lds_addr2(idx_p);
-        float cp[5][8];
+        // ---- group N ----
+        const int idx_n = (wave * 64 + lane_chunk(lane)) * 8;
+        const int an = lds_addr2(idx_n);
+        float cn[6][8];
 #pragma unroll
-        for (int j = 0; j < 5; ++j)
+        for (int j = 0; j < 6; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r)
-                cp[j][r] = (!kVirt || 8 + j <= pt.n_log)
-                               ? fg[pt.trow(idx_p + p_reg_idx2<K>(r), 7 + j) + pt.col(idx_p + p_reg_idx2<K>(r))]
-                               : 0.0f;
-        float c13[8], acc13[8];  // kHalf only: layer 13 in layout N (it pairs column e with e + 4096)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            c13[r] = kHalf ? fg[12 * ts + pt.col(idx_n) + r] : 0.0f;
-            acc13[r] = 0.0f;
+            for (int r = 0; r < 8; ++r) cn[j][r] = fg[pt.trow(idx_n, j) + pt.col(idx_n) + r];
+        {
+            const float *e0 = A.fd_inv + (size_t)pt.head(idx_n) * ts + pt.col(idx_n);
+            tab[tid] = *(const float4 *)e0;
+            tab[512 + tid] = *(const float4 *)(e0 + 4);
         }
-        PAcc acc;
+        NAcc6 acc;
         acc.clear();
-        // uniform row pointers + 32-bit per-thread byte offsets: the loads take their base from scalar
-        // registers and no 64-bit per-thread pointer stays live across the loop
-        const T *dy = (const T *)A.dy + A.row0 * A.ld_in + pt.c0;
-        const T *dyo = (const T *)A.dy + A.row0 * A.ld_in + (pt.c0 ^ G::n);  // the other half (kHalf)
-        const float *xk = A.xk + pt.c0;
-        // kVirt: a sub-row missing from the last block reads the block's first row; its gradient is zeroed below
-        const uint32_t off_g = pt.off(idx_n, A.sub_ld_in) * (uint32_t)sizeof(T);
-        const uint32_t off_g0 = pt.off(idx_n & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
-        const bool gap = pt.in_tail_gap(idx_n);
-        auto fetch = [&](int r, float(&ox)[8], Raw8 &og, Raw8 &ogo) {
-            uint32_t offx = (uint32_t)idx_n * 4u, offg = (gap && r == pt.tail_row) ? off_g0 : off_g;
-            asm volatile("" : "+v"(offx), "+v"(offg));
-            load8_f32((const float *)((const char *)(xk + (size_t)r * xs) + offx), ox);
-            og = load8((const T *)((const char *)(dy + r * A.ld_in) + offg));
-            if (kHalf) ogo = load8((const T *)((const char *)(dyo + r * A.ld_in) + offg));
-        };
-        float nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        Raw8 ng = {}, ngo = {};
-        int row = pt.slot;
-        if (mine > 0) fetch(row, nx, ng, ngo);
-        for (int it = 0; it < mine; ++it, row += pt.nslots) {
-            float vx[8], vg[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) vx[r] = nx[r];
-            unpack8(ng, vg, (const T *)nullptr);
-            if (gap && row == pt.tail_row) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) vg[r] = 0.0f;
-            }
-            if (kHalf) {
-                // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
-                // (its coefficient is the negative of this half's: both scales are still 1)
-                float go[8];
-                unpack8(ngo, go, (const T *)nullptr);
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const float other12 = __builtin_fmaf(-c13[r], vg[r], go[r]);
-                    acc13[r] = __builtin_fmaf(other12, vx[r], acc13[r]);
-                    vg[r] = __builtin_fmaf(c13[r], go[r], vg[r]);
-                }
-            }
-            const int next = it + 1 < mine ? row + pt.nslots : row;  // the last one reads its own row again
-            fetch(next, nx, ng, ngo);
-            lds_write_n2(lds, an, vx);
-            lds_write_n2(lds + G::kRowFloats, an, vg);
-            __syncthreads();  // B1
-            lds_read_p2<K>(lds, ap, vx);
-            lds_read_p2<K>(lds + G::kRowFloats, ap, vg);
-            p_phase<!kHalf>(vx, vg, cp, acc);
-            lds_write_p2<K>(hand, ap, vx);
-            lds_write_p2<K>(hand + G::kRowFloats, ap, vg);
-            __syncthreads();  // B2
-        }
-        __syncthreads();  // the other group's last row
-        __syncthreads();
-        finalize_p(part, acc, idx_p, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, kVirt ? pt.rmask : 0, A.first_chunk);
-        if (kHalf) {
-            // sum of layer 13 = (scale after the layer)^2 * deferred sum; the lower half's share goes to the
-            // layer's place in the slice, the upper half's, negated, behind the slice's regular part
-            float *dst = part + (size_t)(pt.half ? 13 : 12) * G::n + idx_n;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const float d = fw[11 * ts + pt.col(idx_n) + r];
-                const float v = acc13[r] * (d * d);
-                put_partial(dst + r, pt.half ? -v : v, A.first_chunk);
-            }
-        }
-    } else {
-        float *dtab = lds + 4 * G::kRowFloats;  // tables written and read by the same thread
-        CoefSplit<kPnLdsLayers> cn;
-        cn.load(fg + pt.trow(idx_n, 0), ts, pt.col(idx_n), dtab + G::n, tid);
-        const float *fdi = A.fd_inv + (size_t)pt.head(idx_n) * ts + pt.col(idx_n);
-        ((float4 *)dtab)[tid] = *(const float4 *)fdi;
-        ((float4 *)dtab)[512 + tid] = *(const float4 *)(fdi + 4);
-        NAcc acc;
-        acc.clear();
+        const T *x = (const T *)A.x + A.row0 * A.ld_in + pt.c0;
         T *dx = (T *)A.dx + A.row0 * A.ld_out + pt.c0;  // used only if kDx
+        // kVirt: a sub-row missing from the last block reads the block's first row instead (its dy will be zero)
+        const uint32_t off_x = pt.off(idx_n, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const uint32_t off_x0 = pt.off(idx_n & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const bool gap = pt.in_tail_gap(idx_n);
         const uint32_t off_dx = pt.off(idx_n, A.sub_ld_out) * (uint32_t)sizeof(T);
         const uint32_t block_bytes = (uint32_t)(((G::n >> pt.row_log) - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T);
         const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T) : 0u;
-        __syncthreads();  // the other group's first row
-        __syncthreads();
-        int row = pt.slot;
-        for (int it = 0; it < mine; ++it, row += pt.nslots) {
+        auto load_row = [&](int r) {
+            uint32_t off = (gap && r == pt.tail_row) ? off_x0 : off_x;
+            asm volatile("" : "+v"(off));
+            return load8((const T *)((const char *)(x + r * A.ld_in) + off));
+        };
+        Raw8 raw = {};
+        if (mine > 0) raw = load_row(pt.slot);
+        for (int it = 0; it < iters; ++it) {
             float vx[8], vg[8];
-            lds_read_n2(hand, an, vx);
-            lds_read_n2(hand + G::kRowFloats, an, vg);
-            __syncthreads();  // B1: the reads above are complete before the other group refills the area
-            n_phase(vx, vg, cn, acc);
-            if (kDx) {
-                const float4 da = ((const float4 *)dtab)[tid], db = ((const float4 *)dtab)[512 + tid];
-                vg[0] *= da.x; vg[1] *= da.y; vg[2] *= da.z; vg[3] *= da.w;
-                vg[4] *= db.x; vg[5] *= db.y; vg[6] *= db.z; vg[7] *= db.w;
-                uint32_t off = off_dx;
-                asm volatile("" : "+v"(off));
-                if (kVirt)  // the short last block stores only the rows it has
-                    store8_bounded(dx + row * A.ld_out, row == pt.tail_row ? tail_bytes : block_bytes, off, vg);
-                else
-                    store8((T *)((char *)(dx + row * A.ld_out) + off), vg);
+            if (it >= 2) {
+                lds_read_n2(hx, an, vx);
+                lds_read_n2(hg, an, vg);
             }
-            __syncthreads();  // B2
+            wg_barrier();  // M
+            if (it >= 2) {
+                n_phase6(vx, vg, cn, acc);
+                if (kDx) {
+                    const int row = pt.slot + (it - 2) * pt.nslots;
+                    const float4 da = tab[tid], db = tab[512 + tid];
+                    vg[0] *= da.x; vg[1] *= da.y; vg[2] *= da.z; vg[3] *= da.w;
+                    vg[4] *= db.x; vg[5] *= db.y; vg[6] *= db.z; vg[7] *= db.w;
+                    uint32_t off = off_dx;
+                    asm volatile("" : "+v"(off));
+                    if (kVirt)  // the short last block stores only the rows it has
+                        store8_bounded(dx + row * A.ld_out, row == pt.tail_row ? tail_bytes : block_bytes, off, vg);
+                    else
+                        store8((T *)((char *)(dx + row * A.ld_out) + off), vg);
+                }
+            }
+            if (it < mine) {
+                float w[8];
+                unpack8(raw, w, (const T *)nullptr);
+                if (it + 1 < mine) raw = load_row(pt.slot + (it + 1) * pt.nslots);
+                const float4 da = tab[tid], db = tab[512 + tid];
+                w[0] *= da.x; w[1] *= da.y; w[2] *= da.z; w[3] *= da.w;
+                w[4] *= db.x; w[5] *= db.y; w[6] *= db.z; w[7] *= db.w;
+                n_forward(w, cn);
+                lds_write_n2(xa, an, w);
+            }
+            wg_barrier();  // E
         }
-        finalize_n(part, acc, idx_n, fw, ts, pt.tmask, xs / 2, pt.c0, pt.n_log, kVirt ? pt.rmask : 0, A.first_chunk);
+        const auto elem = [&](int r) { return idx_n + r; };
+        finalize_reg_layer<0>(F, acc.r[0], 1, elem);
+        finalize_reg_layer<1>(F, acc.r[1], 2, elem);
+        finalize_reg_layer<2>(F, acc.r[2], 3, elem);
+        finalize_lane_layer(F, acc.d[0], 4, 0, elem);
+        finalize_lane_layer(F, acc.d[1], 5, 1, elem);
+        finalize_lane_layer(F, acc.d[2], 6, 2, elem);
+    } else {
+        // ---- group Q ----
+        const int idx_q = base_q(wave, lane);
+        const int aq = lds_addr2(idx_q);
+        float cq[6][8];
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
+                cq[j][r] = (!kVirt || 7 + j <= pt.n_log)
+                               ? fg[pt.trow(idx_q + p_reg_idx2<K>(r), 6 + j) + pt.col(idx_q + p_reg_idx2<K>(r))]
+                               : 0.0f;
+        float acc13[8];  // kHalf only: layer 13 pairs column e with e + 4096
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc13[r] = 0.0f;
+        if (kHalf) {
+            float c13[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c13[r] = fg[12 * ts + pt.col(idx_q + p_reg_idx2<K>(r))];
+            tab[1024 + tid] = make_float4(c13[0], c13[1], c13[2], c13[3]);
+            tab[1536 + tid] = make_float4(c13[4], c13[5], c13[6], c13[7]);
+        }
+        QAcc acc;
+        acc.clear();
+        // -- the dy ring: what this lane loads, and where this thread reads --
+        constexpr int kSlots = L::kSlots, kLead = kSlots - 2;
+        constexpr int kLoads = ((int)sizeof(T) / 2) * (kHalf ? 2 : 1);  // load instructions per wave and row
+        const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+        const int q_load = ((lane >> 3) & 7) | ((wave & 1) << 3) | ((lane & 7) << 4) | ((wave >> 1) << 7);  // chunk of 8 elements
+        const int e_load = q_load * 8;
+        const uint32_t voff = pt.off(e_load, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const uint32_t voff0 = pt.off(e_load & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const bool gap_load = pt.in_tail_gap(e_load);
+        const uint32_t wave_base = __builtin_amdgcn_readfirstlane(ring0 + (uint32_t)wave * 1024u);
+        const T *dy = (const T *)A.dy + A.row0 * A.ld_in + pt.c0;
+        const T *dyo = (const T *)A.dy + A.row0 * A.ld_in + (pt.c0 ^ G::n);  // the other half (kHalf)
+        auto ring_load = [&](int j) {
+            const int jj = j < mine ? j : mine - 1;  // past the end: the last row again (unused)
+            const int row = pt.slot + jj * pt.nslots;
+            const uint32_t vo = (gap_load && row == pt.tail_row) ? voff0 : voff;
+            const uint32_t m0v = wave_base + (uint32_t)(j % kSlots) * L::kSlotBytes;
+#pragma unroll
+            for (int h = 0; h < (kHalf ? 2 : 1); ++h) {
+                const char *rowp = (const char *)((h ? dyo : dy) + row * A.ld_in);
+#pragma unroll
+                for (int part16 = 0; part16 < (int)sizeof(T) / 2; ++part16) {
+                    // 32-bit rows: the two 16-byte halves of a chunk go to two regions of the slot, 8192 bytes apart
+                    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
+                                 :
+                                 : "v"(vo + 16u * part16), "s"(m0v + (uint32_t)h * L::kHalfRowBytes + 8192u * part16), "s"(rowp)
+                                 : "memory");
+                }
+            }
+        };
+        const int c4 = lane_chunk(lane & 15);
+        const uint32_t pos = (uint32_t)((c4 & 7) | (wave << 3) | ((c4 >> 3) << 6));
+        const uint32_t rd_off = sizeof(T) == 2 ? pos * 16u + (uint32_t)(((lane >> 4) & 1) | (((lane >> 5) & 1) << 1)) * 4u
+                                               : pos * 16u + (uint32_t)((lane >> 5) & 1) * 8192u + (uint32_t)((lane >> 4) & 1) * 8u;
+        const char *ring = (const char *)lds;
+        auto ring_read = [&](int j, int h, float(&v)[8]) {
+            const char *p = ring + (j % kSlots) * L::kSlotBytes + h * L::kHalfRowBytes + rd_off;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (sizeof(T) == 4) {
+                    const float2 f = *(const float2 *)(p + q * 2048);
+                    v[2 * q] = f.x;
+                    v[2 * q + 1] = f.y;
+                } else {
+                    const uint32_t wd = *(const uint32_t *)(p + q * 2048);
+                    if (std::is_same<T, __half>::value) {
+                        const __half2 hh = *(const __half2 *)&wd;
+                        v[2 * q] = __low2float(hh);
+                        v[2 * q + 1] = __high2float(hh);
+                    } else {
+                        v[2 * q] = __uint_as_float(wd << 16);
+                        v[2 * q + 1] = __uint_as_float(wd & 0xFFFF0000u);
+                    }
+                }
+            }
+        };
+        // kVirt: which of the thread's elements lie in rows missing from the short last block
+        int gap_mask = 0;
+        if (kVirt)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) gap_mask |= pt.in_tail_gap(idx_q + p_reg_idx2<K>(r)) ? (1 << r) : 0;
+        if (mine > 0)
+            for (int j = 0; j < kLead; ++j) ring_load(j);
+        for (int it = 0; it < iters; ++it) {
+            ring_load(it + kLead);
+            float vx[8], vg[8];
+            const bool work = it >= 1 && it <= mine;
+            if (work) lds_read_p2<K>(xa, aq, vx);
+            wg_barrier();  // M
+            if (work) {
+                const int row = pt.slot + (it - 1) * pt.nslots;
+                q_forward(vx, cq);
+                ring_read(it - 1, 0, vg);
+                if (kVirt && row == pt.tail_row) {
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (gap_mask & (1 << r)) vg[r] = 0.0f;
+                }
+                if (kHalf) {
+                    // the forward state arrives as E_12 x_12 with E_12 = the cosine of the element's layer-13
+                    // pair; the transposed cascade wants x_12 / E_12:  1 / cos^2 = 1 + tan^2, and the layer's
+                    // coefficient is -+ tan (both scales still 1)
+                    float go[8];
+                    ring_read(it - 1, 1, go);
+                    const float4 ca = tab[1024 + tid], cb = tab[1536 + tid];
+                    const float c13[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        vx[r] *= __builtin_fmaf(c13[r], c13[r], 1.0f);
+                        // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
+                        const float other12 = __builtin_fmaf(-c13[r], vg[r], go[r]);
+                        acc13[r] = __builtin_fmaf(other12, vx[r], acc13[r]);
+                        vg[r] = __builtin_fmaf(c13[r], go[r], vg[r]);
+                    }
+                }
+                q_phase(vx, vg, cq, acc);
+                lds_write_p2<K>(hx, aq, vx);
+                lds_write_p2<K>(hg, aq, vg);
+            }
+            // the row group Q consumes in the next iteration has arrived (younger loads may still be in flight)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLead * kLoads) : "memory");
+            wg_barrier();  // E
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const auto elem = [&](int r) { return idx_q + p_reg_idx2<K>(r); };
+        finalize_reg_layer<2>(F, acc.r2, K, elem);
+        finalize_reg_layer<1>(F, acc.r1, K - 1, elem);
+        finalize_lane_layer(F, acc.d[3], 10, 2, elem);
+        finalize_lane_layer(F, acc.d[2], 9, 1, elem);
+        finalize_lane_layer(F, acc.d[1], 8, 0, elem);
+        finalize_lane_layer(F, acc.d[0], 7, 3, elem);
+        if (kHalf) {
+            // sum of layer 13 = (scale after the layer)^2 * deferred sum; the lower half's share goes to the
+            // layer's place in the slice, the upper half's, negated, behind the slice's regular part
+            float *dst = F.part + (size_t)(pt.half ? 13 : 12) * G::n;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int e = idx_q + p_reg_idx2<K>(r);
+                const float d = A.fw_inv[11 * ts + pt.col(e)];
+                const float v = acc13[r] * (d * d);
+                put_partial(dst + e, pt.half ? -v : v, A.first_chunk);
+            }
+        }
     }
 }
 
@@ -624,13 +715,10 @@ __global__ void bwd_fold_kernel(const double *__restrict__ sums, float *__restri
 }
 
 // ---- host side -----------------------------------------------------------------------------------
-// Slices = row slots of the PN kernel, which runs one workgroup per compute unit (n = 8192: two per slot).
+// Slices = row slots of the kernel, which runs one workgroup per compute unit (n = 8192: two per slot).
 static int bwd_fast_slices(int k) { return k == 13 ? 128 : 256; }
-static constexpr int kBwdFGrid = 512;
-// Kernel rows (of 4096 or 8192 elements) per chunk bound the float32 intermediate in the workspace (2^30
-// elements, 4 GiB).  Small chunks that would stay in the last-level cache measured slower: every launch
-// re-reads the coefficients and rewrites the partial slices, which only amortises over many rows per workgroup.
-static int64_t bwd_fast_chunk_rows(int k) { return (int64_t)1 << (k == 13 ? 17 : 18); }
+// Kernel rows (of 4096 or 8192 elements) per launch: row counters inside the kernel are 32-bit.
+static int64_t bwd_fast_chunk_rows(int) { return (int64_t)1 << 22; }
 static size_t bwd_fast_slice_floats(int k) { return k == 13 ? (size_t)13 * 4096 + 4096 : (size_t)K * (G::n / 2); }
 static int64_t bwd_fast_block_rows(const Shape &s) { return s.k < K ? (int64_t)G::n / ((int64_t)s.n * s.heads) : 1; }
 static int64_t bwd_fast_kernel_rows(const Shape &s)
@@ -656,12 +744,30 @@ bool bwd_fast_supported(const void *x, const void *dy, const void *dx, const flo
 
 static size_t bwd_fast_fold_bytes(int k) { return k < K ? align256((size_t)K * (G::n / 2) * sizeof(double)) : 0; }
 
+// The workspace holds the partial sums only (25 MB; 29 MB for n = 8192; plus the fold buffer for n < 4096).
 size_t bwd_fast_workspace_bytes(const Shape &s)
 {
-    const int64_t kr = bwd_fast_kernel_rows(s);
-    const size_t chunk = (size_t)(kr < bwd_fast_chunk_rows(s.k) ? kr : bwd_fast_chunk_rows(s.k));
-    return align256((size_t)bwd_fast_slices(s.k) * bwd_fast_slice_floats(s.k) * sizeof(float)) + bwd_fast_fold_bytes(s.k) +
-           align256(chunk * (s.k == 13 ? 8192 : 4096) * sizeof(float));
+    return align256((size_t)bwd_fast_slices(s.k) * bwd_fast_slice_floats(s.k) * sizeof(float)) + bwd_fast_fold_bytes(s.k);
+}
+
+// The kernel needs more dynamic LDS than the default limit: raised once per kernel and device.
+template <typename T, bool kDx, bool kHalf, bool kVirt>
+static hipError_t fused_kernel_ready()
+{
+    static hipError_t state[64];
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64)
+        return hipFuncSetAttribute((const void *)bwd_fused_kernel<T, kDx, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)FusedLds<T, kHalf>::kBytes);
+    if (!done[dev]) {  // (a race between two first calls only repeats the same setting)
+        state[dev] = hipFuncSetAttribute((const void *)bwd_fused_kernel<T, kDx, kHalf, kVirt>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)FusedLds<T, kHalf>::kBytes);
+        done[dev] = state[dev] == hipSuccess;
+    }
+    return state[dev];
 }
 
 template <typename T, bool kHalf, bool kVirt>
@@ -673,25 +779,19 @@ static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta
     A.slice_floats = (int64_t)bwd_fast_slice_floats(s.k);
     A.partial = (float *)ws;
     double *fold = (double *)(ws + align256((size_t)slices * A.slice_floats * sizeof(float)));
-    A.xk = (float *)((char *)fold + bwd_fast_fold_bytes(s.k));
-    const size_t lds_f = 2 * G::kRowFloats * sizeof(float), lds_pn = kPnLdsFloats * sizeof(float);
-    hipError_t e = hipFuncSetAttribute((const void *)bwd_f_kernel<T, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_f);
+    const size_t lds_bytes = FusedLds<T, kHalf>::kBytes;
+    hipError_t e = A.dx ? fused_kernel_ready<T, true, kHalf, kVirt>() : fused_kernel_ready<T, false, kHalf, kVirt>();
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, true, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_pn_kernel<T, false, kHalf, kVirt>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pn);
-    if (e != hipSuccess) return e;
-    const int pn_grid = kHalf ? 2 * slices : slices;  // kHalf: a multiple of 16 (see Part)
+    const int grid = kHalf ? 2 * slices : slices;  // kHalf: a multiple of 16 (see Part)
     for (int64_t r0 = 0; r0 < kernel_rows; r0 += chunk_rows) {
         A.row0 = r0;
         A.rows = kernel_rows - r0 < chunk_rows ? kernel_rows - r0 : chunk_rows;
         A.first_chunk = (r0 == 0);
-        // every slice must be written by the first chunk, so the grids do not shrink with the row count
-        hipLaunchKernelGGL((bwd_f_kernel<T, kHalf, kVirt>), dim3(kBwdFGrid), dim3(G::threads), lds_f, stream, A);
+        // every slice must be written by the first chunk, so the grid does not shrink with the row count
         if (A.dx)
-            hipLaunchKernelGGL((bwd_pn_kernel<T, true, kHalf, kVirt>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
+            hipLaunchKernelGGL((bwd_fused_kernel<T, true, kHalf, kVirt>), dim3(grid), dim3(kFusedThreads), lds_bytes, stream, A);
         else
-            hipLaunchKernelGGL((bwd_pn_kernel<T, false, kHalf, kVirt>), dim3(pn_grid), dim3(kPnThreads), lds_pn, stream, A);
+            hipLaunchKernelGGL((bwd_fused_kernel<T, false, kHalf, kVirt>), dim3(grid), dim3(kFusedThreads), lds_bytes, stream, A);
     }
     if (kVirt) {
         const size_t sums = (size_t)s.k * (G::n / 2);  // the layers the transform has
@@ -726,9 +826,6 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     A.x = x;
     A.dy = dy;
     A.dx = dx;
-    A.fg_fwd = pv.fg_fwd;
-    A.fd_fwd = pv.fd_fwd;
-    A.fm_fwd = pv.fm_fwd;
     A.fg_inv = pv.fg_inv;
     A.fd_inv = pv.fd_inv;
     A.fw_inv = pv.fw_inv;

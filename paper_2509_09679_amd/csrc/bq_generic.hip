@@ -352,6 +352,12 @@ static void bwd_geometry(const Shape &s, int *rows_per_tile, int64_t *n_tiles, u
     // the grid must be a multiple of heads so that a workgroup always sees the same head sequence;
     // any grid works for correctness, this one keeps partial slices dense
     int64_t g = tiles < 512 ? tiles : 512;
+    // ... and the partial slices (one per workgroup) within 32 MiB where 8 workgroups or more still fit
+    const int64_t slice_bytes = (int64_t)s.heads * s.k * (s.n / 2) * (int64_t)sizeof(float);
+    int64_t cap = ((int64_t)32 << 20) / slice_bytes;
+    cap -= cap % s.heads;
+    if (cap < 8 * (int64_t)s.heads) cap = 8 * (int64_t)s.heads;
+    if (g > cap) g = cap;
     if (g < 1) g = 1;
     *rows_per_tile = U;
     *n_tiles = tiles;
