@@ -250,37 +250,78 @@ struct NAcc6 {  // group N: register layers 1..3 (r[0..2]), lane layers 4..6 (d[
     }
 };
 
-// layers 12..7 transposed on (vx, vg) held in layout Q; cq[j] = coefficients of layer 7 + j
-__device__ __forceinline__ void q_phase(float (&vx)[8], float (&vg)[8], const float (&cq)[6][8], QAcc &acc)
+// Coefficients of layer 7 for group Q: in registers, or parked in LDS (written and read by the same thread)
+// where the registers are short.
+template <bool kLds>
+struct Coef7 {
+    float c[kLds ? 1 : 8];
+    const float4 *tab;  // kLds: the workgroup's table area; this thread's float4 slots are first and first + 512
+    int first;
+    __device__ __forceinline__ void init(const float (&v)[8], float4 *table, int slot)
+    {
+        if (kLds) {
+            table[slot] = make_float4(v[0], v[1], v[2], v[3]);
+            table[slot + 512] = make_float4(v[4], v[5], v[6], v[7]);
+            tab = table;
+            first = slot;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) c[kLds ? 0 : r] = v[r];
+        }
+    }
+    __device__ __forceinline__ void get(float (&o)[8]) const
+    {
+        if (kLds) {
+            int f = first;
+            asm volatile("" : "+v"(f));  // keeps the reads inside the row loop (hoisted, they would occupy registers again)
+            const float4 a = tab[f], b = tab[f + 512];
+            o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) o[r] = c[kLds ? 0 : r];
+        }
+    }
+};
+
+// layers 12..7 transposed on (vx, vg) held in layout Q; cq[j] = coefficients of layer 8 + j
+template <class C7>
+__device__ __forceinline__ void q_phase(float (&vx)[8], float (&vg)[8], const C7 &c7, const float (&cq)[5][8], QAcc &acc)
 {
     reg_acc<2>(acc.r2, vg, vx);  // layer 12 (register bit 2)
-    reg_layer<2>(vx, cq[5]);
-    reg_layer<2>(vg, cq[5]);
+    reg_layer<2>(vx, cq[4]);
+    reg_layer<2>(vg, cq[4]);
     reg_acc<1>(acc.r1, vg, vx);  // layer 11 (register bit 1)
-    reg_layer<1>(vx, cq[4]);
-    reg_layer<1>(vg, cq[4]);
+    reg_layer<1>(vx, cq[3]);
+    reg_layer<1>(vg, cq[3]);
     dpp_acc_xor7(acc.d[3], vg, vx);  // layer 10
-    dpp_layer_xor7(vx, cq[3]);
-    dpp_layer_xor7(vg, cq[3]);
+    dpp_layer_xor7(vx, cq[2]);
+    dpp_layer_xor7(vg, cq[2]);
     dpp_acc_xor2(acc.d[2], vg, vx);  // layer 9
-    dpp_layer_xor2(vx, cq[2]);
-    dpp_layer_xor2(vg, cq[2]);
+    dpp_layer_xor2(vx, cq[1]);
+    dpp_layer_xor2(vg, cq[1]);
     dpp_acc_xor1(acc.d[1], vg, vx);  // layer 8
-    dpp_layer_xor1(vx, cq[1]);
-    dpp_layer_xor1(vg, cq[1]);
+    dpp_layer_xor1(vx, cq[0]);
+    dpp_layer_xor1(vg, cq[0]);
+    float c[8];
+    c7.get(c);
     dpp_acc_xor8(acc.d[0], vg, vx);  // layer 7
-    dpp_layer_xor8(vx, cq[0]);
-    dpp_layer_xor8(vg, cq[0]);
+    dpp_layer_xor8(vx, c);
+    dpp_layer_xor8(vg, c);
 }
 // layers 7..12 forward on w held in layout Q
-__device__ __forceinline__ void q_forward(float (&w)[8], const float (&cq)[6][8])
+template <class C7>
+__device__ __forceinline__ void q_forward(float (&w)[8], const C7 &c7, const float (&cq)[5][8])
 {
-    dpp_fwd_xor8(w, cq[0]);
-    dpp_fwd_xor1(w, cq[1]);
-    dpp_fwd_xor2(w, cq[2]);
-    dpp_fwd_xor7(w, cq[3]);
-    reg_layer_swapped<1>(w, cq[4]);
-    reg_layer_swapped<2>(w, cq[5]);
+    {
+        float c[8];
+        c7.get(c);
+        dpp_fwd_xor8(w, c);
+    }
+    dpp_fwd_xor1(w, cq[0]);
+    dpp_fwd_xor2(w, cq[1]);
+    dpp_fwd_xor7(w, cq[2]);
+    reg_layer_swapped<1>(w, cq[3]);
+    reg_layer_swapped<2>(w, cq[4]);
 }
 // layers 6..1 transposed on (vx, vg) held in layout N; on return vg holds g_0 in deferred units
 __device__ __forceinline__ void n_phase6(float (&vx)[8], float (&vg)[8], const float (&cn)[6][8], NAcc6 &acc)
@@ -417,15 +458,25 @@ constexpr int kFusedThreads = 1024;
 
 template <typename T, bool kHalf>
 struct FusedLds {
-    static constexpr int kSlots = (sizeof(T) == 4 && kHalf) ? 2 : 3;
+    static constexpr int kSlots = kHalf ? 2 : 3;  // dy ring
     static constexpr uint32_t kHalfRowBytes = G::n * sizeof(T);
     static constexpr uint32_t kSlotBytes = kHalfRowBytes * (kHalf ? 2 : 1);
-    static constexpr int kTabFloats = (kHalf ? 2 : 1) * G::n;  // E_0 (group N) and, n = 8192, the layer-13 coefficients (group Q)
-    // The ring comes first: the LDS address of a direct global->LDS load travels in M0, and the ring's addresses
+    // 16-bit rows: x comes through a ring of its own (two slots; a wave reads back only what it loaded itself);
+    // 32-bit rows are prefetched in registers
+    static constexpr bool kXRing = sizeof(T) == 2;
+    static constexpr uint32_t kXSlotBytes = kHalfRowBytes;
+    static constexpr size_t kDyRingBytes = (size_t)kSlots * kSlotBytes;
+    static constexpr size_t kXRingBytes = kXRing ? 2 * (size_t)kXSlotBytes : 0;
+    // n = 8192 with 16-bit rows: group Q is short of registers and parks the coefficients of layer 7 in LDS
+    static constexpr bool kPark7 = kHalf && sizeof(T) == 2;
+    // per-thread tables: E_0 (group N); n = 8192: the layer-13 coefficients (group Q); kPark7: layer 7 (group Q)
+    static constexpr int kTabFloats = (kHalf ? (kPark7 ? 3 : 2) : 1) * G::n;
+    // The rings come first: the LDS address of a direct global->LDS load travels in M0, and the rings' addresses
     // stay below 64 KB this way whatever the field's width.
-    static constexpr size_t kRingBytes = (size_t)kSlots * kSlotBytes;
+    static constexpr size_t kRingBytes = kDyRingBytes + kXRingBytes;
     static_assert(kRingBytes <= 65536, "ring addresses must fit 16 bits");
     static constexpr size_t kBytes = kRingBytes + (3 * (size_t)G::kRowFloats + kTabFloats) * sizeof(float);
+    static_assert(kBytes <= 160 * 1024, "LDS of a compute unit");
 };
 
 template <typename T, bool kDx, bool kHalf, bool kVirt>
@@ -468,6 +519,12 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             tab[tid] = *(const float4 *)e0;
             tab[512 + tid] = *(const float4 *)(e0 + 4);
         }
+        // The empty statements consume the loaded coefficients: the waits for these loads then sit here and not,
+        // as waits for everything outstanding, inside the row loop.
+#pragma unroll
+        for (int j = 0; j < 6; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) asm volatile("" ::"v"(cn[j][r]));
         NAcc6 acc;
         acc.clear();
         const T *x = (const T *)A.x + A.row0 * A.ld_in + pt.c0;
@@ -479,13 +536,44 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
         const uint32_t off_dx = pt.off(idx_n, A.sub_ld_out) * (uint32_t)sizeof(T);
         const uint32_t block_bytes = (uint32_t)(((G::n >> pt.row_log) - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T);
         const uint32_t tail_bytes = pt.tail > 0 ? (uint32_t)((pt.tail - 1) * A.sub_ld_out + pt.rmask + 1) * (uint32_t)sizeof(T) : 0u;
-        auto load_row = [&](int r) {
+        auto load_row = [&](int r) {  // 32-bit rows: the thread's 8 elements of kernel row r
             uint32_t off = (gap && r == pt.tail_row) ? off_x0 : off_x;
             asm volatile("" : "+v"(off));
             return load8((const T *)((const char *)(x + r * A.ld_in) + off));
         };
+        // 16-bit rows: the x ring.  Lane l of wave w loads the chunk (8 elements) 64 w + l of row j into bytes
+        // [1024 w + 16 l, +16) of slot j & 1 and the thread reads its own chunk 64 w + e(l) back: only the wave's
+        // own loads are involved, so s_waitcnt vmcnt is the only synchronisation, and the load of row it + 2 can
+        // follow the read of row it at once.  Memory operations of a wave complete in issue order: when row `it`
+        // is consumed, the younger ones are the load of row it + 1 and the dx stores of two iterations.
+        constexpr bool kXRing = L::kXRing;
+        constexpr int kStores = kDx ? 1 : 0;
+        const uint32_t xring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds + (uint32_t)L::kDyRingBytes;
+        const uint32_t xwave_base = __builtin_amdgcn_readfirstlane(xring0 + (uint32_t)wave * 1024u);
+        const uint32_t xrd_addr = xring0 + (uint32_t)(wave * 64 + lane_chunk(lane)) * 16u;
+        const int e_xload = (wave * 64 + lane) * 8;
+        const uint32_t xvoff = pt.off(e_xload, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const uint32_t xvoff0 = pt.off(e_xload & pt.tmask, A.sub_ld_in) * (uint32_t)sizeof(T);
+        const bool xgap = pt.in_tail_gap(e_xload);
+        auto x_ring_load = [&](int j) {
+            const int jj = j < mine ? j : mine - 1;  // past the end: the last row again (unused)
+            const int row = pt.slot + jj * pt.nslots;
+            const uint32_t vo = (xgap && row == pt.tail_row) ? xvoff0 : xvoff;
+            const char *rowp = (const char *)(x + row * A.ld_in);
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
+                         :
+                         : "v"(vo), "s"(xwave_base + (uint32_t)(j & 1) * L::kXSlotBytes), "s"(rowp)
+                         : "memory");
+        };
         Raw8 raw = {};
-        if (mine > 0) raw = load_row(pt.slot);
+        if (mine > 0) {
+            if (kXRing) {
+                x_ring_load(0);
+                x_ring_load(1);
+            } else {
+                raw = load_row(pt.slot);
+            }
+        }
         for (int it = 0; it < iters; ++it) {
             float vx[8], vg[8];
             if (it >= 2) {
@@ -510,8 +598,24 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             }
             if (it < mine) {
                 float w[8];
-                unpack8(raw, w, (const T *)nullptr);
-                if (it + 1 < mine) raw = load_row(pt.slot + (it + 1) * pt.nslots);
+                if (kXRing) {
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    u32x4 v;
+                    const uint32_t ra = xrd_addr + (uint32_t)(it & 1) * L::kXSlotBytes;
+                    if (it >= 4)
+                        asm volatile("s_waitcnt vmcnt(%2)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(ra), "n"(1 + 2 * kStores) : "memory");
+                    else  // the pipeline is still filling (fewer stores issued): wait for everything
+                        asm volatile("s_waitcnt vmcnt(0)\n\tds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                                     : "=v"(v) : "v"(ra) : "memory");
+                    x_ring_load(it + 2);  // refills the slot just read
+                    Raw8 r8;
+                    r8.lo = make_uint4(v.x, v.y, v.z, v.w);
+                    unpack8(r8, w, (const T *)nullptr);
+                } else {
+                    unpack8(raw, w, (const T *)nullptr);
+                    if (it + 1 < mine) raw = load_row(pt.slot + (it + 1) * pt.nslots);
+                }
                 const float4 da = tab[tid], db = tab[512 + tid];
                 w[0] *= da.x; w[1] *= da.y; w[2] *= da.z; w[3] *= da.w;
                 w[4] *= db.x; w[5] *= db.y; w[6] *= db.z; w[7] *= db.w;
@@ -520,6 +624,7 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             }
             wg_barrier();  // E
         }
+        if (kXRing) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const auto elem = [&](int r) { return idx_n + r; };
         finalize_reg_layer<0>(F, acc.r[0], 1, elem);
         finalize_reg_layer<1>(F, acc.r[1], 2, elem);
@@ -531,14 +636,21 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
         // ---- group Q ----
         const int idx_q = base_q(wave, lane);
         const int aq = lds_addr2(idx_q);
-        float cq[6][8];
+        float cq[5][8];
 #pragma unroll
-        for (int j = 0; j < 6; ++j)
+        for (int j = 0; j < 5; ++j)
 #pragma unroll
             for (int r = 0; r < 8; ++r)  // layers above log2 n do not exist: weight zero leaves the element as it is
-                cq[j][r] = (!kVirt || 7 + j <= pt.n_log)
-                               ? fg[pt.trow(idx_q + p_reg_idx2<K>(r), 6 + j) + pt.col(idx_q + p_reg_idx2<K>(r))]
+                cq[j][r] = (!kVirt || 8 + j <= pt.n_log)
+                               ? fg[pt.trow(idx_q + p_reg_idx2<K>(r), 7 + j) + pt.col(idx_q + p_reg_idx2<K>(r))]
                                : 0.0f;
+        Coef7<L::kPark7> c7;
+        {
+            float v[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) v[r] = fg[pt.trow(idx_q + p_reg_idx2<K>(r), 6) + pt.col(idx_q + p_reg_idx2<K>(r))];
+            c7.init(v, tab, 2048 + tid);
+        }
         float acc13[8];  // kHalf only: layer 13 pairs column e with e + 4096
 #pragma unroll
         for (int r = 0; r < 8; ++r) acc13[r] = 0.0f;
@@ -548,6 +660,16 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             for (int r = 0; r < 8; ++r) c13[r] = fg[12 * ts + pt.col(idx_q + p_reg_idx2<K>(r))];
             tab[1024 + tid] = make_float4(c13[0], c13[1], c13[2], c13[3]);
             tab[1536 + tid] = make_float4(c13[4], c13[5], c13[6], c13[7]);
+        }
+#pragma unroll
+        for (int j = 0; j < 5; ++j)  // (see group N: pins the waits for the coefficient loads in front of the loop)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) asm volatile("" ::"v"(cq[j][r]));
+        if (!L::kPark7) {
+            float c[8];
+            c7.get(c);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) asm volatile("" ::"v"(c[r]));
         }
         QAcc acc;
         acc.clear();
@@ -586,24 +708,22 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
         const uint32_t rd_off = sizeof(T) == 2 ? pos * 16u + (uint32_t)(((lane >> 4) & 1) | (((lane >> 5) & 1) << 1)) * 4u
                                                : pos * 16u + (uint32_t)((lane >> 5) & 1) * 8192u + (uint32_t)((lane >> 4) & 1) * 8u;
         const char *ring = (const char *)lds;
-        auto ring_read = [&](int j, int h, float(&v)[8]) {
-            const char *p = ring + (j % kSlots) * L::kSlotBytes + h * L::kHalfRowBytes + rd_off;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (sizeof(T) == 4) {
-                    const float2 f = *(const float2 *)(p + q * 2048);
-                    v[2 * q] = f.x;
-                    v[2 * q + 1] = f.y;
+        // elements 2 q and 2 q + 1 of the thread (layout Q) of row j, half h of the slot
+        auto ring_read_pair = [&](int j, int h, int q, float &v0, float &v1) {
+            const char *p = ring + (j % kSlots) * L::kSlotBytes + h * L::kHalfRowBytes + rd_off + q * 2048;
+            if (sizeof(T) == 4) {
+                const float2 f = *(const float2 *)p;
+                v0 = f.x;
+                v1 = f.y;
+            } else {
+                const uint32_t wd = *(const uint32_t *)p;
+                if (std::is_same<T, __half>::value) {
+                    const __half2 hh = *(const __half2 *)&wd;
+                    v0 = __low2float(hh);
+                    v1 = __high2float(hh);
                 } else {
-                    const uint32_t wd = *(const uint32_t *)(p + q * 2048);
-                    if (std::is_same<T, __half>::value) {
-                        const __half2 hh = *(const __half2 *)&wd;
-                        v[2 * q] = __low2float(hh);
-                        v[2 * q + 1] = __high2float(hh);
-                    } else {
-                        v[2 * q] = __uint_as_float(wd << 16);
-                        v[2 * q + 1] = __uint_as_float(wd & 0xFFFF0000u);
-                    }
+                    v0 = __uint_as_float(wd << 16);
+                    v1 = __uint_as_float(wd & 0xFFFF0000u);
                 }
             }
         };
@@ -622,31 +742,39 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             wg_barrier();  // M
             if (work) {
                 const int row = pt.slot + (it - 1) * pt.nslots;
-                q_forward(vx, cq);
-                ring_read(it - 1, 0, vg);
+                q_forward(vx, c7, cq);
+                if (!kHalf) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) ring_read_pair(it - 1, 0, q, vg[2 * q], vg[2 * q + 1]);
+                } else {
+                    // the forward state arrives as E_12 x_12 with E_12 = the cosine of the element's layer-13
+                    // pair; the transposed cascade wants x_12 / E_12:  1 / cos^2 = 1 + tan^2, and the layer's
+                    // coefficient is -+ tan (both scales still 1)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float2 c13 = *((const float2 *)&tab[(q < 2 ? 1024 : 1536) + tid] + (q & 1));
+                        float g[2], go[2];
+                        ring_read_pair(it - 1, 0, q, g[0], g[1]);
+                        ring_read_pair(it - 1, 1, q, go[0], go[1]);
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            const int r = 2 * q + b;
+                            const float c = b ? c13.y : c13.x;
+                            vx[r] *= __builtin_fmaf(c, c, 1.0f);
+                            // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
+                            const float other12 = __builtin_fmaf(-c, g[b], go[b]);
+                            acc13[r] = __builtin_fmaf(other12, vx[r], acc13[r]);
+                            vg[r] = __builtin_fmaf(c, go[b], g[b]);
+                        }
+                        asm volatile("" ::: "memory");  // one pair at a time: keeps few values alive
+                    }
+                }
                 if (kVirt && row == pt.tail_row) {
 #pragma unroll
                     for (int r = 0; r < 8; ++r)
                         if (gap_mask & (1 << r)) vg[r] = 0.0f;
                 }
-                if (kHalf) {
-                    // the forward state arrives as E_12 x_12 with E_12 = the cosine of the element's layer-13
-                    // pair; the transposed cascade wants x_12 / E_12:  1 / cos^2 = 1 + tan^2, and the layer's
-                    // coefficient is -+ tan (both scales still 1)
-                    float go[8];
-                    ring_read(it - 1, 1, go);
-                    const float4 ca = tab[1024 + tid], cb = tab[1536 + tid];
-                    const float c13[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) {
-                        vx[r] *= __builtin_fmaf(c13[r], c13[r], 1.0f);
-                        // transposed layer 13 on g: own half kept, the other half only feeds the layer's sum
-                        const float other12 = __builtin_fmaf(-c13[r], vg[r], go[r]);
-                        acc13[r] = __builtin_fmaf(other12, vx[r], acc13[r]);
-                        vg[r] = __builtin_fmaf(c13[r], go[r], vg[r]);
-                    }
-                }
-                q_phase(vx, vg, cq, acc);
+                q_phase(vx, vg, c7, cq, acc);
                 lds_write_p2<K>(hx, aq, vx);
                 lds_write_p2<K>(hg, aq, vg);
             }
