@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the butterfly + quantisation hot path on one MI355X.
 
-A step is one pass of the whole path over the calibration/prefill batch (n = 4096, 262144 rows of
-fp16 activations, resident in HBM): plan build from theta, fused forward + INT2 quantisation
-(group 128, fp16 scales), standalone forward, standalone inverse, and the backward pass (dx, dtheta).
-`value` is rows per second through that whole step.  The `roofline` object describes the fused
-forward + quantisation kernel, the kernel the headline metric is about; `kernels` lists the same
-figures for every kernel of the step, `decode` the latency of the small-batch calls.
+A step is one pass of the metric's kernel -- the fused forward transform + INT2 quantisation (group 128, fp16
+scales) -- over the calibration/prefill batch (n = 4096, 262144 rows of fp16 activations, resident in HBM).
+`value` is rows per second through that step; `roofline` describes the same kernel against the roof that binds
+it (vector issue; the HBM figures are carried beside it, because the metric asks for them).  Further keys:
+`peaks` (what this GPU delivers on a plain copy and on a float32 FMA loop, measured in this run),
+`calibration_step` (plan build + fused quantiser + forward + inverse + backward on the same batch, every call
+timed), `decode` (latency of the small-batch calls) and the other workloads' figures.
 
 Prints one JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
 """
@@ -23,7 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-VALU_PEAK_TFLOPS = 157.3       # published fp32 vector peak (counts packed fp32 FMAs)
+VALU_PEAK_TFLOPS = 157.3       # published fp32 vector peak (counts packed fp32 FMAs: two per lane and cycle)
+# What this build can issue: 256 compute units x 64 lanes x 2.4 GHz x 2 flops, one unpacked fp32 FMA per lane
+# and cycle (packed fp32 instructions are compiled out)
+VALU_PEAK_UNPACKED_TFLOPS = 256 * 64 * 2.4e9 * 2 / 1e12
+SIMDS = 256 * 4
 
 
 def alg_bytes_per_row(op: str, n: int, heads: int, itemsize: int, bits: int = 0, group: int = 0,
@@ -102,6 +107,31 @@ def cpu_baseline(sample_rows: int):
                       f"{t_total:.1f} s of wall time on these threads"}
 
 
+def percentile(ts, q):
+    ts = sorted(ts)
+    return ts[min(len(ts) - 1, int(q * len(ts)))]
+
+
+def measured_peaks(B, torch, x, y, dev):
+    """What the GPU delivers on the two roofs, measured here: a plain copy of the 2 GiB input (library kernel,
+    16 bytes per lane) and a float32 FMA loop of independent chains (unpacked instructions, as in every kernel of
+    this library)."""
+    nbytes = x.numel() * x.element_size()
+    avg, med, _ = time_kernel(lambda: B.bq_probe_copy(x, y, nbytes), 20, 10)
+    copy_gbps = 2 * nbytes / (med * 1e-3) / 1e9
+    out = torch.empty(B.bq_probe_fma_out_floats(), dtype=torch.float32, device=dev)
+    iters = 4096
+    n_fma = B.bq_probe_fma(out, iters)
+    avg_f, med_f, _ = time_kernel(lambda: B.bq_probe_fma(out, iters), 10, 3)
+    rate = n_fma / (med_f * 1e-3)
+    return {"measured_copy_GBps": round(copy_gbps, 1), "copy_bytes": nbytes, "copy_ms": round(med, 4),
+            "measured_fma_Tlane_ops": round(rate / 1e12, 2), "fma_TFLOPps": round(2 * rate / 1e12, 1),
+            "fma_lane_ops_per_launch": n_fma, "fma_ms": round(med_f, 4),
+            # lane-FMAs per second / (SIMDs x 16 lanes per cycle) = the clock at which a SIMD would issue one wave
+            # instruction every four cycles
+            "fma_implied_clock_GHz": round(rate / (SIMDS * 16) / 1e9, 3)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,7 +139,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rows", type=int, default=262144, help="rows of the batch (default: the full workload)")
     ap.add_argument("--cpu-rows", type=int, default=786432, help="rows of the oracle's timed sample (0 = skip)")
-    ap.add_argument("--no-extra", action="store_true", help="skip the decode / per-head / n=8192 backward figures")
+    ap.add_argument("--no-extra", action="store_true", help="skip the figures of the other workloads")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also launch one plain device copy of the 2 GiB input (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -139,84 +169,81 @@ def main() -> int:
     theta = torch.from_numpy(theta_h).to(dev)
     plan = torch.empty(B.bq_plan_bytes(n, heads), dtype=torch.uint8, device=dev)
     y = torch.empty_like(x)
-    xi = torch.empty_like(x)
-    dx = torch.empty_like(x)
-    dtheta = torch.empty_like(theta)
     codes, scales = B.alloc_quant_outputs(T, n, heads, bits, group, wl.scale_dtype, dev)
     rows = B.make_rows(x, n, heads)
     quant = B.make_quant(bits, group, wl.scale_dtype)
-    ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows)), dtype=torch.uint8, device=dev)
+    B.bq_plan_build(theta, n, heads, plan)
 
-    kernels = {
-        "plan_build": lambda: B.bq_plan_build(theta, n, heads, plan),
-        "fwd_quant": lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, quant, rows),
-        "fwd": lambda: B.bq_butterfly_fwd(x, y, plan, rows),
-        "inv": lambda: B.bq_butterfly_inv(y, xi, plan, rows),
-        "bwd": lambda: B.bq_butterfly_bwd(x, dy, plan, dx, dtheta, ws, rows),
-    }
-    order = ["plan_build", "fwd_quant", "fwd", "inv", "bwd"]
+    # the measured peaks come first: they also bring the clocks up before the timed region
+    peaks = measured_peaks(B, torch, x, y, dev)
 
-    def step(events=None):
-        for name in order:
-            if events is not None:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record()
-                kernels[name]()
-                b.record()
-                events.setdefault(name, []).append((a, b))
-            else:
-                kernels[name]()
+    def step():
+        B.bq_butterfly_fwd_quant(x, plan, codes, scales, quant, rows)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = {}
+    events = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(events)
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        step()
+        b.record()
+        events.append((a, b))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ts = [a.elapsed_time(b) for a, b in events]
+    launch_ms = sum(ts) / len(ts)
 
     itemsize = 2
-    kinfo = {}
-    for name in order:
-        ts = [a.elapsed_time(b) for a, b in events[name]]
-        avg = sum(ts) / len(ts)
-        rec = {"avg_ms": round(avg, 4), "median_ms": round(sorted(ts)[len(ts) // 2], 4)}
-        if name != "plan_build":
-            bpr = alg_bytes_per_row(name, n, heads, itemsize, bits, group, 2)
-            fpr = alg_flops_per_row(name, n, heads)
-            gbs = bpr * T / (avg * 1e-3) / 1e9
-            tf = fpr * T / (avg * 1e-3) / 1e12
-            rec.update({"rows_per_s": T / (avg * 1e-3), "alg_bytes_per_row": bpr, "GBps": round(gbs, 1),
-                        "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "alg_TFLOPps": round(tf, 2),
-                        "valu_frac": round(tf / VALU_PEAK_TFLOPS, 4)})
-        kinfo[name] = rec
-
-    fq = kinfo["fwd_quant"]
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    bpr = alg_bytes_per_row("fwd_quant", n, heads, itemsize, bits, group, 2)
+    fpr = alg_flops_per_row("fwd_quant", n, heads)
+    gbs = bpr * T / (launch_ms * 1e-3) / 1e9
+    tf = fpr * T / (launch_ms * 1e-3) / 1e12
+    counters = {}
+    cpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(cpath):
         try:
-            traffic = json.load(open(tpath)).get("fwd_quant_n4096_f16_int2_g128")
+            counters = json.load(open(cpath))
         except Exception:
-            traffic = None
-    roofline = {"kernel": "fused forward + INT2 quantisation, n=4096 fp16, group 128", "bound": "hbm",
-                "achieved": fq["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fq["hbm_frac"],
-                "traffic": traffic, "launch_ms": fq["avg_ms"], "alg_bytes_per_launch": fq["alg_bytes_per_row"] * T,
-                # the same launch against the vector-ALU roof (3 n log2 n flop per row; the published fp32 peak
-                # counts packed instructions, which this build does not use)
-                "alu": {"achieved": fq["alg_TFLOPps"], "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": fq["valu_frac"]}}
+            counters = {}
+    traffic = counters.get("fwd_quant_n4096_f16_int2_g128")
+    valu_insts = counters.get("fwd_quant_n4096_f16_int2_g128_valu_wave_insts")  # SQ_INSTS_VALU of one launch
+    issue = None
+    if valu_insts:
+        # one fp32 wave instruction occupies a SIMD for four cycles: the launch cannot be shorter than this at the
+        # clock the FMA loop above ran at
+        clock = peaks["fma_implied_clock_GHz"] * 1e9
+        floor_ms = valu_insts * 4 / (SIMDS * clock) * 1e3
+        issue = {"valu_wave_insts_per_launch": valu_insts, "per_thread_row": round(valu_insts * 64 / (T * 512), 1),
+                 "issue_floor_ms": round(floor_ms, 4), "issue_frac": round(floor_ms / launch_ms, 4)}
+    hbm_frac = gbs / HBM_PEAK_GBS
+    alu_frac = tf / VALU_PEAK_TFLOPS
+    alu_frac_unpacked = tf / VALU_PEAK_UNPACKED_TFLOPS
+    # which roof binds: the one the launch is closer to, with the ALU roof taken as what this build can issue
+    bound = "alu" if max(alu_frac_unpacked, issue["issue_frac"] if issue else 0.0) > hbm_frac else "hbm"
+    roofline = {"kernel": "fused forward + INT2 quantisation, n=4096 fp16, group 128", "bound": bound,
+                "launch_ms": round(launch_ms, 4), "traffic": traffic,
+                "alg_bytes_per_launch": bpr * T, "alg_flops_per_launch": fpr * T}
+    hbm = {"achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)}
+    alu = {"achieved": round(tf, 2), "peak": VALU_PEAK_TFLOPS, "peak_published": VALU_PEAK_TFLOPS,
+           "peak_unpacked": round(VALU_PEAK_UNPACKED_TFLOPS, 1), "unit": "TFLOP/s", "frac": round(alu_frac, 4),
+           "frac_unpacked": round(alu_frac_unpacked, 4), "issue": issue}
+    roofline.update(alu if bound == "alu" else hbm)
+    roofline["hbm"] = hbm
+    roofline["alu"] = alu
 
     if args.copy_ref:
-        y.copy_(x)
+        B.bq_probe_copy(x, y, x.numel() * x.element_size())
         torch.cuda.synchronize()
     extra = {}
     if not args.no_extra:
-        extra = extra_figures(B, synth, torch, dev)
+        extra["calibration_step"] = calibration_step(B, torch, x, dy, theta, plan, y, codes, scales, quant, rows, n, heads,
+                                                     bits, group, T)
+        extra.update(extra_figures(B, synth, torch, dev))
 
     out = {
         "metric": "rows/sec + achieved HBM GB/s (% peak), butterfly fwd+quant n=4096 fp16",
@@ -226,20 +253,72 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"calibration/prefill shape: n=4096, T={T} rows, fp16 Student-t(3) activations with "
-                               "1% outlier channels x100; step = plan build + fused fwd+INT2 quant (g128, fp16 "
-                               "scales) + fwd + inv + bwd",
+                               "1% outlier channels x100; step = fused forward + INT2 quantisation (group 128, fp16 "
+                               "scales), fp16 in, float32 arithmetic",
                    "n": n, "rows": T, "io_dtype": "f16", "bits": bits, "group": group},
-        "fwd_quant_rows_per_s": fq["rows_per_s"],
-        "fwd_quant_GBps": fq["GBps"],
-        "fwd_quant_hbm_frac": fq["hbm_frac"],
+        "fwd_quant_rows_per_s": T / (launch_ms * 1e-3),
+        "fwd_quant_GBps": round(gbs, 1),
+        "fwd_quant_hbm_frac": round(hbm_frac, 4),
         "roofline": roofline,
-        "kernels": kinfo,
+        "peaks": peaks,
     }
     out.update(extra)
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_rows)
     print(json.dumps(out))
     return 0
+
+
+def calibration_step(B, torch, x, dy, theta, plan, y, codes, scales, quant, rows, n, heads, bits, group, T, steps=10):
+    """The whole path on the same batch: plan build, fused forward + INT2 quantisation, forward, inverse, backward;
+    every call timed with events, the sequence by the wall clock."""
+    xi = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    dtheta = torch.empty_like(theta)
+    ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows)), dtype=torch.uint8, device=x.device)
+    kernels = {
+        "plan_build": lambda: B.bq_plan_build(theta, n, heads, plan),
+        "fwd_quant": lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, quant, rows),
+        "fwd": lambda: B.bq_butterfly_fwd(x, y, plan, rows),
+        "inv": lambda: B.bq_butterfly_inv(y, xi, plan, rows),
+        "bwd": lambda: B.bq_butterfly_bwd(x, dy, plan, dx, dtheta, ws, rows),
+    }
+    order = ["plan_build", "fwd_quant", "fwd", "inv", "bwd"]
+    for _ in range(3):
+        for name in order:
+            kernels[name]()
+    torch.cuda.synchronize()
+    events = {}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for name in order:
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            kernels[name]()
+            b.record()
+            events.setdefault(name, []).append((a, b))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / steps
+    kinfo = {}
+    for name in order:
+        ts = [a.elapsed_time(b) for a, b in events[name]]
+        avg = sum(ts) / len(ts)
+        rec = {"avg_ms": round(avg, 4), "median_ms": round(sorted(ts)[len(ts) // 2], 4)}
+        if name != "plan_build":
+            bpr = alg_bytes_per_row(name, n, heads, 2, bits, group, 2)
+            fpr = alg_flops_per_row(name, n, heads)
+            gbs = bpr * T / (avg * 1e-3) / 1e9
+            tf = fpr * T / (avg * 1e-3) / 1e12
+            rec.update({"rows_per_s": T / (avg * 1e-3), "alg_bytes_per_row": bpr, "GBps": round(gbs, 1),
+                        "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "alg_TFLOPps": round(tf, 2),
+                        "valu_frac": round(tf / VALU_PEAK_TFLOPS, 4),
+                        "valu_frac_unpacked": round(tf / VALU_PEAK_UNPACKED_TFLOPS, 4)})
+        kinfo[name] = rec
+    kinfo["bwd"]["workspace_MiB"] = round(ws.numel() / 2 ** 20, 1)
+    return {"workload": "plan build + fused fwd+INT2 quant + fwd + inv + bwd on the n=4096, T=%d fp16 batch" % T,
+            "ms_per_step": round(ms, 4), "rows_per_s": T / (ms * 1e-3), "steps": steps, "kernels": kinfo}
 
 
 def extra_figures(B, synth, torch, dev):
@@ -251,13 +330,32 @@ def extra_figures(B, synth, torch, dev):
     plan = B.alloc_plan(theta, wl.n, 1)
     xs = synth.storage_to_torch(wl.x, wl.dtype, dev)
     dec = {}
+    cases = {}
     for T in (1, 8, 64):
         x = xs[:T].contiguous()
         codes, scales = B.alloc_quant_outputs(T, wl.n, 1, 4, 128, "f16", dev)
-        rows = B.make_rows(x, wl.n, 1)
-        q = B.make_quant(4, 128, "f16")
-        avg, med, mx = time_kernel(lambda: B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows), 200, 20)
-        dec[f"T{T}"] = {"avg_us": round(avg * 1e3, 2), "median_us": round(med * 1e3, 2), "max_us": round(mx * 1e3, 2)}
+        cases[T] = (x, codes, scales, B.make_rows(x, wl.n, 1))
+    q = B.make_quant(4, 128, "f16")
+    samples = {T: [] for T in cases}
+    for T, (x, codes, scales, rows) in cases.items():  # warm-up
+        for _ in range(50):
+            B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows)
+    # per-call latency between two events; the batch sizes take turns (five rounds of 200 calls each), so that
+    # whatever the device does between phases of the benchmark lands on all of them alike
+    for _ in range(5):
+        for T, (x, codes, scales, rows) in cases.items():
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+            for a, b in evs:
+                a.record()
+                B.bq_butterfly_fwd_quant(x, plan, codes, scales, q, rows)
+                b.record()
+            torch.cuda.synchronize()
+            samples[T] += [a.elapsed_time(b) for a, b in evs]
+    for T, (x, codes, scales, rows) in cases.items():
+        ts = samples[T]
+        dec[f"T{T}"] = {"avg_us": round(sum(ts) / len(ts) * 1e3, 2), "median_us": round(percentile(ts, 0.5) * 1e3, 2),
+                        "p99_us": round(percentile(ts, 0.99) * 1e3, 2), "max_us": round(max(ts) * 1e3, 2),
+                        "calls": len(ts)}
         # 2000 calls back to back between two events (the events of the per-call figures cost about 2 us each)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -281,9 +379,9 @@ def extra_figures(B, synth, torch, dev):
         avg_g, med_g, _ = time_kernel(graph.replay, 30, 30)
         dec[f"T{T}"]["in_graph_us"] = round(med_g * 1e3 / 32, 2)
         del graph
-    res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream; "
-                                 "back_to_back_us: 2000 calls between two events; in_graph_us: per call inside a "
-                                 "captured graph of 32 calls", **dec}
+    res["decode"] = {"workload": "n=4096 fp16 fused fwd+INT4 g128, event-timed per call on the stream (1000 calls per "
+                                 "batch size, the sizes taking turns); back_to_back_us: 2000 calls between two events; "
+                                 "in_graph_us: per call inside a captured graph of 32 calls", **dec}
     # per-head: 32 heads x n=128, T=8192, bf16, rotating over 6 buffers (> 256 MB in total)
     x4, th4, _ = synth.device_rows(4, 8192, dev)
     theta4 = torch.from_numpy(th4).to(dev)
@@ -388,15 +486,23 @@ def extra_figures(B, synth, torch, dev):
                        "fwd_quant_ms": round(a_q, 4), "fwd_quant_GBps": round(b_q * Tf / (a_q * 1e-3) / 1e9, 1),
                        "fwd_quant_hbm_frac": round(b_q * Tf / (a_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     del xf, yf, cf, sf
-    # the same forward kernel with every angle at pi/4 (a signed Hadamard transform): in the scale-deferred
-    # form a butterfly layer and a Hadamard layer both cost one FMA-class instruction per element
+    # The fixed Hadamard rotation as baseline (paper, "Inference Efficiency": the learned transform's overhead over
+    # the fast Hadamard transform): the add/sub kernel (no plan, no coefficient registers, one scale) against the
+    # butterfly kernel with learned angles on the same batch, and the butterfly kernel with every angle at pi/4.
     import math
     y3 = yq3
     a_rand, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan3, rows3), 30, 30)
+    a_fht, _, _ = time_kernel(lambda: B.bq_hadamard_fwd(x3, y3, rows3), 30, 30)
     plan_h = B.alloc_plan(torch.full_like(theta3, math.pi / 4), 4096, 1)
     a_had, _, _ = time_kernel(lambda: B.bq_butterfly_fwd(x3, y3, plan_h, rows3), 30, 30)
-    res["hadamard_angles"] = {"workload": "n=4096, T=262144, fp16 forward: learned angles vs all angles pi/4",
-                              "butterfly_ms": round(a_rand, 4), "hadamard_ms": round(a_had, 4)}
+    b_f = alg_bytes_per_row("fwd", 4096, 1, 2)
+    res["hadamard_baseline"] = {"workload": "n=4096, T=262144, fp16 forward: learned butterfly vs add/sub Hadamard "
+                                            "kernel (bq_hadamard_fwd) vs butterfly kernel with all angles pi/4",
+                                "butterfly_ms": round(a_rand, 4), "fht_ms": round(a_fht, 4),
+                                "butterfly_at_quarter_pi_ms": round(a_had, 4),
+                                "butterfly_over_fht": round(a_rand / a_fht, 4),
+                                "fht_GBps": round(b_f * T3 / (a_fht * 1e-3) / 1e9, 1),
+                                "butterfly_GBps": round(b_f * T3 / (a_rand * 1e-3) / 1e9, 1)}
     del yq3, y3
     # composite transform for a width that is not a power of two: 5120 = 40 x 128, fp16
     Tk, d1k, d2k = 65536, 40, 128

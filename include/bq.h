@@ -152,6 +152,17 @@ bq_status bq_butterfly_bwd_static(const void *x, const void *dy, const void *pla
                                   const bq_rows *rows, void *stream);
 size_t bq_butterfly_bwd_static_max_bytes(void);
 
+/* ---- fixed Hadamard rotation (the baseline the learned transform is compared with) ------------ */
+
+/* y = H_n x / sqrt(n) for every block of n elements of every row, H_n the Sylvester-ordered Walsh-Hadamard
+ * matrix (paper, "Hadamard Transform": H_2n = [[H_n, H_n], [H_n, -H_n]]; the fixed rotation of QuIP / QuaRot that
+ * the learned butterfly replaces, and the "FHT" column of the appendix "Inference FLOP Analysis").  Additions and
+ * subtractions in float32, one multiplication by 1 / sqrt(n) at the end, one rounding to rows->dtype; no plan, no
+ * angles.  H_n / sqrt(n) is symmetric and orthogonal: the same call is its own inverse.  Implemented for
+ * n = 4096 and n = 8192 (heads <= 512, 16-byte aligned pointers, leading dimensions multiples of 16 bytes);
+ * other shapes return BQ_ERR_UNSUPPORTED.  y == x (with ld_y == ld_x) is allowed. */
+bq_status bq_hadamard_fwd(const void *x, void *y, const bq_rows *rows, void *stream);
+
 /* ---- widths that are not powers of two ------------------------------------------------------ */
 
 /* Orthogonal factor for a width d = d1 * d2 with d1 not a power of two (paper, "Concrete Example for
@@ -176,6 +187,19 @@ bq_status bq_kron_fwd(const void *x, void *y, const float *q1, int32_t d1, const
 /* x = (Q1 (x) B(theta))^T y, the inverse of bq_kron_fwd; same conventions. */
 bq_status bq_kron_inv(const void *y, void *x, const float *q1, int32_t d1, const void *plan,
                       const bq_rows *rows, void *stream);
+
+/* ---- measurement helpers (not part of the method) ------------------------------------------- */
+
+/* dst[0, bytes) = src[0, bytes): a plain streaming copy (16 bytes per lane), the reference for what the memory
+ * system delivers.  Device pointers aligned to 16 bytes, bytes a multiple of 16; asynchronous on `stream`. */
+bq_status bq_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+/* A float32 FMA issue-rate loop: every lane of a fixed grid runs 16 independent chains of `iters` FMAs, in the
+ * instructions this library is built from (no packed float32).  out: device buffer of
+ * bq_probe_fma_out_floats() floats (receives one checksum per lane).  Returns the number of lane-FMAs the
+ * launch performs (2 flops each), or -1 on a bad argument or launch failure.  Asynchronous on `stream`. */
+int64_t bq_probe_fma(float *out, int32_t iters, void *stream);
+size_t bq_probe_fma_out_floats(void);
 
 /* ---- helpers ------------------------------------------------------------------------------- */
 

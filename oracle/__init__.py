@@ -16,6 +16,7 @@ import numpy as np
 
 from . import build as _build
 from .dense import dense_butterfly, dense_layer, pair_indices  # noqa: F401
+from .hadamard import hadamard  # noqa: F401
 
 _LIB = None
 

@@ -20,9 +20,10 @@ STATUS_NAMES = {0: "BQ_OK", 1: "BQ_ERR_NULL", 2: "BQ_ERR_SHAPE", 3: "BQ_ERR_DTYP
 DTYPE_CODES = {"f32": BQ_F32, "f16": BQ_F16, "bf16": BQ_BF16}
 
 EXPORTS = ["bq_plan_bytes", "bq_plan_build", "bq_butterfly_fwd", "bq_butterfly_inv", "bq_butterfly_fwd_quant",
-           "bq_butterfly_fwd_fakequant", "bq_cayley_build", "bq_kron_fwd", "bq_kron_inv",
+           "bq_butterfly_fwd_fakequant", "bq_hadamard_fwd", "bq_cayley_build", "bq_kron_fwd", "bq_kron_inv",
            "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_butterfly_bwd_static",
-           "bq_butterfly_bwd_static_max_bytes", "bq_status_string", "bq_last_error",
+           "bq_butterfly_bwd_static_max_bytes", "bq_probe_copy", "bq_probe_fma", "bq_probe_fma_out_floats",
+           "bq_status_string", "bq_last_error",
            "bq_version"]
 
 
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.argtypes = [vp, vp, vp, ctypes.POINTER(bq_rows), vp]
             f.restype = ctypes.c_int
+        L.bq_hadamard_fwd.argtypes = [vp, vp, ctypes.POINTER(bq_rows), vp]
+        L.bq_hadamard_fwd.restype = ctypes.c_int
         L.bq_butterfly_fwd_quant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
         L.bq_butterfly_fwd_fakequant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(bq_quant), ctypes.POINTER(bq_rows), vp]
         L.bq_butterfly_fwd_fakequant.restype = ctypes.c_int
@@ -79,6 +82,12 @@ def lib() -> ctypes.CDLL:
         L.bq_butterfly_bwd_static.restype = ctypes.c_int
         L.bq_butterfly_bwd_static_max_bytes.argtypes = []
         L.bq_butterfly_bwd_static_max_bytes.restype = sz
+        L.bq_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.bq_probe_copy.restype = ctypes.c_int
+        L.bq_probe_fma.argtypes = [vp, ctypes.c_int32, vp]
+        L.bq_probe_fma.restype = ctypes.c_int64
+        L.bq_probe_fma_out_floats.argtypes = []
+        L.bq_probe_fma_out_floats.restype = sz
         L.bq_status_string.argtypes = [ctypes.c_int]
         L.bq_status_string.restype = ctypes.c_char_p
         L.bq_last_error.restype = ctypes.c_char_p
@@ -151,6 +160,10 @@ def bq_butterfly_inv(y, x, plan, rows: bq_rows, stream=None) -> None:
     _check(lib().bq_butterfly_inv(_ptr(y), _ptr(x), _ptr(plan), ctypes.byref(rows), _stream_ptr(stream)))
 
 
+def bq_hadamard_fwd(x, y, rows: bq_rows, stream=None) -> None:
+    _check(lib().bq_hadamard_fwd(_ptr(x), _ptr(y), ctypes.byref(rows), _stream_ptr(stream)))
+
+
 def bq_butterfly_fwd_quant(x, plan, codes, scales, quant: bq_quant, rows: bq_rows, stream=None) -> None:
     _check(lib().bq_butterfly_fwd_quant(_ptr(x), _ptr(plan), _ptr(codes), _ptr(scales), ctypes.byref(quant),
                                         ctypes.byref(rows), _stream_ptr(stream)))
@@ -191,6 +204,22 @@ def bq_butterfly_bwd_static(x, dy, plan, dx, dtheta, rows: bq_rows, stream=None)
 
 def bq_butterfly_bwd_static_max_bytes() -> int:
     return int(lib().bq_butterfly_bwd_static_max_bytes())
+
+
+def bq_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(lib().bq_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream_ptr(stream)))
+
+
+def bq_probe_fma_out_floats() -> int:
+    return int(lib().bq_probe_fma_out_floats())
+
+
+def bq_probe_fma(out, iters: int, stream=None) -> int:
+    """Launches the FMA loop; returns the number of lane-FMAs of the launch."""
+    n = int(lib().bq_probe_fma(_ptr(out), iters, _stream_ptr(stream)))
+    if n < 0:
+        raise BqError(7, "bq_probe_fma failed")
+    return n
 
 
 def bq_version() -> int:

@@ -160,6 +160,24 @@ bq_status bq_butterfly_inv(const void *y, void *x, const void *plan, const bq_ro
     return transform(bq::kInv, y, x, plan, rows, stream, "bq_butterfly_inv");
 }
 
+bq_status bq_hadamard_fwd(const void *x, void *y, const bq_rows *rows, void *stream)
+{
+    const char *who = "bq_hadamard_fwd";
+    bq::Shape s;
+    bq_status st = check_rows(rows, &s, who);
+    if (st != BQ_OK) return st;
+    if (s.rows == 0) return ok();
+    if (!x || !y) return fail(BQ_ERR_NULL, "%s: data pointer is NULL", who);
+    if (misaligned(x, itemsize(s.dtype)) || misaligned(y, itemsize(s.dtype)))
+        return fail(BQ_ERR_ALIGN, "%s: data pointer not aligned to its element size", who);
+    if (!bq::hadamard_supported(x, y, s))
+        return fail(BQ_ERR_UNSUPPORTED, "%s: implemented for n = 4096 and 8192 with at most 512 heads, 16-byte aligned "
+                                        "pointers and leading dimensions that are multiples of 16 bytes", who);
+    hipError_t e = bq::launch_hadamard(x, y, s, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, who);
+    return ok();
+}
+
 bq_status bq_butterfly_fwd_quant(const void *x, const void *plan, uint8_t *codes, void *scales,
                                  const bq_quant *quant, const bq_rows *rows, void *stream)
 {

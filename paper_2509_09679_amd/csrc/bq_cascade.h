@@ -200,6 +200,11 @@ __device__ __forceinline__ float amax8(const float (&y)[8])
 }
 
 // kMaxGiven: group_max is the group's max |y|, formed by the caller (groups that reach beyond a 16-lane row)
+//
+// The common case is kept short: with binary16 scales, "ordinary" means that the rounded scale is a normal,
+// finite binary16 number (one range test on its bit pattern); then no clip can act (|y * inv| <= qmax (1 + 2^-10)),
+// the scale is not zero and did not saturate.  Everything else -- a zero or subnormal scale, a scale beyond
+// 65504 (which saturates), the clip -- is redone on a cold path from the same inputs.
 template <int BITS, bool kMaxGiven = false>
 __device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool scale_f16, float (&t)[8], float *scale_out,
                                         bool *ordinary_out, float group_max = -1.0f)
@@ -208,43 +213,70 @@ __device__ __forceinline__ void scaled8(const float (&y)[8], int lanes, bool sca
     constexpr float qmax = (float)((1 << (BITS - 1)) - 1);
     constexpr float qmin = -(float)(1 << (BITS - 1));
     float s, inv;
-    bool ordinary;  // scale for which |y * inv| <= qmax (1 + 2^-10): the clip cannot act
+    bool ordinary;
     if (scale_f16) {
         // qmax = 1 for INT2: the division is the identity.  For INT4, m / 7 correctly rounded with
         // three FMA-class operations (multiply by RN(1/7), exact remainder, correction); exact for
         // every normal quotient, and quotients below the binary16 range round to a zero scale anyway.
+        float s_exact;
         if (BITS == 2) {
-            s = m;
+            s_exact = m;
         } else {
             constexpr float kRcp = 1.0f / qmax;
             const float q0 = m * kRcp;
             const float rem = __builtin_fmaf(-qmax, q0, m);
-            s = __builtin_fmaf(rem, kRcp, q0);
+            s_exact = __builtin_fmaf(rem, kRcp, q0);
         }
-        const float sh = __half2float(__float2half_rn(fminf(s, 65504.0f)));
-        // binary16 rounding moves a normal scale by at most 2^-11 relative; subnormal and saturated
-        // scales can be far below amax / qmax and need the clip
-        ordinary = (sh >= 6.103515625e-05f) && (s <= 65504.0f);
-        s = sh;
+        // The quotient is pinned as a float32 value: left alone, the compiler merges its last FMA with the
+        // conversion below into one instruction that rounds the exact sum once to binary16, which differs from
+        // "float32 quotient, then one rounding" where the float32 quotient is a binary16 tie.
+        asm volatile("" : "+v"(s_exact));
+        const __half hs = __float2half_rn(s_exact);  // beyond the binary16 range: infinity
+        const uint16_t hb = __half_as_ushort(hs);
+        ordinary = (uint16_t)(hb - 0x0400u) < (uint16_t)0x7800u;  // 2^-14 <= scale <= 65504
+        s = __half2float(hs);
         inv = rcp_f16_valued(s);
+        if (__builtin_expect(!ordinary, 0)) {  // rare: saturation at 65504, zero scale
+            asm volatile("");              // (keeps this a branch: the statements must not join the common path)
+            s = __half2float(__float2half_rn(fminf(s_exact, 65504.0f)));
+            inv = (s == 0.0f) ? 0.0f : rcp_f16_valued(s);
+        }
     } else {
         s = (BITS == 2) ? m : m / qmax;
         inv = 1.0f / s;
         ordinary = s >= 0x1p-100f;
+        if (__builtin_expect(!ordinary, 0)) {
+            asm volatile("");
+            inv = (s == 0.0f) ? 0.0f : inv;
+        }
     }
-    inv = (s == 0.0f) ? 0.0f : inv;
-    *scale_out = s;
-    *ordinary_out = ordinary;
 #pragma unroll
     for (int r = 0; r < 8; ++r) t[r] = y[r] * inv;
-    if (__builtin_expect(!ordinary, 0)) {  // rare: clip before rounding (the bounds are integers)
+    if (__builtin_expect(!ordinary, 0)) {  // rare: clip before rounding (the bounds are integers, so the two commute)
 #pragma unroll
         for (int r = 0; r < 8; ++r) t[r] = __builtin_amdgcn_fmed3f(t[r], qmin, qmax);
     }
+    *scale_out = s;
+    *ordinary_out = ordinary;
 }
 
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23, bits 0x4B400000
 
+// acc = (acc << BITS) + v in one instruction (left to itself the compiler turns the chain into a tree of
+// shifts and three-operand adds, half as many instructions again)
+template <int BITS>
+__device__ __forceinline__ uint32_t shl_add(uint32_t acc, uint32_t v)
+{
+    uint32_t d;
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(d) : "v"(acc), "n"(BITS), "v"(v));
+    return d;
+}
+
+// Rounding and packing: adding 1.5 * 2^23 + 2^(BITS-1) rounds t to an integer (ties to even) and leaves
+// q + 2^(BITS-1), a non-negative BITS-bit field, in the low bits of the sum's pattern.  The 8 fields are
+// gathered with one shift-add each (no borrows between fields); the upper bits of the patterns do not reach
+// the low 16 bits (INT2) or are subtracted as one constant (INT4); the final XOR turns every field
+// q + 2^(BITS-1) into q in two's complement.
 template <int BITS, bool kMaxGiven = false>
 __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool scale_f16, float *scale_out,
                                            float group_max = -1.0f)
@@ -252,18 +284,18 @@ __device__ __forceinline__ uint32_t quant8(const float (&y)[8], int lanes, bool 
     float t[8];
     bool ordinary;
     scaled8<BITS, kMaxGiven>(y, lanes, scale_f16, t, scale_out, &ordinary, group_max);
-    uint32_t acc = 0;
+    constexpr float kBiasedMagic = kRoundMagic + (float)(1 << (BITS - 1));
+    uint32_t acc = __float_as_uint(t[7] + kBiasedMagic);
 #pragma unroll
-    for (int r = 7; r >= 0; --r) acc = (acc << BITS) + __float_as_uint(t[r] + kRoundMagic);
+    for (int r = 6; r >= 0; --r) acc = shl_add<BITS>(acc, __float_as_uint(t[r] + kBiasedMagic));
     uint32_t magic_sum = 0, bias = 0;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         magic_sum += 0x4B400000u << (r * BITS);
         bias |= (1u << (BITS - 1)) << (r * BITS);
     }
-    uint32_t packed = (acc - magic_sum + bias) ^ bias;
-    if (BITS == 2) packed &= 0xFFFFu;
-    return packed;
+    if (BITS == 2) return (acc ^ bias) & 0xFFFFu;
+    return (acc - magic_sum) ^ bias;
 }
 
 // ---- fake quantisation: Dequant(Quant(y)) and code-bin counting -----------------------------------

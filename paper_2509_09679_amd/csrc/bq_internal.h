@@ -117,7 +117,8 @@ struct QuantArgs {
 };
 
 // kFwdFake: forward + quantise + dequantise (`out` receives s * q, may be NULL) + code-bin histogram
-enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2, kFwdFake = 3 };
+// kHadamard: the fixed Walsh-Hadamard transform H_n / sqrt(n) (additions and subtractions only; no plan)
+enum Mode { kFwd = 0, kInv = 1, kFwdQuant = 2, kFwdFake = 3, kHadamard = 4 };
 
 // generic (any n) kernels: bq_generic.hip
 hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
@@ -145,6 +146,26 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
 int k12_block_rows(const Shape &s);  // launch_k12 processes floor(rows / this) * this rows, from the first
 hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, const Shape &s,
                       const QuantArgs *q, hipStream_t stream);
+
+// y = H_n x / sqrt(n) for n = 4096 and 8192 (bq_k12.hip); false if the shape or alignment is not covered
+bool hadamard_supported(const void *in, const void *out, const Shape &s);
+hipError_t launch_hadamard(const void *in, void *out, const Shape &s, hipStream_t stream);
+
+// Raises a kernel's dynamic shared-memory limit once per device instead of on every launch (the call costs
+// host time, which the small-batch calls feel).  One object per kernel instantiation.
+struct LdsLimitOnce {
+    bool done[64] = {};
+    hipError_t set(const void *kernel, size_t bytes)
+    {
+        int dev = -1;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;  // (a race between first calls repeats the same setting)
+        return e;
+    }
+};
 
 // n = 8..128 specialised kernels: bq_small.hip
 bool small_supported(Mode mode, const void *in, const void *out, const Shape &s, const QuantArgs *q);

@@ -27,6 +27,34 @@ bool k12_supported(Mode mode, const void *in, const void *out, const Shape &s, c
     return true;
 }
 
+bool hadamard_supported(const void *in, const void *out, const Shape &s)
+{
+    if (s.n != kN && s.n != 2 * kN) return false;
+    if (s.heads > 512) return false;
+    const int vec = s.dtype == BQ_F32 ? 4 : 8;  // elements per 16 bytes
+    if (((uintptr_t)in & 15) || ((uintptr_t)out & 15) || (s.ld_x % vec) || (s.ld_y % vec)) return false;
+    return true;
+}
+
+hipError_t launch_hadamard(const void *in, void *out, const Shape &s, hipStream_t stream)
+{
+    K12Args A{};
+    A.in = in;
+    A.out = out;
+    A.rows = s.rows;
+    A.ld_in = A.sub_ld_in = s.ld_x;
+    A.ld_out = A.sub_ld_out = s.ld_y;
+    A.n = s.n;
+    A.n_log = s.k;
+    A.heads = s.heads;
+    const bool wide = s.n > kN;
+    int64_t per_head = 256 / A.heads > 0 ? 256 / A.heads : 1;  // as for the forward transform: one workgroup per compute unit
+    if (per_head > A.rows) per_head = A.rows;
+    const unsigned grid = (unsigned)(per_head * A.heads);
+    if (wide) return launch_k13_dtype(kHadamard, A, 4, grid, s.dtype, stream);
+    return launch_k12_dtype<false, false>(kHadamard, A, 4, grid, s.dtype, stream);
+}
+
 int k12_block_rows(const Shape &s)
 {
     const int64_t width = (int64_t)s.n * s.heads;

@@ -311,6 +311,11 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     constexpr bool kRing32 = sizeof(T) == 4;
     float *lds = lds_raw + kHalves * (kRing32 ? 2 * kN : kFrontFloats);
     constexpr bool kInverse = (kMode == kInv);
+    // kHadamard: the same cascade with every coefficient +1 (lower element of a pair) or -1 (upper element), i.e.
+    // additions and subtractions; nothing is read from a plan.  A layer then maps (a, b) to (a + b, b - a), which
+    // is the Sylvester butterfly (a + b, a - b) up to the sign of its second output; over all layers the signs
+    // collect to (-1)^popcount(index) per output element, which the single scale 1 / sqrt(n) takes along.
+    constexpr bool kHad = (kMode == kHadamard);
     // kWide: `half` selects the half of the row; tid, wave, chunk and idx_n count inside the half
     const int half = kWide ? (int)(threadIdx.x >> 9) : 0;
     const int tid = threadIdx.x & (kThreads - 1), wave = tid >> 6, lane = tid & 63;
@@ -334,6 +339,17 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     float cn[7][8], cp[5][8];
     float cw[8];  // kWide: layer 13, in layout N (forward, phase C) or layout P (inverse, phase B)
     auto load_coefficients = [&]() {
+        if (kHad) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+#pragma unroll
+                for (int j = 0; j < 7; ++j) cn[j][r] = (((idx_n + r) >> j) & 1) ? -1.0f : 1.0f;
+#pragma unroll
+                for (int j = 0; j < 5; ++j) cp[j][r] = (((idx_p + p_reg_idx(r)) >> (7 + j)) & 1) ? -1.0f : 1.0f;
+                cw[r] = half ? -1.0f : 1.0f;
+            }
+            return;
+        }
         // tables are [head][layer][n]; kVirt: the head is the element's own (virt_head)
         const float *fg = A.fg + (kVirt ? 0 : (size_t)head * kLayers * kPoints);
         const float *fg_n = fg + (kVirt ? (size_t)virt_head(A, head, idx_n) * nk * tn : 0);
@@ -369,7 +385,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             if (kWide) asm volatile("" ::"v"(cw[r]));
         }
     }
-    if (*A.fast_bad != 0) {  // rare: plain rotations through LDS
+    if (!kHad && *A.fast_bad != 0) {  // rare: plain rotations through LDS
         const float2 *cs = A.cs + (kVirt ? 0 : (size_t)head * kLayers * (kPoints / 2));
         for (int64_t row = row_first; row < A.rows; row += row_step) {
             float u[8];
@@ -472,9 +488,15 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     float d[8];
     float *dtab = lds + (2 * kHalves + half) * kLdsRow;  // kScaleLds: the third buffer
     {
-        const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
+        if (kHad) {
+            const float scale = kWide ? 0.011048543456039806f : 0.015625f;  // 1 / sqrt(8192), 1 / sqrt(4096)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
+            for (int r = 0; r < 8; ++r) d[r] = (__builtin_popcount(col0 + idx_n + r) & 1) ? -scale : scale;
+        } else {
+            const float *fd = A.fd + (kVirt ? (size_t)virt_head(A, head, idx_n) * tn : (size_t)head * kPoints);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) d[r] = fd[((col0 + idx_n) & tmask) + r];
+        }
         if (kScaleLds) lds_write_n(dtab, an, d);  // read back by the same thread only
     }
     const int wave_row = half * 8 + wave;  // the wave's piece of a row: 512 elements, 1 KB per load
@@ -506,7 +528,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     // BB: phase B of row it-1, BC: phase C of row it-2), so that buffer offsets become immediates of the
     // LDS instructions instead of per-lane address arithmetic.  Three such steps make one turn.
     // n = 8192: whether phase B runs before phase C (see below)
-    constexpr bool kBFirst = kWide && (sizeof(T) == 2 ? (kMode == kFwd || kMode == kInv) : kMode == kFwdFake);
+    constexpr bool kBFirst = kWide && (sizeof(T) == 2 ? (kMode == kFwd || kMode == kInv || kHad) : kMode == kFwdFake);
     auto step = [&](auto BA, auto BB, auto BC, int it) {
         constexpr int ba = decltype(BA)::value, bb = decltype(BB)::value, bc = decltype(BC)::value;
         float *la = lds + (ba * kHalves + half) * kLdsRow, *lb = lds + (bb * kHalves + half) * kLdsRow;
@@ -612,7 +634,11 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     } else if (mode == kFwdQuant && (kBig || kVirt || A.group != 128 || !A.scale_f16)) {
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, V, W, G> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, V, W, G>;
     } else if constexpr (!kBig) {
-        if (mode == kFwd)
+        if constexpr (!kVirt) {
+            if (mode == kHadamard) kern = k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W>;
+        }
+        if (kern) {
+        } else if (mode == kFwd)
             kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
         else if (mode == kInv)
             kern = k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
@@ -621,7 +647,11 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     }
     if (!kern) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (kWide ? 2 : 1) * kLdsBytes;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    // one record per kernel of this instantiation of the launcher (the modes, bit widths and output choices)
+    static LdsLimitOnce once[5][2][3];
+    const int variant = mode != kFwdFake ? 0 : (A.out && A.hist) ? 0 : A.out ? 1 : 2;
+    const int general = (mode == kFwdQuant && (kBig || kVirt || A.group != 128 || !A.scale_f16)) ? 1 : 0;
+    hipError_t e = once[mode][bits == 2 ? 0 : 1][mode == kFwdQuant ? general : variant].set((const void *)kern, lds_bytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kWide ? 2 * kThreads : kThreads), lds_bytes, stream, A);
     return hipGetLastError();

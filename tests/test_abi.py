@@ -238,3 +238,17 @@ def test_bwd_static_validation():
     assert B.bq_butterfly_bwd_workspace_bytes(big) > cap
     assert call(big) == 5
     assert b"fixed scratch" in L.bq_last_error()
+
+
+def test_hadamard_validation():
+    L = B.lib()
+
+    def call(r, x=FAKE, y=FAKE):
+        return L.bq_hadamard_fwd(x, y, ctypes.byref(r), None)
+
+    assert call(_rows(rows=0, n=4096, dtype=B.BQ_F16)) == 0
+    assert call(_rows(rows=3, n=4096, dtype=B.BQ_F16), x=None) == 1
+    assert call(_rows(rows=3, n=1024, dtype=B.BQ_F16)) == 6       # only n = 4096 and 8192
+    assert call(_rows(rows=3, n=4096, dtype=B.BQ_F16, ld=4100)) == 6  # rows not 16-byte aligned
+    assert call(_rows(rows=3, n=4096, dtype=B.BQ_F32), y=FAKE + 2) == 4
+    assert call(_rows(rows=3, n=48)) == 2
