@@ -1,7 +1,12 @@
 """One calibration step of the learnable butterfly rotation on a single linear layer, built from the
-library's calls (paper, sections "Loss Function" and "Implementation Details").
+library's calls (paper, sections "Loss Function", "Uniformity Regularization" and "Implementation Details").
 
-    L_recon = || X W^T - Dequant(Quant(B X)) . Dequant(Quant(W B^T))^T ||^2      (rows of X are tokens)
+    L_recon   = || X W^T - Dequant(Quant(B X)) . Dequant(Quant(W B^T))^T ||^2      (rows of X are tokens)
+    L_uniform = D_KL(P_bins || U): P_bins the occupancy of the 2^b activation code bins, U uniform
+
+L_uniform is evaluated from the histogram the fake-quantising kernel counts in the same pass and is REPORTED beside
+L_recon; it is not differentiated (the paper does not say how a gradient passes the hard bin assignment), so the
+descent direction is that of L_recon alone.
 
 The butterfly work — B X, W B^T (the forward transform over the rows of W), both fake quantisations and both
 backward passes — runs in the HIP library; torch supplies memory, the two dense products with W (they
@@ -81,14 +86,26 @@ class ButterflyCalibrator:
         dV.scatter_add_(-1, idx, through_scale)
         return dV.reshape(rows, n)
 
-    def _bwd_scaled(self, X, dV, dtheta, rows):
-        """bq_butterfly_bwd with dV brought into the row type's range first (dtheta is linear in dV)."""
-        scale = dV.abs().max().clamp_min(1e-30)
-        B.bq_butterfly_bwd(X, (dV / scale).to(X.dtype), self.plan, None, dtheta, self._workspace(rows), rows)
-        return dtheta * scale
+    def _bwd_f32(self, X, dV, dtheta):
+        """dtheta from (X, dL/dV) with float32 rows: the gradient's entries span many orders of magnitude (the
+        term through the scale sits on one element per group), which a 16-bit row type would flush to zero."""
+        X32 = X if X.dtype == self.torch.float32 else X.float()
+        rows = B.make_rows(X32, self.n, 1)
+        B.bq_butterfly_bwd(X32, dV.contiguous(), self.plan, None, dtheta, self._workspace(rows), rows)
+        return dtheta
+
+    def uniformity_kl(self):
+        """D_KL(P_bins || U) of the activation codes of the last loss_and_grad call, from the kernel's histogram
+        (0 log 0 = 0); a 0-dim float64 tensor."""
+        torch = self.torch
+        h = self.hist.to(torch.float64)
+        p = h / h.sum().clamp_min(1.0)
+        bins = float(1 << self.act.bits)
+        return torch.where(p > 0, p * torch.log(p.clamp_min(1e-300) * bins), torch.zeros_like(p)).sum()
 
     def loss_and_grad(self, X):
-        """Returns (L_recon as a 0-dim float32 tensor, dtheta); self.hist holds the activation code bins."""
+        """Returns (L_recon as a 0-dim float32 tensor, dtheta of L_recon, L_uniform as a 0-dim float64 tensor);
+        self.hist holds the activation code bins."""
         torch = self.torch
         B.bq_plan_build(self.theta, self.n, 1, self.plan)
         rx, rw = B.make_rows(X, self.n, 1), B.make_rows(self.W, self.n, 1)
@@ -105,18 +122,21 @@ class ButterflyCalibrator:
         loss = (E * E).sum()
         dV = self._through_quantiser(V.float(), Xq32, 2.0 * (E @ Wq32), self.act)
         dWr = self._through_quantiser(Wr.float(), Wq32, 2.0 * (E.t() @ Xq32), self.wgt)
-        gx = self._bwd_scaled(X, dV, self.dth_x, rx)
-        gw = self._bwd_scaled(self.W, dWr, self.dth_w, rw)
-        return loss, gx + gw
+        gx = self._bwd_f32(X, dV, self.dth_x)
+        gw = self._bwd_f32(self.W, dWr, self.dth_w)
+        self.Xq = Xq
+        return loss, gx + gw, self.uniformity_kl()
 
     def fit(self, X, steps: int, lr: float, log=None):
         """SGD with a cosine learning-rate schedule; returns the losses seen (before each update).  The step
         is lr times the unit-norm gradient (this module's choice: the loss scale varies by orders of
         magnitude with the batch and layer size, the paper gives no learning rate)."""
         losses = []
+        self.kl_seen = []
         for t in range(steps):
-            loss, g = self.loss_and_grad(X)
+            loss, g, kl = self.loss_and_grad(X)
             losses.append(float(loss))
+            self.kl_seen.append(float(kl))
             step_lr = 0.5 * lr * (1.0 + math.cos(math.pi * t / steps))
             gn = g.norm()
             self.theta -= step_lr * g / (gn + 1e-30)

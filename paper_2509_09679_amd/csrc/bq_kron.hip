@@ -5,12 +5,19 @@
 // every row (the ordinary transform kernels on the [rows * d1, d2] view), and the kernel here mixes the
 // sub-rows:  Y[i][j] = sum_k Q1[i][k] Z[k][j].
 //
-// The mix is a small dense product (d1^2 * d2 multiply-adds per row, 40 per element for d1 = 40).  A
-// thread owns two adjacent columns j of one row and all d1 outputs of them: it reads its 2 * d1 inputs
-// (4- or 8-byte loads, contiguous across lanes, eight sub-rows ahead), keeps 2 * d1 sums in registers and
-// takes Q1 from LDS, where the workgroup put it transposed and zero-padded: every lane reads the same four
-// coefficients with one 16-byte LDS read (a broadcast), then does eight FMAs.  In place is safe: a thread
-// reads all its inputs before it writes, and no other thread touches its columns.
+// The mix is the one dense contraction of the method (d1^2 * d2 multiply-adds per row, 40 per element for
+// d1 = 40).  Two kernels here:
+//   * kron128_kernel (d2 = 128, d1 <= 40): butterflies and mix in one pass over the row.  Three wave groups
+//     pipeline a row through LDS tiles: 16 lanes per sub-row run the 128-point butterflies in registers; four
+//     waves mix the sub-rows on the matrix cores (Q1 zero-padded and resident in registers as A operands;
+//     float32 MFMA for float32 and bfloat16 rows, bfloat16 MFMA on two-way splits of both factors for
+//     binary16 rows); two waves store the result with one rounding.
+//   * mix_kernel (any other shape, after or before the ordinary transform kernels on the [rows * d1, d2] view):
+//     plain FMAs.  A thread owns two adjacent columns j of one row and all d1 outputs of them: it reads its
+//     2 * d1 inputs (4- or 8-byte loads, contiguous across lanes, eight sub-rows ahead), keeps 2 * d1 sums in
+//     registers and takes Q1 from LDS, where the workgroup put it transposed and zero-padded: every lane reads
+//     the same four coefficients with one 16-byte LDS read (a broadcast), then does eight FMAs.  In place is
+//     safe: a thread reads all its inputs before it writes, and no other thread touches its columns.
 #include <type_traits>
 
 #include "bq_cascade.h"

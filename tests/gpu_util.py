@@ -182,3 +182,76 @@ def run_fwd_fakequant(x_store, theta, n, heads, dtype, bits, group, scale_dtype,
     torch.cuda.synchronize()
     return (synth.torch_to_storage(yq, dtype) if want_y else None,
             hist.cpu().numpy().astype(np.uint64) if want_hist else None)
+
+
+# ---- the same criteria evaluated on the device (torch), for whole benchmark-size batches -------------------
+# The oracle's values are computed on the CPU as everywhere else and uploaded chunk by chunk; only the
+# comparison runs in torch on the GPU, where a pass over 10^9 elements takes milliseconds.
+
+def check_rotated_dev(y_dev, y_ref64, dtype, what=""):
+    """check_rotated for a chunk of rows that is resident on the device; y_ref64: numpy float64 [rows, w]."""
+    import torch
+
+    ref = torch.from_numpy(np.ascontiguousarray(y_ref64)).to(y_dev.device)
+    y = y_dev.to(torch.float64)
+    assert bool(torch.isfinite(y).all()), f"{what}: non-finite output"
+    d = (y - ref).abs()
+    rms = ref.pow(2).mean(dim=1, keepdim=True).sqrt()
+    etol, tol = ELEM_TOL[dtype], TOL[dtype]
+    if dtype != "f32":
+        # (torch rounds float64 to a 16-bit type through float32; a double rounding differs from the correct
+        # rounding for about one value in 2^13 of those near a tie, far below the one per cent at stake)
+        ref_r = ref.to(synth.torch_dtype(dtype)).to(torch.float64)
+        exact = float((y == ref_r).double().mean())
+        assert exact > 0.99, f"{what}: only {exact:.4f} of outputs are the correctly rounded oracle value"
+        if dtype == "bf16":
+            _, e = torch.frexp(ref_r)
+            excess = d - torch.ldexp(torch.ones_like(d), e - 9)
+            slack = 2e-5 * torch.maximum(ref.abs(), rms)
+            worst_x = float((excess / slack.clamp_min(1e-300)).max())
+            assert worst_x <= 1.0, f"{what}: {worst_x:.2f} x the allowed excess over a correct rounding"
+    worst = float((d / (etol * torch.maximum(ref.abs(), rms)).clamp_min(1e-300)).max())
+    assert worst <= 1.0, f"{what}: element error {worst:.3f} x the bound"
+    if dtype != "bf16":
+        rn = torch.linalg.vector_norm(d, dim=1)
+        ref_n = torch.linalg.vector_norm(ref, dim=1)
+        assert bool((rn <= tol * ref_n + 1e-300).all()), f"{what}: row-norm error"
+    return worst
+
+
+def check_fused_codes_dev(codes_dev, scales_dev, y_ref64, bits, group, scale_dtype, in_dtype, what=""):
+    """check_fused_codes for a chunk of rows whose packed codes and scales are resident on the device."""
+    import torch
+
+    dev = codes_dev.device
+    qmax = 2 ** (bits - 1) - 1
+    rows, w = y_ref64.shape
+    ref_codes, ref_scales = oracle.quantize(y_ref64.astype(np.float32), group, bits, scale_dtype)  # the oracle, on the CPU
+    ref = torch.from_numpy(np.ascontiguousarray(y_ref64)).to(dev)
+    rc = torch.from_numpy(np.ascontiguousarray(ref_codes)).to(dev).to(torch.float64)
+    s_ref = torch.from_numpy(np.ascontiguousarray(ref_scales.astype(np.float64))).to(dev)
+    # unpack: two's-complement fields, lowest channel in the lowest bits
+    per = 8 // bits
+    b = codes_dev.to(torch.int32).unsqueeze(-1)
+    sh = torch.arange(per, device=dev, dtype=torch.int32) * bits
+    f = (b >> sh) & ((1 << bits) - 1)
+    q = torch.where(f >= (1 << (bits - 1)), f - (1 << bits), f).reshape(rows, w).to(torch.float64)
+    tol_rot = 1e-5 if in_dtype == "f32" else 2e-5
+    rms = ref.pow(2).mean(dim=1, keepdim=True).sqrt()
+    amax = ref.reshape(rows, -1, group).abs().amax(dim=2)
+    s_gpu = scales_dev.to(torch.float64)
+    ulp = 2.0 ** -10 if scale_dtype == "f16" else 2.0 ** -22
+    slack = tol_rot * torch.maximum(amax, rms) / qmax
+    assert bool(((s_gpu - s_ref).abs() <= s_ref * ulp + slack + 1e-30).all()), f"{what}: scales differ"
+    assert float(q.abs().max()) <= qmax + (1 if scale_dtype == "f16" else 0)
+    sg = s_gpu.repeat_interleave(group, dim=1)
+    zero = sg == 0
+    sg1 = torch.where(zero, torch.ones_like(sg), sg)
+    t = torch.where(zero, torch.zeros_like(ref), ref / sg1)
+    delta = tol_rot * torch.maximum(ref.abs(), rms) / sg1 + 1e-6 * t.abs() + 1e-9
+    bad = (t.clamp(-(qmax + 1), qmax) - q).abs() > 0.5 + delta
+    assert not bool(bad.any()), f"{what}: {int(bad.sum())} codes are not a valid rounding"
+    same_scale = (s_gpu == s_ref).repeat_interleave(group, dim=1)
+    agree = float((q == rc)[same_scale].double().mean()) if bool(same_scale.any()) else 1.0
+    assert agree > 0.999, f"{what}: only {agree:.5f} of codes equal the oracle's"
+    return agree

@@ -25,15 +25,15 @@ def _through_quantiser(v, vq, g, bits, group):
     return dv
 
 
-def _oracle_step(X, W, theta, n, act, wgt):
-    """L_recon and dtheta with the oracle: float64 throughout, except the quantiser, which is float32 by
-    definition."""
+def _oracle_step(X, W, theta, n, act, wgt, Xq_given=None, Wq_given=None):
+    """L_recon, dtheta and the code-bin histogram with the oracle: float64 throughout, except the quantiser, which
+    is float32 by definition.  Xq_given / Wq_given replace the oracle's own fake-quantised values (see the test)."""
     Xr = oracle.forward(X, theta, n)
     Wr = oracle.forward(W, theta, n)
     qx, sx = oracle.quantize(Xr.astype(np.float32), act[1], act[0], act[2])
     qw, sw = oracle.quantize(Wr.astype(np.float32), wgt[1], wgt[0], wgt[2])
-    Xq = oracle.dequantize(qx, sx, act[1]).astype(np.float64)
-    Wq = oracle.dequantize(qw, sw, wgt[1]).astype(np.float64)
+    Xq = oracle.dequantize(qx, sx, act[1]).astype(np.float64) if Xq_given is None else Xq_given
+    Wq = oracle.dequantize(qw, sw, wgt[1]).astype(np.float64) if Wq_given is None else Wq_given
     E = Xq @ Wq.T - X @ W.T
     loss = float((E * E).sum())
     _, dth_x, _ = oracle.backward(X, _through_quantiser(Xr, Xq, 2.0 * E @ Wq, act[0], act[1]), theta, n)
@@ -72,16 +72,38 @@ def test_step_matches_the_oracle(n, m, T, dtype):
     dev = "cuda:0"
     cal = ButterflyCalibrator(synth.storage_to_torch(Wn, dtype, dev), QuantSpec(*act), QuantSpec(*wgt),
                               theta=torch.from_numpy(theta).to(dev))
-    loss, g = cal.loss_and_grad(synth.storage_to_torch(X, dtype, dev))
+    loss, g, kl = cal.loss_and_grad(synth.storage_to_torch(X, dtype, dev))
     torch.cuda.synchronize()
-    ref_loss, ref_g, ref_hist = _oracle_step(synth.to_f64(X, dtype), synth.to_f64(Wn, dtype), theta, n, act, wgt)
-    # a handful of codes may sit on a rounding boundary and differ: loose bounds on loss and gradient, tight on
-    # the histogram's total
-    assert abs(float(loss) - ref_loss) <= 2e-2 * ref_loss
-    gd = g.cpu().numpy().astype(np.float64) - ref_g
-    assert np.linalg.norm(gd) <= 5e-2 * np.linalg.norm(ref_g)
+    X64, W64 = synth.to_f64(X, dtype), synth.to_f64(Wn, dtype)
+    ref_loss, ref_g, ref_hist = _oracle_step(X64, W64, theta, n, act, wgt)
+    # The GPU's rotation differs from the oracle's in the last float32 bits, so a few values that sit on a rounding
+    # boundary get the neighbouring code (each of them a valid rounding: tests/test_gpu_parity.py).  Counted here:
+    Xq_gpu = cal.Xq.double().cpu().numpy()
+    Wq_gpu = cal.Wq.double().cpu().numpy()
+    Xq_ref = oracle.dequantize(*oracle.quantize(oracle.forward(X64, theta, n).astype(np.float32), act[1], act[0], act[2]),
+                               act[1]).astype(np.float64)
+    Wq_ref = oracle.dequantize(*oracle.quantize(oracle.forward(W64, theta, n).astype(np.float32), wgt[1], wgt[0], wgt[2]),
+                               wgt[1]).astype(np.float64)
+    differ = int((np.abs(Xq_gpu - Xq_ref) > 1e-4 * np.abs(Xq_ref).max()).sum() +
+                 (np.abs(Wq_gpu - Wq_ref) > 1e-4 * np.abs(Wq_ref).max()).sum())
+    assert differ <= 1e-3 * (T * n + m * n), differ
+    # With the fake-quantised values the GPU actually produced, the rest of the step -- error matrix, loss, the
+    # gradient rule through the quantiser, both backward passes -- must agree with the oracle's arithmetic in
+    # double to float32 accuracy; what the `differ` codes move is then no longer part of the comparison.
+    same_loss, same_g, _ = _oracle_step(X64, W64, theta, n, act, wgt, Xq_given=Xq_gpu, Wq_given=Wq_gpu)
+    assert abs(float(loss) - same_loss) <= 1e-4 * same_loss, (float(loss), same_loss, differ)
+    gd = g.cpu().numpy().astype(np.float64) - same_g
+    assert np.linalg.norm(gd) <= 1e-3 * np.linalg.norm(same_g), (np.linalg.norm(gd) / np.linalg.norm(same_g), differ)
+    # and with the oracle's own codes the loss moves by no more than those codes can move it:
+    # |L - L'| <= (2 |E| + |dE|) |dE| with dE the change of the error matrix
+    dE = Xq_gpu @ Wq_gpu.T - Xq_ref @ Wq_ref.T
+    nE = np.sqrt(ref_loss)
+    assert abs(same_loss - ref_loss) <= (2 * nE + np.linalg.norm(dE)) * np.linalg.norm(dE) * (1 + 1e-9) + 1e-12 * ref_loss
     h = cal.hist.cpu().numpy().astype(np.int64)
-    assert h.sum() == T * n and np.abs(h - ref_hist.astype(np.int64)).sum() <= 1e-3 * T * n + 4
+    assert h.sum() == T * n and np.abs(h - ref_hist.astype(np.int64)).sum() <= 2 * differ
+    # L_uniform from the kernel's histogram = the oracle's KL on the same counts, and close to the oracle's own
+    assert abs(float(kl) - oracle.uniformity_kl(h.astype(np.uint64), act[0])) <= 1e-12
+    assert abs(float(kl) - oracle.uniformity_kl(ref_hist, act[0])) <= 1e-2 * max(1e-3, oracle.uniformity_kl(ref_hist, act[0])) + 8.0 * differ / (T * n)
 
 
 @gpu
@@ -98,7 +120,8 @@ def test_sgd_from_identity_lowers_the_reconstruction_loss():
     # identity is a stationary point by symmetry (theta -> -theta), so the first steps wander before the loss falls
     losses = cal.fit(Xd, steps=100, lr=1.0)
     torch.cuda.synchronize()
-    final, _ = cal.loss_and_grad(Xd)
+    final, _, kl = cal.loss_and_grad(Xd)
+    assert np.isfinite(cal.kl_seen).all() and float(kl) >= 0.0
     assert np.isfinite(losses).all()
     assert float(final) < 0.85 * losses[0], (losses[0], float(final))
     # theta moved away from the identity and the transform is still orthogonal: norms are preserved

@@ -64,6 +64,39 @@ def test_workload3_full_size_fused_forward_inverse():
     assert torch.all((nx - ny).abs() <= 2e-3 * nx)
 
 
+def test_workload3_every_row_against_the_oracle():
+    """The whole calibration batch, every element: forward, inverse, INT2 and INT4 codes and scales.  The oracle runs
+    on the CPU chunk by chunk; the comparisons (the criteria of gpu_util.check_rotated / check_fused_codes) run in
+    torch on the device."""
+    cfg, T, chunk = 3, 262144, 16384
+    x, th, _ = synth.device_rows(cfg, T, DEV)
+    wl = synth.make_workload(cfg, rows=1)
+    n, dtype = wl.n, wl.dtype
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, 1)
+    rows = B.make_rows(x, n, 1)
+    y, xi = torch.empty_like(x), torch.empty_like(x)
+    B.bq_butterfly_fwd(x, y, plan, rows)
+    B.bq_butterfly_inv(y, xi, plan, rows)
+    out = {}
+    for bits in (2, 4):
+        out[bits] = B.alloc_quant_outputs(T, n, 1, bits, 128, "f16", DEV)
+        B.bq_butterfly_fwd_quant(x, plan, out[bits][0], out[bits][1], B.make_quant(bits, 128, "f16"), rows)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for r0 in range(0, T, chunk):
+        sl = slice(r0, r0 + chunk)
+        x64 = synth.to_f64(synth.torch_to_storage(x[sl], dtype), dtype)
+        y_ref = oracle.forward(x64, th, n)
+        worst = max(worst, gu.check_rotated_dev(y[sl], y_ref, dtype, f"c3 rows {r0}.. fwd"))
+        for bits in (2, 4):
+            gu.check_fused_codes_dev(out[bits][0][sl], out[bits][1][sl], y_ref, bits, 128, "f16", dtype, f"c3 rows {r0}.. int{bits}")
+        # the inverse is checked on what the forward kernel actually stored
+        y64 = synth.to_f64(synth.torch_to_storage(y[sl], dtype), dtype)
+        gu.check_rotated_dev(xi[sl], oracle.inverse(y64, th, n), dtype, f"c3 rows {r0}.. inv")
+    assert worst > 0.0
+
+
 def test_workload4_full_size_per_head_quant():
     cfg, T = 4, 8192
     x, th, _ = synth.device_rows(cfg, T, DEV)
@@ -107,10 +140,9 @@ def test_backward_full_size(cfg, T):
     B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
     torch.cuda.synchronize()
     del ws
-    pick = _sample_rows(T, 48, 2)
-    gs = synth.torch_to_storage(dy[torch.as_tensor(pick, device=DEV)], dtype)
-    dxs = synth.torch_to_storage(dx[torch.as_tensor(pick, device=DEV)], dtype)
-    gu.check_rotated(dxs, oracle.inverse(synth.to_f64(gs, dtype), th, n), dtype, f"cfg {cfg} full dx")
+    for r0 in range(0, T, 16384):  # dx of every row (the comparison itself runs on the device)
+        g64 = synth.to_f64(synth.torch_to_storage(dy[r0:r0 + 16384], dtype), dtype)
+        gu.check_rotated_dev(dx[r0:r0 + 16384], oracle.inverse(g64, th, n), dtype, f"cfg {cfg} full dx rows {r0}..")
     ref, ab = _oracle_dtheta_in_chunks(x, dy, th, n, dtype)
     gu.check_dtheta(dth.cpu().numpy(), ref, ab, what=f"cfg {cfg} full dtheta")
 

@@ -112,3 +112,58 @@ def test_output_form_of_the_angle_gradient():
     y = oracle.forward(x, th, 2)
     _, dth, _ = oracle.backward(x, dy, th, 2)
     assert abs(dth[0, 0, 0] - (dy[0, 1] * y[0, 0] - dy[0, 0] * y[0, 1])) < 1e-15
+
+
+def _plain_float32_backward(x, dy, theta, n, heads):
+    """dtheta with every operation in float32: (cos, sin) rounded to float32, all layer outputs kept, the printed
+    derivative's pair expression summed over the rows, transposed layers on the gradient."""
+    k = theta.shape[1]
+    dth = np.zeros(theta.shape, np.float32)
+    e = np.arange(n)
+    for h in range(heads):
+        c = np.cos(theta[h].astype(np.float64)).astype(np.float32)
+        s = np.sin(theta[h].astype(np.float64)).astype(np.float32)
+        xs = [x[:, h * n:(h + 1) * n].astype(np.float32)]
+        for i in range(1, k + 1):
+            st = 1 << (i - 1)
+            a = e[(e & st) == 0]
+            b = a | st
+            p = ((a >> i) << (i - 1)) | (a & (st - 1))
+            cur, nxt = xs[-1], np.empty_like(xs[-1])
+            nxt[:, a] = c[i - 1][p] * cur[:, a] - s[i - 1][p] * cur[:, b]
+            nxt[:, b] = s[i - 1][p] * cur[:, a] + c[i - 1][p] * cur[:, b]
+            xs.append(nxt)
+        g = dy[:, h * n:(h + 1) * n].astype(np.float32)
+        for i in range(k, 0, -1):
+            st = 1 << (i - 1)
+            a = e[(e & st) == 0]
+            b = a | st
+            p = ((a >> i) << (i - 1)) | (a & (st - 1))
+            acc = np.zeros(n // 2, np.float32)
+            for r in range(x.shape[0]):
+                acc += g[r, b] * xs[i][r, a] - g[r, a] * xs[i][r, b]
+            dth[h, i - 1][p] = acc
+            ng = np.empty_like(g)
+            ng[:, a] = c[i - 1][p] * g[:, a] + s[i - 1][p] * g[:, b]
+            ng[:, b] = -s[i - 1][p] * g[:, a] + c[i - 1][p] * g[:, b]
+            g = ng
+    return dth
+
+
+def test_a_plain_float32_backward_misses_the_per_angle_bound_on_a_single_row():
+    # Why the seeded GPU sweep floors the per-angle bound at the layer's median for batches of fewer than 32 rows:
+    # with one row there is no averaging, an angle whose own two products nearly cancel still carries the float32
+    # rounding of the ordinary-sized elements of its layer, and ANY float32 implementation then exceeds
+    # 1e-5 x (sum of the absolute products of that angle) on some angle, while it stays far inside the floored
+    # bound and inside the norm-wise bound.  (One of the sweep's own cases: n = 512, two heads, one bfloat16 row.)
+    from paper_2509_09679_amd import synth
+
+    n, heads, rows, dtype, seed = 512, 2, 1, "bf16", 2248
+    x, th, dy = synth.small_case(n, rows, dtype, heads=heads, seed=seed, with_dy=True, outliers=0)
+    x64, g64 = synth.to_f64(x, dtype), synth.to_f64(dy, dtype)
+    _, ref, ab = oracle.backward(x64, g64, th, n, heads)
+    d = np.abs(_plain_float32_backward(x64, g64, th, n, heads).astype(np.float64) - ref)
+    assert (d / np.maximum(1e-5 * ab, 1e-300)).max() > 1.0          # the unfloored per-angle bound is missed
+    floor = np.median(ab, axis=2, keepdims=True)
+    assert (d / (1e-5 * np.maximum(ab, floor))).max() < 0.5         # the floored one is met with room
+    assert np.linalg.norm(d) < 0.5 * 1e-5 * np.linalg.norm(ab)      # and so is the norm-wise one
