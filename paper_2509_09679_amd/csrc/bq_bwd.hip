@@ -344,15 +344,30 @@ __device__ __forceinline__ void n_phase6(float (&vx)[8], float (&vg)[8], const f
     reg_acc<0>(acc.r[0], vg, vx);  // layer 1 (x is not needed below it)
     reg_layer<0>(vg, cn[0]);
 }
-// layers 1..6 forward on w held in layout N
-__device__ __forceinline__ void n_forward(float (&w)[8], const float (&cn)[6][8])
+// layers 1..6 forward on w held in layout N.  kParked: the partner lane's coefficients of layers 4..6 come from the
+// thread's LDS slots (float4 slots first + 1024 j and first + 1024 j + 512 for layer 4 + j).
+template <bool kParked>
+__device__ __forceinline__ void n_forward(float (&w)[8], const float (&cn)[6][8], const float4 *tab, int first)
 {
     reg_layer_swapped<0>(w, cn[0]);
     reg_layer_swapped<1>(w, cn[1]);
     reg_layer_swapped<2>(w, cn[2]);
-    dpp_fwd_xor1(w, cn[3]);
-    dpp_fwd_xor2(w, cn[4]);
-    dpp_fwd_xor7(w, cn[5]);
+    if (!kParked) {
+        dpp_fwd_xor1(w, cn[3]);
+        dpp_fwd_xor2(w, cn[4]);
+        dpp_fwd_xor7(w, cn[5]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            int f = first + 1024 * j;
+            asm volatile("" : "+v"(f));  // keeps the reads inside the row loop (hoisted, they would occupy registers)
+            const float4 a = tab[f], b = tab[f + 512];
+            const float c[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            if (j == 0) dpp_layer_xor1(w, c);
+            if (j == 1) dpp_layer_xor2(w, c);
+            if (j == 2) dpp_layer_xor7(w, c);
+        }
+    }
 }
 
 // fw_inv entry (scale before transposed layer i) of block element e; rmask != 0: the tables of e's own head
@@ -469,8 +484,13 @@ struct FusedLds {
     static constexpr size_t kXRingBytes = kXRing ? 2 * (size_t)kXSlotBytes : 0;
     // n = 8192 with 16-bit rows: group Q is short of registers and parks the coefficients of layer 7 in LDS
     static constexpr bool kPark7 = kHalf && sizeof(T) == 2;
-    // per-thread tables: E_0 (group N); n = 8192: the layer-13 coefficients (group Q); kPark7: layer 7 (group Q)
-    static constexpr int kTabFloats = (kHalf ? (kPark7 ? 3 : 2) : 1) * G::n;
+    // n <= 4096 with 16-bit rows: LDS has room for the PARTNER's coefficients of group N's three lane layers, with
+    // which the forward recomputation of those layers costs one DPP FMA per element instead of a multiplication
+    // and a DPP addition
+    static constexpr bool kParkFwd = !kHalf && sizeof(T) == 2;
+    // per-thread tables: E_0 (group N); n = 8192: the layer-13 coefficients (group Q); kPark7: layer 7 (group Q);
+    // kParkFwd: three layers of partner coefficients (group N)
+    static constexpr int kTabFloats = (kHalf ? (kPark7 ? 3 : 2) : kParkFwd ? 4 : 1) * G::n;
     // The rings come first: the LDS address of a direct global->LDS load travels in M0, and the rings' addresses
     // stay below 64 KB this way whatever the field's width.
     static constexpr size_t kRingBytes = kDyRingBytes + kXRingBytes;
@@ -518,6 +538,16 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
             const float *e0 = A.fd_inv + (size_t)pt.head(idx_n) * ts + pt.col(idx_n);
             tab[tid] = *(const float4 *)e0;
             tab[512 + tid] = *(const float4 *)(e0 + 4);
+        }
+        if (L::kParkFwd) {
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                float pc[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) pc[r] = lane_partner(cn[3 + j][r], j);
+                tab[1024 + 1024 * j + tid] = make_float4(pc[0], pc[1], pc[2], pc[3]);
+                tab[1024 + 1024 * j + 512 + tid] = make_float4(pc[4], pc[5], pc[6], pc[7]);
+            }
         }
         // The empty statements consume the loaded coefficients: the waits for these loads then sit here and not,
         // as waits for everything outstanding, inside the row loop.
@@ -619,7 +649,7 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
                 const float4 da = tab[tid], db = tab[512 + tid];
                 w[0] *= da.x; w[1] *= da.y; w[2] *= da.z; w[3] *= da.w;
                 w[4] *= db.x; w[5] *= db.y; w[6] *= db.z; w[7] *= db.w;
-                n_forward(w, cn);
+                n_forward<L::kParkFwd>(w, cn, tab, 1024 + tid);
                 lds_write_n2(xa, an, w);
             }
             wg_barrier();  // E
