@@ -85,7 +85,14 @@ size_t bq_plan_bytes(int32_t n, int32_t heads);
  * float32) into `plan`, a caller-owned device buffer of at least bq_plan_bytes(n, heads) bytes,
  * aligned to 256 bytes.  Asynchronous on `stream`; call it again whenever theta changes.  The plan's
  * layout is private to the library.  cos/sin are evaluated in double from the float32 angle and
- * rounded once. */
+ * rounded once.
+ * The plan records the (n, heads) it was built for.  The calls below cannot read it on the host without
+ * a synchronisation, so their kernels compare it with the call's shape on the device, before the first
+ * table access: given a buffer that bq_plan_build has not filled for exactly this (n, heads) (never
+ * built, or built for another shape) they return at once, nothing is read beyond the plan's header,
+ * the call still returns BQ_OK and its outputs keep their previous contents (bq_butterfly_fwd_fakequant:
+ * hist is set to zero; bq_kron_*: the output is unspecified where the mix with q1 runs as a pass of
+ * its own).  The buffer must in every case be readable for its first 256 bytes. */
 bq_status bq_plan_build(const float *theta, int32_t n, int32_t heads, void *plan, size_t plan_bytes,
                         void *stream);
 

@@ -102,6 +102,7 @@ struct BwdFastArgs {
     float *partial;  // [slices][slice_floats]
     const float *fg_inv, *fd_inv, *fw_inv;  // plan tables of the transposed cascade
     const int *bad_fwd, *bad_inv;
+    PlanRef plan;
     int64_t row0, rows;  // this chunk: rows [row0, row0 + rows) of the batch
     int64_t ld_in, ld_out;
     int64_t slice_floats;
@@ -115,7 +116,11 @@ struct BwdFastArgs {
     int64_t sub_ld_in, sub_ld_out, total_rows;
 };
 
-__device__ __forceinline__ bool plan_is_bad(const BwdFastArgs &A) { return (*A.bad_fwd | *A.bad_inv) != 0; }
+// true: this kernel must not run (tables flagged unusable, or not a plan of this shape at all)
+__device__ __forceinline__ bool plan_is_bad(const BwdFastArgs &A)
+{
+    return !plan_matches(A.plan) || (*A.bad_fwd | *A.bad_inv) != 0;
+}
 
 constexpr int K = 12;  // layers inside one 4096-point block
 using G = Geo<K>;
@@ -839,10 +844,9 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
 // one), in double, slice order; skipped for flagged plans
 template <typename Out>
 __global__ void bwd_reduce_kernel(const float *__restrict__ partial, Out *__restrict__ out, size_t n_angles,
-                                  size_t slice_floats, size_t last_layer_at, int n_parts, const int *bad_fwd,
-                                  const int *bad_inv)
+                                  size_t slice_floats, size_t last_layer_at, int n_parts, PlanRef plan)
 {
-    if ((*bad_fwd | *bad_inv) != 0) return;
+    if (!plan_fast_both(plan)) return;
     const size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= n_angles) return;
     const size_t extra = slice_floats - n_angles;  // 0, or the number of angles of the last layer
@@ -858,9 +862,9 @@ __global__ void bwd_reduce_kernel(const float *__restrict__ partial, Out *__rest
 // n < 4096: the sums of a 4096-point block hold, per layer, the block's rows side by side, each with its `heads`
 // transforms; dtheta[h][i][p] = sum over the rows, in row order
 __global__ void bwd_fold_kernel(const double *__restrict__ sums, float *__restrict__ dtheta, int n_log, int heads,
-                                const int *bad_fwd, const int *bad_inv)
+                                PlanRef plan)
 {
-    if ((*bad_fwd | *bad_inv) != 0) return;
+    if (!plan_fast_both(plan)) return;
     const int half = 1 << (n_log - 1);
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= heads * n_log * half) return;
@@ -954,15 +958,15 @@ static hipError_t launch_bwd_fast_t(BwdFastArgs A, const Shape &s, float *dtheta
     if (kVirt) {
         const size_t sums = (size_t)s.k * (G::n / 2);  // the layers the transform has
         hipLaunchKernelGGL(bwd_reduce_kernel<double>, dim3((unsigned)((sums + 255) / 256)), dim3(256), 0, stream,
-                           (const float *)ws, fold, sums, (size_t)A.slice_floats, sums, slices, A.bad_fwd, A.bad_inv);
+                           (const float *)ws, fold, sums, (size_t)A.slice_floats, sums, slices, A.plan);
         const unsigned angles = (unsigned)(s.heads * s.k * (s.n / 2));
         hipLaunchKernelGGL(bwd_fold_kernel, dim3((angles + 255) / 256), dim3(256), 0, stream, (const double *)fold, dtheta, s.k,
-                           s.heads, A.bad_fwd, A.bad_inv);
+                           s.heads, A.plan);
     } else {
         const size_t angles = (size_t)s.k * (s.n / 2);
         hipLaunchKernelGGL(bwd_reduce_kernel<float>, dim3((unsigned)((angles + 255) / 256)), dim3(256), 0, stream,
                            (const float *)ws, dtheta, angles, (size_t)A.slice_floats, (size_t)(s.k - 1) * (s.n / 2), slices,
-                           A.bad_fwd, A.bad_inv);
+                           A.plan);
     }
     return hipGetLastError();
 }
@@ -989,6 +993,7 @@ hipError_t launch_bwd_fast(const void *x, const void *dy, const PlanView &pv, vo
     A.fw_inv = pv.fw_inv;
     A.bad_fwd = &pv.hdr->fast_bad_fwd;
     A.bad_inv = &pv.hdr->fast_bad_inv;
+    A.plan = pv.ref;
     A.n = s.n;
     A.n_log = s.k;
     A.heads = s.heads;

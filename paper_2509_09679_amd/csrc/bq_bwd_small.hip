@@ -29,6 +29,7 @@ struct SmallBwdArgs {
     float *partial;  // [slots][n_angles]
     const float *fg_fwd, *fd_fwd, *fg_inv, *fd_inv, *fw_inv;
     const int *bad_fwd, *bad_inv;
+    PlanRef plan;
     int64_t rows, ld_in, ld_out;
     int heads, width;    // width = heads * n
     int span;            // elements covered by a workgroup: 2048, or the largest power of two below it that
@@ -43,7 +44,7 @@ template <typename T, int K, bool kDx>
 __global__ __launch_bounds__(kSbThreads) void small_bwd_kernel(SmallBwdArgs A)
 {
     constexpr int n = 1 << K;
-    if ((*A.bad_fwd | *A.bad_inv) != 0) return;
+    if (!plan_matches(A.plan) || (*A.bad_fwd | *A.bad_inv) != 0) return;
     const int tid = threadIdx.x;
     const int chunk = (tid & ~15) | lane_chunk(tid & 15);  // chunk of 8 elements inside the workgroup's span
     const int e0 = chunk * 8;
@@ -158,10 +159,9 @@ __global__ __launch_bounds__(kSbThreads) void small_bwd_kernel(SmallBwdArgs A)
 // dtheta[q] = sum over slots of partial[slot][q], in double: a workgroup takes 32 angles, its 8 groups of 32
 // threads take every eighth slot each and their sums are added in group order.
 __global__ __launch_bounds__(256) void small_bwd_reduce_kernel(const float *__restrict__ partial, float *__restrict__ dtheta,
-                                                               int64_t n_angles, int64_t slots, const int *bad_fwd,
-                                                               const int *bad_inv)
+                                                               int64_t n_angles, int64_t slots, PlanRef plan)
 {
-    if ((*bad_fwd | *bad_inv) != 0) return;
+    if (!plan_fast_both(plan)) return;
     __shared__ double sums[8][32];
     const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
     const int64_t q = (int64_t)blockIdx.x * 32 + lane;
@@ -259,6 +259,7 @@ hipError_t launch_small_bwd(const void *x, const void *dy, const PlanView &pv, v
     A.fw_inv = pv.fw_inv;
     A.bad_fwd = &pv.hdr->fast_bad_fwd;
     A.bad_inv = &pv.hdr->fast_bad_inv;
+    A.plan = pv.ref;
     A.rows = s.rows;
     A.ld_in = s.ld_x;
     A.ld_out = s.ld_y;
@@ -276,7 +277,7 @@ hipError_t launch_small_bwd(const void *x, const void *dy, const PlanView &pv, v
     }
     const unsigned blocks = (unsigned)((A.n_angles + 31) / 32);
     hipLaunchKernelGGL(small_bwd_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta, A.n_angles,
-                       g.slots, A.bad_fwd, A.bad_inv);
+                       g.slots, A.plan);
     return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ struct GenArgs {
     const void *in;
     void *out;
     const float2 *cs;
+    PlanRef plan;
     int64_t rows, ld_in, ld_out;
     int n, heads, k;
     int tile_elems;  // U * n
@@ -63,6 +64,7 @@ template <typename T, int kMode>
 __global__ __launch_bounds__(kGenThreads) void generic_kernel(GenArgs A)
 {
     extern __shared__ float lds[];
+    if (!plan_matches(A.plan)) return;
     float *buf = lds;
     float *inv_lds = lds + A.tile_elems;  // one reciprocal scale per group of the tile
     float *s_lds = inv_lds + A.tile_elems / (A.group > 0 ? A.group : 1);  // kFwdFake: the scales themselves
@@ -199,6 +201,7 @@ hipError_t launch_generic(Mode mode, const void *in, void *out, const PlanView &
     A.in = in;
     A.out = out;
     A.cs = pv.cs;
+    A.plan = pv.ref;
     A.rows = s.rows;
     A.ld_in = s.ld_x;
     A.ld_out = s.ld_y;
@@ -255,14 +258,15 @@ struct BwdArgs {
     int64_t rows, ld_in, ld_out;
     int n, heads, k, rows_per_tile;
     int64_t n_tiles;
-    const int *bad_a, *bad_b;  // if not NULL: run only when one of the flags is set
+    PlanRef plan;
+    int only_if_bad;  // != 0: run only when one of the plan's table sets is flagged unusable
 };
 
 template <typename T>
 __global__ __launch_bounds__(kGenThreads) void generic_bwd_kernel(BwdArgs A)
 {
     extern __shared__ float lds[];
-    if (A.bad_a && (*A.bad_a | *A.bad_b) == 0) return;
+    if (!plan_matches(A.plan) || (A.only_if_bad && plan_fast_both(A.plan))) return;
     const int n = A.n, k = A.k, heads = A.heads, U = A.rows_per_tile;
     float *xb = lds;
     float *gb = lds + (size_t)U * n;
@@ -334,9 +338,9 @@ __global__ __launch_bounds__(kGenThreads) void generic_bwd_kernel(BwdArgs A)
 
 // dtheta[q] = sum over workgroups of partial[w][q], accumulated in double in workgroup order.
 __global__ void reduce_partials_kernel(const float *__restrict__ partial, float *__restrict__ dtheta,
-                                       size_t n_angles, int n_parts, const int *bad_a, const int *bad_b)
+                                       size_t n_angles, int n_parts, PlanRef plan, int only_if_bad)
 {
-    if (bad_a && (*bad_a | *bad_b) == 0) return;
+    if (!plan_matches(plan) || (only_if_bad && plan_fast_both(plan))) return;
     size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= n_angles) return;
     double acc = 0.0;
@@ -391,8 +395,8 @@ hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv,
     A.n = s.n;
     A.heads = s.heads;
     A.k = s.k;
-    A.bad_a = only_if_bad ? &pv.hdr->fast_bad_fwd : nullptr;
-    A.bad_b = only_if_bad ? &pv.hdr->fast_bad_inv : nullptr;
+    A.plan = pv.ref;
+    A.only_if_bad = only_if_bad ? 1 : 0;
     size_t lds_bytes = (size_t)2 * A.rows_per_tile * s.n * sizeof(float);
     void (*kern)(BwdArgs) = s.dtype == BQ_F32   ? generic_bwd_kernel<float>
                             : s.dtype == BQ_F16 ? generic_bwd_kernel<__half>
@@ -409,7 +413,7 @@ hipError_t launch_generic_bwd(const void *x, const void *dy, const PlanView &pv,
         size_t n_angles = (size_t)s.heads * s.k * (s.n / 2);
         unsigned blocks = (unsigned)((n_angles + 255) / 256);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws, dtheta,
-                           n_angles, (int)grid, A.bad_a, A.bad_b);
+                           n_angles, (int)grid, A.plan, A.only_if_bad);
         e = hipGetLastError();
     }
     return e;

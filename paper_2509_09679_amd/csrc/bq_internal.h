@@ -77,8 +77,29 @@ inline int ilog2_exact(int n)
     return ((1 << k) == n) ? k : -1;
 }
 
+// What a kernel needs to tell whether the plan it was handed is one that bq_plan_build wrote for the
+// shape of this call.  Every kernel that reads plan tables tests plan_matches() before its first table
+// access and returns without writing anything when the test fails: a buffer that was never built, or
+// built for another (n, heads), then leaves the outputs as they were instead of being read past its end.
+struct PlanRef {
+    const PlanHeader *hdr;
+    int32_t n, heads;
+};
+
+__device__ __forceinline__ bool plan_matches(const PlanRef &p)
+{
+    return p.hdr->magic == kPlanMagic && p.hdr->n == p.n && p.hdr->heads == p.heads;
+}
+
+// the plan is of this shape and both of its scale-deferred table sets (forward, transposed) are usable
+__device__ __forceinline__ bool plan_fast_both(const PlanRef &p)
+{
+    return plan_matches(p) && (p.hdr->fast_bad_fwd | p.hdr->fast_bad_inv) == 0;
+}
+
 struct PlanView {  // device pointers into a plan
     const PlanHeader *hdr;
+    PlanRef ref;
     const float2 *cs;
     const float *fg_fwd, *fd_fwd, *fm_fwd, *fg_inv, *fd_inv, *fw_inv;
 };
@@ -89,6 +110,7 @@ inline PlanView plan_view(const void *plan, int n, int heads, int k)
     const char *p = (const char *)plan;
     PlanView v;
     v.hdr = (const PlanHeader *)p;
+    v.ref = PlanRef{v.hdr, n, heads};
     v.cs = (const float2 *)(p + L.cs);
     v.fg_fwd = (const float *)(p + L.fg_fwd);
     v.fd_fwd = (const float *)(p + L.fd_fwd);

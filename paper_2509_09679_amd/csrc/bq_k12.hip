@@ -71,6 +71,7 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.fd = mode == kInv ? pv.fd_inv : pv.fd_fwd;
     A.cs = pv.cs;
     A.fast_bad = mode == kInv ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
+    A.plan = pv.ref;
     const bool virt = s.n < kN, wide = s.n > kN;
     const int block_rows = k12_block_rows(s);  // rows of the caller per kernel row
     A.rows = s.rows / block_rows;     // whole blocks only (the caller handles the remainder)

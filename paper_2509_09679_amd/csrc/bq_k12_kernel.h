@@ -61,6 +61,7 @@ struct K12Args {
     const float *fd;   // [heads][n] output scales
     const float2 *cs;  // [heads][k][n/2]
     const int *fast_bad;
+    PlanRef plan;  // not read by the fixed transform (its coefficients come from the element index)
     int64_t rows, ld_in, ld_out;
     int heads;
     // quantiser
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     const int tmask = tn - 1;
     const T *in = (const T *)A.in;
     if (row_first >= A.rows) return;
+    if (!kHad && !plan_matches(A.plan)) return;
 
     // coefficients: cn[j][r] for layer j+1 (layout N), cp[j][r'] for layer 8+j (layout P), d[r] (layout N)
     const int idx_p = base_p(wave, lane);

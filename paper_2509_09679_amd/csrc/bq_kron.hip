@@ -280,6 +280,7 @@ struct FusedArgs {
     const float *fg, *fd;
     const float2 *cs;
     const int *fast_bad;
+    PlanRef plan;
     int64_t rows;
     int d1;
     int bfly_threads;  // threads of the butterfly group (whole waves); the mix group follows
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(kFusedMaxThreads) void kron128_kernel(FusedArgs A)
 {
     constexpr int IT = (KS + 3) / 4;
     extern __shared__ __align__(16) float tile[];  // 3 kStepRows x [d1][kTileRow]
-    if ((*A.fast_bad != 0) != kSlow) return;
+    if (!plan_matches(A.plan) || (*A.fast_bad != 0) != kSlow) return;
     const int d1 = A.d1;
     const int tile_floats = d1 * kTileRow;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -601,6 +602,7 @@ hipError_t launch_kron_fused(bool inverse, const void *in, void *out, const floa
     A.fd = inverse ? pv.fd_inv : pv.fd_fwd;
     A.cs = pv.cs;
     A.fast_bad = inverse ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
+    A.plan = pv.ref;
     A.rows = rows;
     A.d1 = d1;
     if (inverse) {

@@ -26,6 +26,7 @@ struct SmallArgs {
     const float *fg, *fd;
     const float2 *cs;
     const int *fast_bad;
+    PlanRef plan;
     int64_t rows, ld_in, ld_out;
     int heads, width;    // width = heads * n
     int span;            // elements covered by a workgroup: kSmallSpan, or the largest power of two below it that
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(SmallArgs A)
 {
     constexpr int n = 1 << K;
     constexpr bool kInverse = (kMode == kInv);
+    if (!plan_matches(A.plan)) return;
     const int tid = threadIdx.x;
     __shared__ unsigned long long wg_bins[16];  // kFwdFake: this workgroup's bin counts
     BinCount<kBits> bins;
@@ -230,6 +232,7 @@ hipError_t launch_small(Mode mode, const void *in, void *out, const PlanView &pv
     A.fd = mode == kInv ? pv.fd_inv : pv.fd_fwd;
     A.cs = pv.cs;
     A.fast_bad = mode == kInv ? &pv.hdr->fast_bad_inv : &pv.hdr->fast_bad_fwd;
+    A.plan = pv.ref;
     A.rows = s.rows;
     A.ld_in = s.ld_x;
     A.ld_out = s.ld_y;
