@@ -325,6 +325,11 @@ def calibration_step(B, torch, x, dy, theta, plan, y, codes, scales, quant, rows
                         "valu_frac": round(tf / VALU_PEAK_TFLOPS, 4),
                         "valu_frac_unpacked": round(tf / VALU_PEAK_UNPACKED_TFLOPS, 4)})
         kinfo[name] = rec
+    # each call once more on its own, 20 launches back to back: inside the sequence every kernel runs a few per cent
+    # slower than alone (the five calls keep the device at its sustained limit)
+    for name in order[1:]:
+        avg, _, _ = time_kernel(kernels[name], 20, 10)
+        kinfo[name]["alone_ms"] = round(avg, 4)
     kinfo["bwd"]["workspace_MiB"] = round(ws.numel() / 2 ** 20, 1)
     return {"workload": "plan build + fused fwd+INT2 quant + fwd + inv + bwd on the n=4096, T=%d fp16 batch" % T,
             "ms_per_step": round(ms, 4), "rows_per_s": T / (ms * 1e-3), "steps": steps, "kernels": kinfo}
