@@ -445,8 +445,7 @@ __device__ __forceinline__ void store8_bounded(T *base, uint32_t bytes, uint32_t
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (std::is_same<T, __half>::value) {
-                const __half2 h = __halves2half2(__float2half_rn(y[2 * i]), __float2half_rn(y[2 * i + 1]));
-                w[i] = *(const uint32_t *)&h;
+                w[i] = f32x2_to_f16x2_bits(y[2 * i], y[2 * i + 1]);
             } else {
                 w[i] = f32x2_to_bf16x2_bits(y[2 * i], y[2 * i + 1]);
             }

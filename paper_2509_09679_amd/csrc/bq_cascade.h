@@ -152,10 +152,7 @@ __device__ __forceinline__ void store8(__half *p, const float (&y)[8])
 {
     uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const __half2 h = __halves2half2(__float2half_rn(y[2 * i]), __float2half_rn(y[2 * i + 1]));
-        w[i] = *(const uint32_t *)&h;
-    }
+    for (int i = 0; i < 4; ++i) w[i] = f32x2_to_f16x2_bits(y[2 * i], y[2 * i + 1]);
     *(uint4 *)p = make_uint4(w[0], w[1], w[2], w[3]);
 }
 __device__ __forceinline__ void store8(bf16_t *p, const float (&y)[8])

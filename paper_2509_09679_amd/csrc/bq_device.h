@@ -34,6 +34,14 @@ __device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi)
     const float2_t v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+// two float32 -> two binary16 in one register, round to nearest even: one v_cvt_pk_f16_f32
+__device__ __forceinline__ uint32_t f32x2_to_f16x2_bits(float lo, float hi)
+{
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    const float2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
 template <>
 __device__ __forceinline__ bf16_t from_float<bf16_t>(float v)
 {

@@ -129,8 +129,7 @@ struct Pair<__half> {
     }
     static __device__ __forceinline__ raw pack(float a, float b)
     {
-        const __half2 h = __halves2half2(__float2half_rn(a), __float2half_rn(b));
-        return *(const uint32_t *)&h;
+        return f32x2_to_f16x2_bits(a, b);
     }
 };
 template <>
