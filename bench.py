@@ -113,11 +113,14 @@ def percentile(ts, q):
 
 
 def measured_copy(B, torch, x, y):
-    """What the memory system delivers, measured here: a plain copy of the 2 GiB input (library kernel, 16 bytes per
-    lane)."""
+    """What the memory system delivers, measured here: a plain copy of the 2 GiB input and a plain read of it (library
+    kernels, 16 bytes per lane)."""
     nbytes = x.numel() * x.element_size()
     avg, med, _ = time_kernel(lambda: B.bq_probe_copy(x, y, nbytes), 20, 10)
-    return {"measured_copy_GBps": round(2 * nbytes / (med * 1e-3) / 1e9, 1), "copy_bytes": nbytes, "copy_ms": round(med, 4)}
+    sink = torch.empty(B.bq_probe_read_sink_bytes(), dtype=torch.uint8, device=x.device)
+    _, med_r, _ = time_kernel(lambda: B.bq_probe_read(x, nbytes, sink), 20, 10)
+    return {"measured_copy_GBps": round(2 * nbytes / (med * 1e-3) / 1e9, 1), "copy_bytes": nbytes, "copy_ms": round(med, 4),
+            "measured_read_GBps": round(nbytes / (med_r * 1e-3) / 1e9, 1), "read_ms": round(med_r, 4)}
 
 
 def measured_fma(B, torch, dev):

@@ -201,6 +201,12 @@ bq_status bq_kron_inv(const void *y, void *x, const float *q1, int32_t d1, const
  * system delivers.  Device pointers aligned to 16 bytes, bytes a multiple of 16; asynchronous on `stream`. */
 bq_status bq_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* The read side alone: every lane of a fixed grid loads its share of src[0, bytes) (16 bytes per lane and access)
+ * and stores one 16-byte checksum into `sink`, a device buffer of bq_probe_read_sink_bytes() bytes.  Same alignment
+ * rules; asynchronous on `stream`. */
+bq_status bq_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+size_t bq_probe_read_sink_bytes(void);
+
 /* A float32 FMA issue-rate loop: every lane of a fixed grid runs 16 independent chains of `iters` FMAs, in the
  * instructions this library is built from (no packed float32).  out: device buffer of
  * bq_probe_fma_out_floats() floats (receives one checksum per lane).  Returns the number of lane-FMAs the

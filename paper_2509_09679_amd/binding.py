@@ -22,7 +22,8 @@ DTYPE_CODES = {"f32": BQ_F32, "f16": BQ_F16, "bf16": BQ_BF16}
 EXPORTS = ["bq_plan_bytes", "bq_plan_build", "bq_butterfly_fwd", "bq_butterfly_inv", "bq_butterfly_fwd_quant",
            "bq_butterfly_fwd_fakequant", "bq_hadamard_fwd", "bq_cayley_build", "bq_kron_fwd", "bq_kron_inv",
            "bq_butterfly_bwd_workspace_bytes", "bq_butterfly_bwd", "bq_butterfly_bwd_static",
-           "bq_butterfly_bwd_static_max_bytes", "bq_probe_copy", "bq_probe_fma", "bq_probe_fma_out_floats",
+           "bq_butterfly_bwd_static_max_bytes", "bq_probe_copy", "bq_probe_read", "bq_probe_read_sink_bytes",
+           "bq_probe_fma", "bq_probe_fma_out_floats",
            "bq_status_string", "bq_last_error",
            "bq_version"]
 
@@ -84,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.bq_butterfly_bwd_static_max_bytes.restype = sz
         L.bq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.bq_probe_copy.restype = ctypes.c_int
+        L.bq_probe_read.argtypes = [vp, sz, vp, vp]
+        L.bq_probe_read.restype = ctypes.c_int
+        L.bq_probe_read_sink_bytes.argtypes = []
+        L.bq_probe_read_sink_bytes.restype = sz
         L.bq_probe_fma.argtypes = [vp, ctypes.c_int32, vp]
         L.bq_probe_fma.restype = ctypes.c_int64
         L.bq_probe_fma_out_floats.argtypes = []
@@ -208,6 +213,14 @@ def bq_butterfly_bwd_static_max_bytes() -> int:
 
 def bq_probe_copy(src, dst, nbytes: int, stream=None) -> None:
     _check(lib().bq_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream_ptr(stream)))
+
+
+def bq_probe_read_sink_bytes() -> int:
+    return int(lib().bq_probe_read_sink_bytes())
+
+
+def bq_probe_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib().bq_probe_read(_ptr(src), nbytes, _ptr(sink), _stream_ptr(stream)))
 
 
 def bq_probe_fma_out_floats() -> int:

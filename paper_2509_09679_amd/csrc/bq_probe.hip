@@ -11,6 +11,26 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = src[i];
 }
 
+// The read side alone: every lane XORs what it loads and stores the result once at the end (16 bytes per thread).
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ sink, size_t count)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const uint4 v = src[i];
+        acc.x ^= v.x;
+        acc.y ^= v.y;
+        acc.z ^= v.z;
+        acc.w ^= v.w;
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+// Persistent grids of the two streaming probes, swept on 2 GiB (256 threads per workgroup): the copy is fastest with
+// three workgroups per compute unit (768: 5.55 TB/s; 1024 and 1280 alike, 2048 and more 4.5 .. 4.7, 512 4.9), the read
+// with eight (2048: 6.45 TB/s; 1024: 6.3).
+constexpr unsigned kProbeCopyGrid = 768, kProbeReadGrid = 2048;
+
 constexpr int kProbeChains = 16;  // independent accumulators per lane: no FMA waits for another
 
 // Every lane runs kProbeChains independent chains of `iters` float32 FMAs (plain v_fma_f32 / v_fmac_f32: this
@@ -44,8 +64,20 @@ bq_status bq_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
     if (bytes == 0) return BQ_OK;
     const size_t count = bytes / 16;
     const size_t want = (count + 255) / 256;
-    const unsigned grid = (unsigned)(want < 8192 ? want : 8192);
+    const unsigned grid = (unsigned)(want < bq::kProbeCopyGrid ? want : bq::kProbeCopyGrid);
     hipLaunchKernelGGL(bq::probe_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, (uint4 *)dst, count);
+    return hipGetLastError() == hipSuccess ? BQ_OK : BQ_ERR_HIP;
+}
+
+size_t bq_probe_read_sink_bytes(void) { return (size_t)bq::kProbeReadGrid * 256 * 16; }
+
+bq_status bq_probe_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink) return BQ_ERR_NULL;
+    if (((uintptr_t)src & 15) || ((uintptr_t)sink & 15) || (bytes & 15)) return BQ_ERR_ALIGN;
+    // every thread of the fixed grid stores its 16 bytes, whatever the size
+    hipLaunchKernelGGL(bq::probe_read_kernel, dim3(bq::kProbeReadGrid), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src,
+                       (uint4 *)sink, bytes / 16);
     return hipGetLastError() == hipSuccess ? BQ_OK : BQ_ERR_HIP;
 }
 
