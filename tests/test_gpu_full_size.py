@@ -336,3 +336,63 @@ def test_float32_rows_at_the_sizes_bench_times(cfg, T):
     assert torch.equal(torch.bincount((c + 8).reshape(-1), minlength=16), hist)
     want = c.reshape(T, n // 128, 128).float() * scales.float().unsqueeze(-1)
     assert torch.equal(want.reshape(T, n), y)
+
+
+@pytest.mark.parametrize("n,heads,T,dtype,group", [(4096, 1, (1 << 20) + 5, "f16", 128), (128, 32, (1 << 20) + 3, "bf16", 128),
+                                                   (16384, 1, (1 << 18) + 3, "f16", 256), (8192, 1, (1 << 19) + 2, "bf16", 128)])
+def test_row_offsets_beyond_four_gibibytes(n, heads, T, dtype, group):
+    """8 GiB per array, so row offsets pass 2^31 and 2^32 bytes (and 2^31 elements), on each kernel family: n = 4096,
+    per-head transforms of 128, the general kernel (n = 16384) and n = 8192.  The rows around those boundaries and the
+    last ones are checked against the oracle: forward, inverse, fused quantiser, and a backward pass whose dy is
+    non-zero only in the last rows (dtheta then comes from there alone)."""
+    w = n * heads
+    tdt = synth.torch_dtype(dtype)
+    g = torch.Generator(device=DEV).manual_seed(20 + n)
+    x = torch.empty((T, w), dtype=tdt, device=DEV)
+    piece = (1 << 30) // w
+    for r0 in range(0, T, piece):  # in pieces: the float32 draw of the whole batch would take 16 GiB more
+        r1 = min(T, r0 + piece)
+        x[r0:r1] = (torch.randn((r1 - r0, w), generator=g, device=DEV) * 1.5).to(tdt)
+    rng = np.random.default_rng(21 + n)
+    k = n.bit_length() - 1
+    th = (rng.standard_normal((heads, k, n // 2)) * 0.7).astype(np.float32)
+    theta = torch.from_numpy(th).to(DEV)
+    plan = B.alloc_plan(theta, n, heads)
+    rows = B.make_rows(x, n, heads)
+    b31 = (1 << 31) // (w * 2)  # the row whose first byte is at 2^31
+    pick = np.array([0, b31 - 1, b31, b31 + 1, 2 * b31 - 1, 2 * b31, 2 * b31 + 1, 3 * b31, T - 3, T - 2, T - 1])
+    sel = torch.as_tensor(pick, device=DEV)
+    xs = synth.torch_to_storage(x[sel], dtype)
+    y_ref = oracle.forward(synth.to_f64(xs, dtype), th, n, heads)
+    y = torch.full_like(x, 7.0)
+    B.bq_butterfly_fwd(x, y, plan, rows)
+    torch.cuda.synchronize()
+    ys = synth.torch_to_storage(y[sel], dtype)
+    gu.check_rotated(ys, y_ref, dtype, "8 GiB fwd")
+    assert not (y[T - 1024:] == 7.0).all(dim=1).any() and not (y[2 * b31 - 512:2 * b31 + 512] == 7.0).all(dim=1).any()
+    for bits in (2, 4):
+        codes, scales = B.alloc_quant_outputs(T, n, heads, bits, group, "f16", DEV)
+        B.bq_butterfly_fwd_quant(x, plan, codes, scales, B.make_quant(bits, group, "f16"), rows)
+        torch.cuda.synchronize()
+        gu.check_fused_codes(codes[sel].cpu().numpy(), scales[sel].float().cpu().numpy(), y_ref, bits, group, "f16", dtype,
+                             f"8 GiB int{bits}")
+        del codes, scales
+    B.bq_butterfly_inv(y, y, plan, rows)  # in place
+    torch.cuda.synchronize()
+    gu.check_rotated(synth.torch_to_storage(y[sel], dtype), oracle.inverse(synth.to_f64(ys, dtype), th, n, heads), dtype, "8 GiB inv")
+    # backward: dy is zero except in the last 37 rows
+    R = 37
+    dy = y
+    dy.zero_()
+    dy[T - R:] = (torch.randn((R, w), generator=g, device=DEV)).to(tdt)
+    dx = torch.full_like(x, 7.0)
+    dth = torch.empty_like(theta)
+    ws = torch.empty(max(256, B.bq_butterfly_bwd_workspace_bytes(rows)), dtype=torch.uint8, device=DEV)
+    B.bq_butterfly_bwd(x, dy, plan, dx, dth, ws, rows)
+    torch.cuda.synchronize()
+    xt = synth.torch_to_storage(x[T - R:], dtype)
+    dyt = synth.torch_to_storage(dy[T - R:], dtype)
+    dx_ref, dth_ref, absacc = oracle.backward(synth.to_f64(xt, dtype), synth.to_f64(dyt, dtype), th, n, heads, want_abs=True)
+    gu.check_rotated(synth.torch_to_storage(dx[T - R:], dtype), dx_ref, dtype, "8 GiB dx tail")
+    gu.check_dtheta(dth.cpu().numpy(), dth_ref, absacc, what="8 GiB dtheta")
+    assert (dx[sel[:8]] == 0).all()  # dy = 0 there
