@@ -550,6 +550,29 @@ def extra_figures(B, synth, torch, dev):
     a2, _, _ = time_kernel(lambda: B.bq_butterfly_bwd(Wt, dWt, plan3, None, dthw, wsw, rw), 30, 30)
     res["weight_side"] = {"workload": "W [11008, 4096] fp16: fused W B^T + INT2 g128; dtheta from (W, dL/dW')",
                           "fwd_quant_ms": round(a1, 4), "bwd_ms": round(a2, 4)}
+    del Wt, dWt, cw, sw, wsw
+    # the method end to end on synthetic data: SGD with a cosine schedule from the identity on one linear layer
+    # (paper, "Implementation Details"), W2A4, every butterfly call in the library, the layer's two dense
+    # products in torch
+    from paper_2509_09679_amd.calibration import ButterflyCalibrator, QuantSpec
+
+    Tc, mc = 16384, 4096
+    Xc, _, _ = synth.device_rows(3, Tc, dev)
+    g = torch.Generator(device=dev).manual_seed(7)
+    Wc = (torch.randn((mc, 4096), generator=g, device=dev) * 0.02).to(Xc.dtype)
+    cal = ButterflyCalibrator(Wc, QuantSpec(4, 128, "f16"), QuantSpec(2, 128, "f16"))
+    cal.fit(Xc, 2, 1.0)  # warm-up
+    cal.theta.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    losses = cal.fit(Xc, 30, 1.0)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    res["calibration_fit"] = {"workload": "30 SGD steps from theta = 0 on one layer: X [16384, 4096] fp16 (INT4 g128), "
+                                          "W [4096, 4096] fp16 (INT2 g128); loss = L_recon, L_uniform reported",
+                              "ms_per_step": round((t1 - t0) * 1e3 / 30, 3), "loss_first": losses[0], "loss_last": losses[-1],
+                              "loss_min": min(losses), "L_uniform_first": round(cal.kl_seen[0], 5),
+                              "L_uniform_last": round(cal.kl_seen[-1], 5)}
     return res
 
 
