@@ -164,6 +164,30 @@ __device__ __forceinline__ void store8(bf16_t *p, const float (&y)[8])
     *(uint4 *)p = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// the same stores with the non-temporal hint (output that is not read again before it leaves the caches)
+typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store8_nt(float *p, const float (&y)[8])
+{
+    const nt_u32x4 a = {__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]), __float_as_uint(y[3])};
+    const nt_u32x4 b = {__float_as_uint(y[4]), __float_as_uint(y[5]), __float_as_uint(y[6]), __float_as_uint(y[7])};
+    __builtin_nontemporal_store(a, (nt_u32x4 *)p);
+    __builtin_nontemporal_store(b, (nt_u32x4 *)p + 1);
+}
+__device__ __forceinline__ void store8_nt(__half *p, const float (&y)[8])
+{
+    nt_u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = f32x2_to_f16x2_bits(y[2 * i], y[2 * i + 1]);
+    __builtin_nontemporal_store(w, (nt_u32x4 *)p);
+}
+__device__ __forceinline__ void store8_nt(bf16_t *p, const float (&y)[8])
+{
+    nt_u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = f32x2_to_bf16x2_bits(y[2 * i], y[2 * i + 1]);
+    __builtin_nontemporal_store(w, (nt_u32x4 *)p);
+}
+
 // ---- quantiser epilogue for 8 consecutive channels per thread ----------------------------------
 // Reciprocal of a positive normal float whose significand has at most 11 bits (a binary16 value),
 // correctly rounded: hardware estimate (1 ulp) plus one Newton step in FMA arithmetic.  Used only

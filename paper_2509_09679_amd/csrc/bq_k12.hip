@@ -46,6 +46,8 @@ hipError_t launch_hadamard(const void *in, void *out, const Shape &s, hipStream_
     A.ld_out = A.sub_ld_out = s.ld_y;
     A.n = s.n;
     A.n_log = s.k;
+    // beyond the 256 MB of the memory-side cache neither input nor output is found in a cache again
+    A.streaming = (int64_t)s.rows * s.n * s.heads * (s.dtype == BQ_F32 ? 4 : 2) >= ((int64_t)256 << 20) ? 1 : 0;
     A.heads = s.heads;
     const bool wide = s.n > kN;
     int64_t per_head = 256 / A.heads > 0 ? 256 / A.heads : 1;  // as for the forward transform: one workgroup per compute unit
@@ -81,6 +83,8 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     A.sub_ld_out = s.ld_y;
     A.n = s.n;
     A.n_log = s.k;
+    // beyond the 256 MB of the memory-side cache neither input nor output is found in a cache again
+    A.streaming = (int64_t)s.rows * s.n * s.heads * (s.dtype == BQ_F32 ? 4 : 2) >= ((int64_t)256 << 20) ? 1 : 0;
     const int64_t width = (int64_t)s.n * s.heads;
     A.heads = virt ? (width > kN ? (int)(width / kN) : 1) : s.heads;  // virt: 4096-element blocks per row
     A.row_log = virt ? (width >= kN ? kK : ilog2_exact((int)width)) : 0;

@@ -69,6 +69,9 @@ struct K12Args {
     void *scales;
     unsigned long long *hist;  // kFwdFake: 2^bits counters or NULL
     int group, scale_f16;
+    // the batch is larger than the memory-side cache (input and output are touched once): the launcher then picks
+    // the kNt variants of the plain transforms
+    int streaming;
     // transforms of n = 2^n_log < 4096 points (kVirt): a "row" of the kernel is a block of 4096 consecutive
     // elements of the caller's [rows][heads * n] array.  Rows of up to 4096 elements: 2^(12 - row_log) whole rows
     // (row_log = log2 of the row width; ld_in / ld_out are the strides between blocks, sub_ld_* the caller's
@@ -221,7 +224,8 @@ struct CountOf<kFwdFake, kBits> {
 // kFwdFake only: kYq = the dequantised row is stored, kHist = the bins are counted.
 // chunk: the thread's group of 8 elements, counted inside the whole row.
 // kBig: quantiser groups of more than 128 channels (the maximum then comes from big_group_max()).
-template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt, bool kWide, bool kBig>
+template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq, bool kHist, bool kVirt, bool kWide, bool kBig,
+          bool kNt = false>
 __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8], int64_t row, int head, int chunk,
                                            typename CountOf<kMode, kBits>::type &bins, unsigned long long *wg_bins,
                                            float *wg_max)
@@ -252,7 +256,10 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
         T *out_row = (T *)A.out + row * A.ld_out;
         uint32_t off = elem_off<kVirt, kWide>(A, head, chunk * 8, A.sub_ld_out) * (uint32_t)sizeof(T);
         asm volatile("" : "+v"(off));
-        store8((T *)((char *)out_row + off), y);
+        if (kNt)
+            store8_nt((T *)((char *)out_row + off), y);
+        else
+            store8((T *)((char *)out_row + off), y);
     } else {
         const int lanes = kLanes > 0 ? kLanes : (A.group >> 3);  // lanes per group
         const bool f16 = kLanes > 0 ? (kScale != 0) : (A.scale_f16 != 0);
@@ -282,10 +289,13 @@ __device__ __forceinline__ void finish_row(const K12Args &A, const float (&y)[8]
 }
 
 template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = true, bool kHist = false, bool kVirt = false,
-          bool kWide = false, bool kBig = false>
+          bool kWide = false, bool kBig = false, bool kNt = false>
 __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel(K12Args A)
 {
     static_assert(!(kWide && kVirt), "blocks of small transforms are a 4096-point scheme");
+    // kNt: rows are loaded and stored with the non-temporal hint (262144 fp16 rows of n = 4096: forward 0.784 ->
+    // 0.768 ms, inverse 0.840 -> 0.810 ms; the fused quantiser, which stores little, does not gain)
+    static_assert(!kNt || kMode == kFwd || kMode == kInv || kMode == kHadamard, "plain transforms only");
     static_assert(!kBig || ((kMode == kFwdQuant || kMode == kFwdFake) && kLanes == 0), "large groups: general quantiser variants");
     constexpr int kHalves = kWide ? 2 : 1;
     constexpr int kPoints = kHalves * kN;  // n
@@ -393,7 +403,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
             float u[8];
             unpack8(load8(in + row * A.ld_in + off_n), u, (const T *)nullptr);
             slow_cascade<kInverse, kWide>(u, lds, cs, col0 + idx_n, nk, kVirt ? (1 << A.row_log) - 1 : 0, kVirt ? head * kN : 0);
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row, head, chunk_row, bins, wg_bins, wg_max);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig, kNt>(A, u, row, head, chunk_row, bins, wg_bins, wg_max);
         }
         flush_bins();
         return;
@@ -514,15 +524,27 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
         const int jj = j < n_my ? j : n_my - 1;  // past the end: re-read the last row (unused)
         const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
         const uint32_t m0v = slice_s + (uint32_t)slot * kSlotBytes;
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
-                     :
-                     : "v"(voff), "s"(m0v), "s"(rowp)
-                     : "memory");
-        if (kLoads == 2)
+        if (kNt) {
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2 nt"
+                         :
+                         : "v"(voff), "s"(m0v), "s"(rowp)
+                         : "memory");
+            if (kLoads == 2)
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2 nt"
+                             :
+                             : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
+                             : "memory");
+        } else {
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
                          :
-                         : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
+                         : "v"(voff), "s"(m0v), "s"(rowp)
                          : "memory");
+            if (kLoads == 2)
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"
+                             :
+                             : "v"(voff1), "s"(m0v + 1024u), "s"(rowp)
+                             : "memory");
+        }
     };
     ring_load(0, 0);
     ring_load(1, 1);
@@ -581,7 +603,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
 #pragma unroll
                 for (int r = 0; r < 8; ++r) u[r] *= d[r];
             }
-            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
+            finish_row<T, kMode, kBits, kLanes, kScale, kYq, kHist, kVirt, kWide, kBig, kNt>(A, u, row_first + (it - 2) * row_step, head, chunk_row, bins, wg_bins, wg_max);
         };
         // The phases touch different buffers, so any order is correct as long as C precedes A where the two
         // share a buffer.  n = 4096: C, B, A measured 1-2 % faster than the other orders on all modes.
@@ -637,23 +659,25 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
         kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 0, 0, true, false, V, W, G> : k12_kernel<T, kFwdQuant, 4, 0, 0, true, false, V, W, G>;
     } else if constexpr (!kBig) {
         if constexpr (!kVirt) {
-            if (mode == kHadamard) kern = k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W>;
+            if (mode == kHadamard)
+                kern = A.streaming ? k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W, false, true>
+                                   : k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W>;
         }
         if (kern) {
         } else if (mode == kFwd)
-            kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
+            kern = A.streaming ? k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W, false, true> : k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
         else if (mode == kInv)
-            kern = k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
+            kern = A.streaming ? k12_kernel<T, kInv, 4, 0, 0, true, false, V, W, false, true> : k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
         else  // the common activation format: group 128, binary16 scales
             kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1, true, false, false, W> : k12_kernel<T, kFwdQuant, 4, 16, 1, true, false, false, W>;
     }
     if (!kern) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (kWide ? 2 : 1) * kLdsBytes;
     // one record per kernel of this instantiation of the launcher (the modes, bit widths and output choices)
-    static LdsLimitOnce once[5][2][3];
+    static LdsLimitOnce once[5][2][3][2];
     const int variant = mode != kFwdFake ? 0 : (A.out && A.hist) ? 0 : A.out ? 1 : 2;
     const int general = (mode == kFwdQuant && (kBig || kVirt || A.group != 128 || !A.scale_f16)) ? 1 : 0;
-    hipError_t e = once[mode][bits == 2 ? 0 : 1][mode == kFwdQuant ? general : variant].set((const void *)kern, lds_bytes);
+    hipError_t e = once[mode][bits == 2 ? 0 : 1][mode == kFwdQuant ? general : variant][A.streaming ? 1 : 0].set((const void *)kern, lds_bytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kWide ? 2 * kThreads : kThreads), lds_bytes, stream, A);
     return hipGetLastError();
