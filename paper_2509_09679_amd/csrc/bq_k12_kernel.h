@@ -293,9 +293,10 @@ template <typename T, int kMode, int kBits, int kLanes, int kScale, bool kYq = t
 __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel(K12Args A)
 {
     static_assert(!(kWide && kVirt), "blocks of small transforms are a 4096-point scheme");
-    // kNt: rows are loaded and stored with the non-temporal hint (262144 fp16 rows of n = 4096: forward 0.784 ->
-    // 0.768 ms, inverse 0.840 -> 0.810 ms; the fused quantiser, which stores little, does not gain)
-    static_assert(!kNt || kMode == kFwd || kMode == kInv || kMode == kHadamard, "plain transforms only");
+    // kNt: rows are loaded and stored with the non-temporal hint.  262144 fp16 rows of n = 4096: forward 0.796 ->
+    // 0.778 ms on every box tried.  Not used where it did not hold up: the inverse gained 3.5 % on some boxes and
+    // lost as much on others, float32 rows lost 15 - 19 % (0.78 -> 0.93 ms), the fused quantiser stores too little.
+    static_assert(!kNt || ((kMode == kFwd || kMode == kHadamard) && sizeof(T) == 2), "16-bit forward transforms only");
     static_assert(!kBig || ((kMode == kFwdQuant || kMode == kFwdFake) && kLanes == 0), "large groups: general quantiser variants");
     constexpr int kHalves = kWide ? 2 : 1;
     constexpr int kPoints = kHalves * kN;  // n
@@ -660,16 +661,21 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     } else if constexpr (!kBig) {
         if constexpr (!kVirt) {
             if (mode == kHadamard)
-                kern = A.streaming ? k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W, false, true>
-                                   : k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W>;
+                kern = k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W>;
         }
         if (kern) {
         } else if (mode == kFwd)
-            kern = A.streaming ? k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W, false, true> : k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
+            kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W>;
         else if (mode == kInv)
-            kern = A.streaming ? k12_kernel<T, kInv, 4, 0, 0, true, false, V, W, false, true> : k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
+            kern = k12_kernel<T, kInv, 4, 0, 0, true, false, V, W>;
         else  // the common activation format: group 128, binary16 scales
             kern = bits == 2 ? k12_kernel<T, kFwdQuant, 2, 16, 1, true, false, false, W> : k12_kernel<T, kFwdQuant, 4, 16, 1, true, false, false, W>;
+    }
+    if constexpr (!kBig && sizeof(T) == 2) {  // large batches of 16-bit rows: the non-temporal variants
+        if (A.streaming && mode == kFwd) kern = k12_kernel<T, kFwd, 4, 0, 0, true, false, V, W, false, true>;
+        if constexpr (!kVirt) {
+            if (A.streaming && mode == kHadamard) kern = k12_kernel<T, kHadamard, 4, 0, 0, true, false, false, W, false, true>;
+        }
     }
     if (!kern) return hipErrorInvalidValue;
     constexpr size_t lds_bytes = (kWide ? 2 : 1) * kLdsBytes;
@@ -677,7 +683,7 @@ static hipError_t launch_k12_t(Mode mode, const K12Args &A, int bits, unsigned g
     static LdsLimitOnce once[5][2][3][2];
     const int variant = mode != kFwdFake ? 0 : (A.out && A.hist) ? 0 : A.out ? 1 : 2;
     const int general = (mode == kFwdQuant && (kBig || kVirt || A.group != 128 || !A.scale_f16)) ? 1 : 0;
-    hipError_t e = once[mode][bits == 2 ? 0 : 1][mode == kFwdQuant ? general : variant][A.streaming ? 1 : 0].set((const void *)kern, lds_bytes);
+    hipError_t e = once[mode][bits == 2 ? 0 : 1][mode == kFwdQuant ? general : variant][(A.streaming && sizeof(T) == 2 && (mode == kFwd || mode == kHadamard)) ? 1 : 0].set((const void *)kern, lds_bytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kWide ? 2 * kThreads : kThreads), lds_bytes, stream, A);
     return hipGetLastError();
