@@ -1,5 +1,6 @@
 // n = 256 .. 4096 instantiations of the specialised transform kernels, and the choice between them.
 #include "bq_k12_kernel.h"
+#include "bq_k12_inv.h"
 
 namespace bq {
 
@@ -103,15 +104,20 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // (768, 1280, 1792, 2304 alike) and 6 .. 18 % slower with anything else tried (512, 640, 896, 1000, 1024,
     // 1152, 1536, 2048).  The forward transform is faster still with ONE workgroup per compute unit (256: 0.84 ->
     // 0.79 ms for 2^30 16-bit elements at every n from 256 to 4096, float32 rows 0.793 -> 0.776 ms, small
-    // batches too); the inverse is not (0.88 against 0.855 ms).
+    // batches too); the three-phase inverse is not (0.88 against 0.855 ms; it still serves float32 rows).
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
-    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : mode == kFwd ? 256 : 768;
+    // The two-phase inverse of 16-bit rows (bq_k12_inv.h) also runs best with one workgroup per compute unit (256: 0.78 ms,
+    // 512: 0.86, 768: 0.85, 1024: 0.99, 1280: 0.85, 2048: 0.95 ms for 2^30 fp16 elements).
+    const bool inv_ring = mode == kInv && !wide && s.dtype != BQ_F32;
+    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : (mode == kFwd || inv_ring) ? 256 : 768;
     int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * A.heads);
     if ((mode == kFwdQuant || mode == kFwdFake) && q->group > 128)
         return launch_k12_big_dtype(mode, A, bits, grid, s.dtype, virt, wide, stream);
     if (wide) return launch_k13_dtype(mode, A, bits, grid, s.dtype, stream);
+    if (inv_ring)  // 16-bit rows: the two-phase inverse
+        return virt ? launch_k12_inv_ring<true>(A, grid, s.dtype, stream) : launch_k12_inv_ring<false>(A, grid, s.dtype, stream);
     if (virt) return launch_k12_dtype<true, false>(mode, A, bits, grid, s.dtype, stream);
     return launch_k12_dtype<false, false>(mode, A, bits, grid, s.dtype, stream);
 }

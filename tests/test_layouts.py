@@ -93,3 +93,38 @@ def test_dy_ring_readers_find_what_the_loaders_put_there():
             pos = (c4 & 7) | (w << 3) | ((c4 >> 3) << 6)
             banks.append(((pos * 16 + (((l >> 4) & 1) | (((l >> 5) & 1) << 1)) * 4 + j * 2048) >> 2) & 31)
         assert sorted(np.bincount(banks, minlength=32)) == [2] * 32
+
+
+# ---- the two-phase inverse (csrc/bq_k12_inv.h): phase B reads the raw 16-bit row from the input ring in layout P ----
+INV_PIECE = 1088
+
+
+def inv_ring_addr(idx):            # byte offset inside a ring slot of element idx (even)
+    j = (idx >> 3) & 63
+    pos = (j >> 4) | ((j & 15) << 2)
+    return (idx >> 9) * INV_PIECE + pos * 16 + (idx & 7) * 2
+
+
+def test_inverse_ring_readers_find_what_the_loaders_put_there():
+    # wave w, lane l loads the 16 bytes of chunk j(l) of piece w (elements 512 w + 8 j .. + 7) to offset 16 l of the piece
+    where = {}
+    for w, l in itertools.product(range(8), range(64)):
+        j = ((l & 3) << 4) | (l >> 2)
+        for b in range(8):
+            where[512 * w + 8 * j + b] = w * INV_PIECE + 16 * l + 2 * b
+    assert sorted(where) == list(range(4096))
+    assert len(set(where.values())) == 4096 and max(where.values()) + 2 <= 8 * INV_PIECE
+    # a reader of layout P takes register pair (r1, r2) from inv_ring_addr(base) + (2 r1 + 4 r2) pieces
+    for w, l in itertools.product(range(8), range(64)):
+        base = base_p(w, l)
+        for r1, r2 in itertools.product(range(2), range(2)):
+            a = inv_ring_addr(base) + (2 * r1 + 4 * r2) * INV_PIECE
+            idx = base + 1024 * r1 + 2048 * r2
+            assert a % 4 == 0 and where[idx] == a and where[idx + 1] == a + 2
+
+
+def test_inverse_ring_reads_are_free_of_bank_conflicts():
+    # a 32-bit read of 32 consecutive lanes (half a wave) touches 32 different banks (4 bytes wide, 32 of them)
+    for w, half, r in itertools.product(range(8), range(2), range(4)):
+        banks = {((inv_ring_addr(base_p(w, 32 * half + l)) + 2 * r * INV_PIECE) >> 2) & 31 for l in range(32)}
+        assert len(banks) == 32
