@@ -62,7 +62,9 @@ __device__ __forceinline__ void unpack2<bf16_t>(uint32_t w, float &a, float &b)
     b = __uint_as_float(w & 0xFFFF0000u);
 }
 
-template <typename T, bool kVirt>
+// kNt: the batch is larger than the caches; rows are loaded and stored with the non-temporal hint (0.780 -> 0.766 ms
+// for 2^30 fp16 elements)
+template <typename T, bool kVirt, bool kNt>
 __global__ __launch_bounds__(kThreads, 4) void k12_inv_ring_kernel(K12Args A)
 {
     static_assert(sizeof(T) == 2, "16-bit rows");
@@ -141,7 +143,10 @@ __global__ __launch_bounds__(kThreads, 4) void k12_inv_ring_kernel(K12Args A)
         const int jj = j < n_my ? j : n_my - 1;  // past the end: the last row again (unused)
         const char *rowp = (const char *)(in + (row_first + jj * row_step) * A.ld_in);
         const uint32_t m0v = piece_s + (uint32_t)slot * (uint32_t)kInvSlotBytes;
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(voff), "s"(m0v), "s"(rowp) : "memory");
+        if (kNt)
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2 nt" : : "v"(voff), "s"(m0v), "s"(rowp) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(voff), "s"(m0v), "s"(rowp) : "memory");
     };
     // Memory operations of a wave complete in issue order.  Per iteration a wave issues one ring load (first) and
     // one store (in C).  Row it + 1 was requested at the start of iteration it - 2; younger than that load are the
@@ -167,8 +172,8 @@ __global__ __launch_bounds__(kThreads, 4) void k12_inv_ring_kernel(K12Args A)
             reg_layer<0>(u, cn[0]);
 #pragma unroll
             for (int r = 0; r < 8; ++r) u[r] *= d[r];
-            finish_row<T, kInv, 4, 0, 0, true, false, kVirt, false, false>(A, u, row_first + (it - 1) * row_step, head, chunk, bins,
-                                                                         wg_bins, wg_max);
+            finish_row<T, kInv, 4, 0, 0, true, false, kVirt, false, false, kNt>(A, u, row_first + (it - 1) * row_step, head, chunk,
+                                                                              bins, wg_bins, wg_max);
         }
         if (it < n_my) {  // B(it)
             uint32_t w0, w1, w2, w3;
@@ -213,9 +218,13 @@ __global__ __launch_bounds__(kThreads, 4) void k12_inv_ring_kernel(K12Args A)
 template <bool kVirt>
 static hipError_t launch_k12_inv_ring(const K12Args &A, unsigned grid, int dtype, hipStream_t stream)
 {
-    void (*kern)(K12Args) = dtype == BQ_F16 ? k12_inv_ring_kernel<__half, kVirt> : k12_inv_ring_kernel<bf16_t, kVirt>;
-    static LdsLimitOnce once[2];
-    hipError_t e = once[dtype == BQ_F16 ? 0 : 1].set((const void *)kern, kInvLdsBytes);
+    void (*kern)(K12Args);
+    if (A.streaming)
+        kern = dtype == BQ_F16 ? k12_inv_ring_kernel<__half, kVirt, true> : k12_inv_ring_kernel<bf16_t, kVirt, true>;
+    else
+        kern = dtype == BQ_F16 ? k12_inv_ring_kernel<__half, kVirt, false> : k12_inv_ring_kernel<bf16_t, kVirt, false>;
+    static LdsLimitOnce once[2][2];
+    hipError_t e = once[dtype == BQ_F16 ? 0 : 1][A.streaming ? 1 : 0].set((const void *)kern, kInvLdsBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kInvLdsBytes, stream, A);
     return hipGetLastError();

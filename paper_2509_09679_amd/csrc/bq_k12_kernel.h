@@ -297,6 +297,7 @@ __global__ __launch_bounds__(kWide ? 2 * kThreads : kThreads, 4) void k12_kernel
     // 0.778 ms on every box tried.  Not used where it did not hold up: the inverse gained 3.5 % on some boxes and
     // lost as much on others, float32 rows lost 15 - 19 % (0.78 -> 0.93 ms), the fused quantiser stores too little.
     static_assert(!kNt || ((kMode == kFwd || kMode == kHadamard) && sizeof(T) == 2), "16-bit forward transforms only");
+    // (the two-phase inverse of 16-bit rows, bq_k12_inv.h, has a variant of its own that does gain)
     static_assert(!kBig || ((kMode == kFwdQuant || kMode == kFwdFake) && kLanes == 0), "large groups: general quantiser variants");
     constexpr int kHalves = kWide ? 2 : 1;
     constexpr int kPoints = kHalves * kN;  // n
