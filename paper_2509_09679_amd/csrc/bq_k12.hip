@@ -104,12 +104,14 @@ hipError_t launch_k12(Mode mode, const void *in, void *out, const PlanView &pv, 
     // (768, 1280, 1792, 2304 alike) and 6 .. 18 % slower with anything else tried (512, 640, 896, 1000, 1024,
     // 1152, 1536, 2048).  The forward transform is faster still with ONE workgroup per compute unit (256: 0.84 ->
     // 0.79 ms for 2^30 16-bit elements at every n from 256 to 4096, float32 rows 0.793 -> 0.776 ms, small
-    // batches too); the three-phase inverse is not (0.88 against 0.855 ms; it still serves float32 rows).
+    // batches too).  The three-phase inverse was not on 16-bit rows (0.88 against 0.855 ms), which now take the two-phase
+    // kernel; on float32 rows, which it still serves, it is.
     // n = 8192: one workgroup of 1024 threads per compute unit at a time.
     // The two-phase inverse of 16-bit rows (bq_k12_inv.h) also runs best with one workgroup per compute unit (256: 0.78 ms,
     // 512: 0.86, 768: 0.85, 1024: 0.99, 1280: 0.85, 2048: 0.95 ms for 2^30 fp16 elements).
     const bool inv_ring = mode == kInv && !wide && s.dtype != BQ_F32;
-    const int target = wide ? 256 : (mode == kFwdQuant || mode == kFwdFake) ? 1280 : (mode == kFwd || inv_ring) ? 256 : 768;
+    // (and so does the three-phase inverse on float32 rows: 0.798 -> 0.779 ms for 2^29 elements)
+    const int target = (mode == kFwdQuant || mode == kFwdFake) && !wide ? 1280 : 256;
     int64_t per_head = target / A.heads > 0 ? target / A.heads : 1;
     if (per_head > A.rows) per_head = A.rows;
     unsigned grid = (unsigned)(per_head * A.heads);
