@@ -645,14 +645,26 @@ __global__ __launch_bounds__(kFusedThreads) void bwd_fused_kernel(BwdFastArgs A)
                     x_ring_load(it + 2);  // refills the slot just read
                     Raw8 r8;
                     r8.lo = make_uint4(v.x, v.y, v.z, v.w);
-                    unpack8(r8, w, (const T *)nullptr);
-                } else {
-                    unpack8(raw, w, (const T *)nullptr);
-                    if (it + 1 < mine) raw = load_row(pt.slot + (it + 1) * pt.nslots);
+                    raw = r8;
                 }
                 const float4 da = tab[tid], db = tab[512 + tid];
-                w[0] *= da.x; w[1] *= da.y; w[2] *= da.z; w[3] *= da.w;
-                w[4] *= db.x; w[5] *= db.y; w[6] *= db.z; w[7] *= db.w;
+                const float e0[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
+                if constexpr (std::is_same<T, __half>::value) {
+                    // w = E_0 * x as a fused multiply-add with a zero addend: the instruction takes the binary16 operand
+                    // as it is, which saves the eight conversions
+                    const uint32_t xw[4] = {raw.lo.x, raw.lo.y, raw.lo.z, raw.lo.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const __half2 h = *(const __half2 *)&xw[i];
+                        w[2 * i] = __builtin_fmaf(e0[2 * i], __low2float(h), 0.0f);
+                        w[2 * i + 1] = __builtin_fmaf(e0[2 * i + 1], __high2float(h), 0.0f);
+                    }
+                } else {
+                    unpack8(raw, w, (const T *)nullptr);
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) w[r] *= e0[r];
+                }
+                if (!kXRing && it + 1 < mine) raw = load_row(pt.slot + (it + 1) * pt.nslots);
                 n_forward<L::kParkFwd>(w, cn, tab, 1024 + tid);
                 lds_write_n2(xa, an, w);
             }
